@@ -1,0 +1,24 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+@pytest.fixture(scope="session")
+def tiny_weights():
+    from paper_2404_08698_amd import synth
+    return synth.make_weights(synth.TINY, seed=1)
+
+
+@pytest.fixture(scope="session")
+def tiny_bf16_weights():
+    from paper_2404_08698_amd import synth
+    return synth.make_weights(synth.TINY_BF16, seed=1)
