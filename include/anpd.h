@@ -1,0 +1,201 @@
+/*
+ * anpd.h - C ABI of the MI355X-native verification path of Adaptive N-gram
+ * Parallel Decoding (ANPD, arXiv 2404.08698).
+ *
+ * Two halves:
+ *   - a host-side adaptive multi-level N-gram table (the drafter), and
+ *   - the device-side verification step: one LLaMA-shaped forward over the
+ *     window [last accepted token, draft_1..draft_k] against the sequence's
+ *     paged KV cache, greedy argmax per row, longest-matching-prefix
+ *     acceptance, KV commit / rollback.
+ *
+ * Conventions
+ *   - Every call returns int32_t: >= 0 on success (a count where documented),
+ *     < 0 an ANPD_E_* code.  anpd_last_error() gives a thread-local message.
+ *     No exceptions, no abort, nothing printed.
+ *   - On error the object's state is unchanged (arguments are validated
+ *     before anything is launched), except ANPD_E_HIP after a launch.
+ *   - Handles are opaque, library-owned, and not thread-safe.  One sequence
+ *     per anpd_kv_t.
+ *   - "host" / "device" on a pointer says where the memory lives.  All
+ *     buffers are caller-owned; the library never frees or reallocates them.
+ *     Device memory (weights, KV page pool, workspace) is allocated by the
+ *     caller and passed as raw device pointers; the library itself allocates
+ *     only a few hundred bytes of pinned host memory per handle.
+ *   - A stream is a hipStream_t passed as void* (NULL = the default stream).
+ */
+#ifndef ANPD_H
+#define ANPD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    ANPD_OK = 0,
+    ANPD_E_INVAL = -1,         /* bad argument */
+    ANPD_E_RANGE = -2,         /* token id outside [0, vocab) */
+    ANPD_E_CAPACITY = -3,      /* KV capacity, window size or workspace exceeded */
+    ANPD_E_NOMEM = -4,         /* host allocation failed */
+    ANPD_E_HIP = -5,           /* a HIP call failed; see anpd_last_error() */
+    ANPD_E_UNIMPLEMENTED = -6
+};
+
+enum { ANPD_F32 = 0, ANPD_BF16 = 1 };               /* storage type of weights and of cached K/V */
+enum { ANPD_VERIFY = 0, ANPD_APPEND = 1 };          /* anpd_verify modes */
+enum { ANPD_GEMM_AUTO = 0, ANPD_GEMM_DOT = 1, ANPD_GEMM_MFMA = 2 };
+
+#define ANPD_MAX_WINDOW 32
+
+const char *anpd_last_error(void);
+
+/* ------------------------------------------------------------------------
+ * Host side: adaptive multi-level N-gram table.
+ *
+ * Paper, Section 3.1 "Token Level N-gram Module" (Initialize / Update /
+ * Query over token ids) and Section 3.2 "Multi-Level N-gram" (Algorithm 2:
+ * one table per level n in [n_min, n_max], queried from n_max downwards, the
+ * first level that answers wins).  The Memory is built from the live context
+ * only and grows with every committed token.
+ *
+ * Query semantics: for a context c of n-1 ids, the answer is the follower
+ * seen most often after c in the committed ids; among equally frequent
+ * followers the one seen most recently; NULL if c was never followed.
+ * ---------------------------------------------------------------------- */
+typedef struct anpd_ngram anpd_ngram_t;
+
+/* 2 <= n_min <= n_max <= 16, vocab >= 1.  *out receives the handle. */
+int32_t anpd_ngram_create(int32_t n_min, int32_t n_max, int32_t vocab, anpd_ngram_t **out);
+void anpd_ngram_destroy(anpd_ngram_t *t);
+/* Forget everything (new prompt => fresh Memory). */
+int32_t anpd_ngram_reset(anpd_ngram_t *t);
+/* Append n COMMITTED tokens (host array) to the context and count, at every
+ * level, the tuple each of them completes.  Initialize(prompt) is reset +
+ * update(prompt).  Drafts are never passed here: Algorithm 1 updates with
+ * accepted tokens only.  ANPD_E_RANGE (nothing appended) on a bad id.
+ * Returns the new context length. */
+int32_t anpd_ngram_update(anpd_ngram_t *t, const int32_t *tokens, int64_t n);
+/* Number of committed tokens. */
+int64_t anpd_ngram_length(const anpd_ngram_t *t);
+/* One multi-level query (Algorithm 2) on an explicit tail (host array of
+ * tail_len ids, most recent last).  Returns 1 and sets *out_token, *out_level
+ * on a hit, 0 on NULL. */
+int32_t anpd_ngram_query(const anpd_ngram_t *t, const int32_t *tail, int32_t tail_len,
+                         int32_t *out_token, int32_t *out_level);
+/* Drafting loop of Algorithm 1: up to max_k iterative multi-level queries,
+ * each on the committed context followed by the tokens drafted so far;
+ * stops at the first NULL.  out_tokens: host, max_k ints.  out_levels
+ * (nullable): host, max_k ints, the level that answered each draft.
+ * Returns the number drafted (0..max_k). */
+int32_t anpd_ngram_propose(const anpd_ngram_t *t, int32_t max_k, int32_t *out_tokens,
+                           int32_t *out_levels);
+
+/* ------------------------------------------------------------------------
+ * Device side: the verification step.
+ *
+ * Paper, Section 3.1 "Parallel Decoding", step 2 and Algorithm 1: the LLM
+ * scores the window in a single forward that re-uses the cached (k, v) of
+ * everything before it; draft j is accepted while it equals the prediction
+ * made after window row j-1; the first mismatch discards that draft and
+ * everything after it, and the LLM's own prediction at that row becomes the
+ * next token.  The decoder layer is the public LLaMA one (RMSNorm, rotary
+ * embedding in the half-split pairing, causal softmax attention, SwiGLU).
+ * ---------------------------------------------------------------------- */
+typedef struct anpd_model anpd_model_t;
+typedef struct anpd_kv anpd_kv_t;
+
+typedef struct {
+    int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
+    float rms_eps, rope_base;
+    int32_t dtype;          /* ANPD_F32 | ANPD_BF16: weights and cached K/V */
+    int32_t page_tokens;    /* tokens per KV page (16) */
+    int32_t max_window;     /* largest n_window, 1..ANPD_MAX_WINDOW */
+    int32_t max_positions;  /* largest KV capacity any anpd_kv_t of this model may have */
+    int32_t gemm_path;      /* ANPD_GEMM_*: AUTO = MFMA for bf16, dot products for f32 */
+} anpd_model_cfg;
+
+/* All pointers are DEVICE pointers to [out][in] row-major matrices (gains:
+ * [d_model]) in cfg.dtype, borrowed for the model's lifetime.  The per-layer
+ * members are HOST arrays of n_layers device pointers (read at create). */
+typedef struct {
+    const void *embed, *final_norm, *lm_head;   /* [vocab][d], [d], [vocab][d] */
+    const void *const *attn_norm, *const *wq, *const *wk, *const *wv, *const *wo;
+    const void *const *ffn_norm, *const *w_gate, *const *w_up, *const *w_down;
+} anpd_weights;
+
+/* Bytes of device workspace anpd_model_create needs for cfg (0 on bad cfg). */
+size_t anpd_model_workspace_bytes(const anpd_model_cfg *cfg);
+/* workspace: DEVICE, 256-byte aligned, >= anpd_model_workspace_bytes(cfg);
+ * used for activations and tables for the model's lifetime.  stream: used to
+ * initialise the tables; the call returns after that work has finished. */
+int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void *workspace,
+                          size_t workspace_bytes, void *stream, anpd_model_t **out);
+void anpd_model_destroy(anpd_model_t *m);
+
+/* Bytes of device pool a cache of max_tokens positions needs (0 on bad args). */
+size_t anpd_kv_pool_bytes(const anpd_model_t *m, int32_t max_tokens);
+/* pool: DEVICE, 256-byte aligned, >= anpd_kv_pool_bytes().  Pages hold
+ * page_tokens positions of every layer's K and V, laid out
+ * [page][layer][k|v][head][token in page][head_dim] in cfg.dtype; a page table
+ * maps logical to physical pages.  max_tokens <= cfg.max_positions. */
+int32_t anpd_kv_create(const anpd_model_t *m, void *pool, size_t pool_bytes, int32_t max_tokens,
+                       anpd_kv_t **out);
+void anpd_kv_destroy(anpd_kv_t *kv);
+/* Committed positions. */
+int32_t anpd_kv_length(const anpd_kv_t *kv);
+/* Explicit commit / rollback: 0 <= new_len <= max_tokens.  Growing is allowed
+ * (positions written by anpd_kv_write or by a previous window become live).
+ * Pages wholly beyond new_len go back to the cache's free list. */
+int32_t anpd_kv_truncate(anpd_kv_t *kv, int32_t new_len, void *stream);
+/* Order in which free physical pages are handed out: perm is a HOST array
+ * holding a permutation of 0..n_pages-1.  Only valid while the cache is empty. */
+int32_t anpd_kv_set_page_order(anpd_kv_t *kv, const int32_t *perm, int32_t n_pages);
+int32_t anpd_kv_num_pages(const anpd_kv_t *kv);
+/* Copy n positions of one layer between the cache and DEVICE float32 arrays
+ * k, v of shape [n][d_model] (values are converted to / from cfg.dtype).
+ * Writing allocates pages as needed and does not change the length.
+ * Synchronous with respect to the host. */
+int32_t anpd_kv_write(anpd_kv_t *kv, int32_t layer, int32_t pos0, int32_t n, const float *k,
+                      const float *v, void *stream);
+int32_t anpd_kv_read(const anpd_kv_t *kv, int32_t layer, int32_t pos0, int32_t n, float *k,
+                     float *v, void *stream);
+
+/* One verification step.
+ *   window (host, n_window ints): window[0] = last accepted token, not yet in
+ *   the cache; window[1..] = drafts.  1 <= n_window <= cfg.max_window.
+ *   ANPD_VERIFY: a = longest prefix with window[i+1] == argmax(logits[i]);
+ *     rows 0..a are committed (length += 1 + a), the rest rolled back;
+ *     *out_accepted = a, *out_next = argmax(logits[a]).
+ *   ANPD_APPEND: all rows are committed without comparing (chunked prefill,
+ *     teacher forcing); *out_accepted = n_window - 1, *out_next = argmax of
+ *     the last row.
+ *   out_predicts (nullable, host, n_window ints): argmax of every row.
+ *   out_logits (nullable, DEVICE, n_window * vocab floats): all logits.
+ *   argmax takes the lowest index among equal maxima.
+ * n_window = 1 is plain greedy decoding.  Blocks until the result is on the
+ * host (one stream synchronisation per step).
+ * Errors: ANPD_E_RANGE (bad token), ANPD_E_CAPACITY (length + n_window >
+ * max_tokens or n_window > max_window), ANPD_E_INVAL, ANPD_E_HIP. */
+int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32_t n_window,
+                    int32_t mode, int32_t *out_accepted, int32_t *out_next, int32_t *out_predicts,
+                    float *out_logits, void *stream);
+
+/* The dominant kernel on its own, for per-kernel parity and bandwidth
+ * measurement: Y[M][N] = X[M][K] * W[N][K]^T with fp32 accumulation.
+ *   X: DEVICE float32 [M][K]; W: DEVICE [N][K] in `dtype`; Y: DEVICE float32
+ *   [M][N]; workspace: DEVICE, >= anpd_linear_workspace_bytes(M, K) bytes
+ *   (holds the bf16 split of X for the MFMA path; may be NULL for DOT).
+ *   path: ANPD_GEMM_DOT (any dtype) or ANPD_GEMM_MFMA (bf16 only).
+ *   1 <= M <= ANPD_MAX_WINDOW, K % 8 == 0, N % 16 == 0.  Asynchronous on stream. */
+size_t anpd_linear_workspace_bytes(int32_t M, int32_t K);
+int32_t anpd_linear(const float *X, const void *W, float *Y, int32_t M, int32_t N, int32_t K,
+                    int32_t dtype, int32_t path, void *workspace, size_t workspace_bytes,
+                    void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ANPD_H */

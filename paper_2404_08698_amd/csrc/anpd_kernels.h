@@ -1,0 +1,589 @@
+// HIP kernels of the ANPD verification step for gfx950 (MI355X, CDNA4).
+//
+// The step is one LLaMA-shaped forward over a window of M = k+1 rows (the last
+// accepted token plus k drafts; paper Section 3.1, "Parallel Decoding", step 2)
+// against a paged KV cache, ending in greedy argmax per row and the
+// longest-matching-prefix acceptance of Algorithm 1.
+//
+// Every kernel computes a window row from that row's own data in an order
+// that does not depend on M, so the result for a position is bit-identical
+// whether it was verified in a 1-row or a 32-row window.  That is what makes
+// ANPD on this path reproduce greedy decoding token for token.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace anpd {
+
+typedef uint16_t bf16_t;  // bfloat16 storage
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int kWave = 64;
+constexpr int kAttnSplit = 64;        // keys per attention split (fixed: part of the numerics)
+constexpr float kMasked = -1.0e30f;   // score of a key a row must not see
+
+// ---------------------------------------------------------------- scalars
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// round to nearest, ties to even (finite inputs)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float load_f32(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float load_f32(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
+__device__ __forceinline__ void store_kv(float *p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void store_kv(bf16_t *p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+
+// eight consecutive elements, widened to float
+__device__ __forceinline__ void load8(const float *p, float (&o)[8])
+{
+    float4 a = *reinterpret_cast<const float4 *>(p);
+    float4 b = *reinterpret_cast<const float4 *>(p + 4);
+    o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+    o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16_t *p, float (&o)[8])
+{
+    uint4 r = *reinterpret_cast<const uint4 *>(p);
+    o[0] = __uint_as_float(r.x << 16); o[1] = __uint_as_float(r.x & 0xffff0000u);
+    o[2] = __uint_as_float(r.y << 16); o[3] = __uint_as_float(r.y & 0xffff0000u);
+    o[4] = __uint_as_float(r.z << 16); o[5] = __uint_as_float(r.z & 0xffff0000u);
+    o[6] = __uint_as_float(r.w << 16); o[7] = __uint_as_float(r.w & 0xffff0000u);
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+// ------------------------------------------------- split bf16 GEMM operand
+//
+// The MFMA GEMM takes its activation operand as two bf16 terms, v ~= hi + lo
+// (hi = bf16(v), lo = bf16(v - hi)), which keeps ~16 mantissa bits of the fp32
+// activation.  The operand buffer is a stack of 16-row bf16 tiles [tile][16][K].
+// Window class 8  (M <= 8):  one tile, rows m = hi, rows m + 8 = lo.
+// Window class 16 (M <= 16): tile 0 = hi, tile 1 = lo.
+// Window class 32 (M <= 32): tiles (0,1) = (hi,lo) of rows 0..15, (2,3) of rows 16..31.
+__host__ __device__ __forceinline__ int window_class(int M) { return M <= 8 ? 8 : (M <= 16 ? 16 : 32); }
+
+__device__ __forceinline__ void split_store(bf16_t *xs, int K, int cls, int m, int k, float v)
+{
+    bf16_t hi = f32_to_bf16(v);
+    bf16_t lo = f32_to_bf16(v - bf16_to_f32(hi));
+    size_t hi_row, lo_row;
+    if (cls == 8) {
+        hi_row = (size_t)m;
+        lo_row = (size_t)m + 8;
+    } else {
+        size_t t = (size_t)(m >> 4) * 2;
+        hi_row = t * 16 + (size_t)(m & 15);
+        lo_row = (t + 1) * 16 + (size_t)(m & 15);
+    }
+    xs[hi_row * (size_t)K + (size_t)k] = hi;
+    xs[lo_row * (size_t)K + (size_t)k] = lo;
+}
+
+// ------------------------------------------------------------------ embed
+
+// x[r][:] = E[token[r]][:]   grid: M blocks
+template <typename WT>
+__global__ __launch_bounds__(256) void embed_kernel(const WT *__restrict__ E, const int32_t *__restrict__ tok,
+                                                     float *__restrict__ x, int d)
+{
+    int r = blockIdx.x;
+    const WT *src = E + (size_t)tok[r] * d;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) x[(size_t)r * d + i] = load_f32(src, (size_t)i);
+}
+
+// --------------------------------------------------- residual add + RMSNorm
+
+// x[r] += y[r] (if y), then h[r] = x[r] * g / sqrt(mean(x[r]^2) + eps).
+// Writes h as fp32 and, if hs != nullptr, as the split bf16 operand.
+// grid: M blocks, one row each; the reduction order depends on d only.
+template <typename WT>
+__global__ __launch_bounds__(256) void addnorm_kernel(float *__restrict__ x, const float *__restrict__ y,
+                                                       const WT *__restrict__ g, float *__restrict__ h,
+                                                       bf16_t *__restrict__ hs, int d, float eps, int cls)
+{
+    __shared__ float part[4];
+    int r = blockIdx.x;
+    float *xr = x + (size_t)r * d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += 256) {
+        float v = xr[i];
+        if (y) {
+            v += y[(size_t)r * d + i];
+            xr[i] = v;
+        }
+        ss = fmaf(v, v, ss);
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float tot = ((part[0] + part[1]) + part[2]) + part[3];
+    float rinv = 1.0f / sqrtf(tot / (float)d + eps);
+    for (int i = threadIdx.x; i < d; i += 256) {
+        float v = xr[i] * load_f32(g, (size_t)i) * rinv;
+        h[(size_t)r * d + i] = v;
+        if (hs) split_store(hs, d, cls, r, i, v);
+    }
+}
+
+// --------------------------------------------------------------- GEMM (dot)
+//
+// Wavefront dot-product form of Y[M][N] = X[M][K] * W[N][K]^T.  A wave owns R
+// output columns; its 64 lanes stride over K in 8-element pieces (one 16-byte
+// load of bf16 weights per lane per row), multiply against the fp32 rows of X
+// and finish with a butterfly sum over the lanes.  Exact fp32 products, fp32
+// accumulation.  The weight matrix may be given as up to three row segments
+// (Wq|Wk|Wv or Wgate|Wup) of n_seg rows each, written side by side into Y.
+// grid: (nseg * n_seg) / (4 * R) blocks of 4 waves.
+template <typename WT, int R>
+__global__ __launch_bounds__(256) void gemm_dot_kernel(const float *__restrict__ X, int M, int K,
+                                                        const WT *__restrict__ W0, const WT *__restrict__ W1,
+                                                        const WT *__restrict__ W2, int n_seg, int n_total,
+                                                        float *__restrict__ Y, int ldy)
+{
+    const int lane = threadIdx.x & 63;
+    const int n0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * R;
+    if (n0 >= n_total) return;
+    const int seg = n0 / n_seg;
+    const WT *W = (seg == 0 ? W0 : (seg == 1 ? W1 : W2)) + (size_t)(n0 - seg * n_seg) * K;
+
+    for (int m0 = 0; m0 < M; m0 += 8) {
+        float acc[R][8];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int mm = 0; mm < 8; ++mm) acc[r][mm] = 0.f;
+
+        for (int k = lane * 8; k < K; k += 64 * 8) {
+            float w[R][8];
+#pragma unroll
+            for (int r = 0; r < R; ++r) load8(W + (size_t)r * K + k, w[r]);
+#pragma unroll
+            for (int mm = 0; mm < 8; ++mm) {
+                if (m0 + mm < M) {
+                    float xv[8];
+                    load8(X + (size_t)(m0 + mm) * K + k, xv);
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) acc[r][mm] = fmaf(xv[i], w[r][i], acc[r][mm]);
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int mm = 0; mm < 8; ++mm) {
+                float v = wave_sum(acc[r][mm]);
+                if (lane == 0 && m0 + mm < M) Y[(size_t)(m0 + mm) * ldy + n0 + r] = v;
+            }
+    }
+}
+
+// -------------------------------------------------------------- GEMM (MFMA)
+//
+// Matrix-core form for bf16 weights.  A block owns one 16-row tile of W (16
+// output columns of Y) and all of K; its waves take interleaved chunks of
+// kU 32-wide k-steps.  The weight tile is the A operand straight from global
+// memory: lane (row = lane % 16, kg = lane / 16) loads the 8 bf16 at
+// W[n0 + row][32 * ks + 8 * kg ..], exactly the layout
+// v_mfma_f32_16x16x32_bf16 wants, so weights go HBM -> VGPR -> MFMA with no
+// staging.  The B operand is the split activation tile (see split_store).
+// hi and lo products are accumulated separately and added once at the end,
+// after the per-wave partial tiles have been summed through LDS in wave order:
+// the arithmetic per output element is the same for every window class.
+// grid: (nseg * n_seg) / 16 blocks of NW waves (NW = blockDim.x / 64 <= 16).
+constexpr int kMfmaU = 4;
+
+template <int CLS>
+__global__ __launch_bounds__(1024) void gemm_mfma_kernel(const bf16_t *__restrict__ Xs, int M, int K,
+                                                          const bf16_t *__restrict__ W0,
+                                                          const bf16_t *__restrict__ W1,
+                                                          const bf16_t *__restrict__ W2, int n_seg,
+                                                          float *__restrict__ Y, int ldy)
+{
+    constexpr int NT = CLS / 8;  // activation tiles: 1, 2, 4
+    extern __shared__ float red[];  // [NW][NT][64][4]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int row = lane & 15, kg = lane >> 4;
+    const int n0 = blockIdx.x * 16;
+    const int seg = n0 / n_seg;
+    const bf16_t *W = (seg == 0 ? W0 : (seg == 1 ? W1 : W2)) + (size_t)(n0 - seg * n_seg + row) * K;
+    const bf16_t *Xr = Xs + (size_t)row * K;
+    const int nks = (K + 31) >> 5;
+
+    f32x4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    for (int ks0 = wave * kMfmaU; ks0 < nks; ks0 += nw * kMfmaU) {
+        uint4 a[kMfmaU], b[kMfmaU][NT];
+#pragma unroll
+        for (int u = 0; u < kMfmaU; ++u) {
+            int k = (ks0 + u) * 32 + kg * 8;
+            bool ok = k < K;
+            a[u] = ok ? *reinterpret_cast<const uint4 *>(W + k) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                b[u][t] = ok ? *reinterpret_cast<const uint4 *>(Xr + (size_t)t * 16 * K + k) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < kMfmaU; ++u)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[u]),
+                                                                 __builtin_bit_cast(bf16x8, b[u][t]), acc[t], 0, 0, 0);
+    }
+
+    // acc[t][i] = D[n0 + 4 * kg + i][slot = row] of this wave's share of K
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+        *reinterpret_cast<f32x4 *>(red + ((size_t)(wave * NT + t) * 64 + lane) * 4) = acc[t];
+    __syncthreads();
+    if (wave != 0) return;
+    f32x4 tot[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        tot[t] = *reinterpret_cast<const f32x4 *>(red + ((size_t)t * 64 + lane) * 4);
+        for (int w = 1; w < nw; ++w) tot[t] += *reinterpret_cast<const f32x4 *>(red + ((size_t)(w * NT + t) * 64 + lane) * 4);
+    }
+    const int ncol = n0 + 4 * kg;
+    if (CLS == 8) {
+        f32x4 lo;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lo[i] = __shfl_down(tot[0][i], 8, kWave);
+        if (row < 8 && row < M) {
+            f32x4 r = tot[0] + lo;
+            *reinterpret_cast<f32x4 *>(Y + (size_t)row * ldy + ncol) = r;
+        }
+    } else {
+#pragma unroll
+        for (int p = 0; p < NT / 2; ++p) {
+            int m = p * 16 + row;
+            if (m < M) {
+                f32x4 r = tot[2 * p] + tot[2 * p + 1];
+                *reinterpret_cast<f32x4 *>(Y + (size_t)m * ldy + ncol) = r;
+            }
+        }
+    }
+}
+
+// fp32 [M][K] -> split bf16 operand (used by the stand-alone linear entry point)
+__global__ __launch_bounds__(256) void split_kernel(const float *__restrict__ X, bf16_t *__restrict__ xs, int M, int K,
+                                                     int cls)
+{
+    int m = blockIdx.y;
+    int k = blockIdx.x * 256 + threadIdx.x;
+    if (m < M && k < K) split_store(xs, K, cls, m, k, X[(size_t)m * K + k]);
+}
+
+// ------------------------------------------------------- RoPE + KV write
+//
+// Page layout: [page][layer][k|v][head][token in page][head_dim].
+__device__ __forceinline__ size_t kv_offset(int page, int layer, int n_layers, int kv, int head, int n_heads,
+                                            int tok_in_page, int page_tokens, int head_dim)
+{
+    return ((((size_t)page * n_layers + layer) * 2 + kv) * n_heads + head) * ((size_t)page_tokens * head_dim) +
+           (size_t)tok_in_page * head_dim;
+}
+
+// Rotates q (in place, in the fused qkv buffer) and k by the row's absolute
+// position len + r, pair (i, i + head_dim/2) by angle pos * base^(-2i/head_dim)
+// (cos/sin from a table computed in double on the host), and writes k and v of
+// the row into the cache in the storage type.  grid: M blocks.
+template <typename KT>
+__global__ __launch_bounds__(256) void rope_kv_kernel(float *__restrict__ qkv, const float2 *__restrict__ rope_tab,
+                                                       KT *__restrict__ pool, const int32_t *__restrict__ page_table,
+                                                       const int32_t *__restrict__ len_ptr, int layer, int n_layers,
+                                                       int n_heads, int head_dim, int page_tokens)
+{
+    const int r = blockIdx.x, d = n_heads * head_dim, half = head_dim >> 1;
+    const int pos = *len_ptr + r;
+    const int page = page_table[pos / page_tokens], tip = pos % page_tokens;
+    float *q = qkv + (size_t)r * 3 * d, *k = q + d, *v = q + 2 * d;
+    for (int idx = threadIdx.x; idx < n_heads * half; idx += 256) {
+        int hd = idx / half, i = idx - hd * half;
+        float2 cs = rope_tab[(size_t)pos * half + i];
+        int e0 = hd * head_dim + i, e1 = e0 + half;
+        float qa = q[e0], qb = q[e1];
+        q[e0] = qa * cs.x - qb * cs.y;
+        q[e1] = qb * cs.x + qa * cs.y;
+        float ka = k[e0], kb = k[e1];
+        size_t ko = kv_offset(page, layer, n_layers, 0, hd, n_heads, tip, page_tokens, head_dim);
+        size_t vo = kv_offset(page, layer, n_layers, 1, hd, n_heads, tip, page_tokens, head_dim);
+        store_kv(pool, ko + i, ka * cs.x - kb * cs.y);
+        store_kv(pool, ko + i + half, kb * cs.x + ka * cs.y);
+        store_kv(pool, vo + i, v[e0]);
+        store_kv(pool, vo + i + half, v[e1]);
+    }
+}
+
+// ------------------------------------------------------------- attention
+//
+// Window-causal attention of the M query rows over the paged cache.  Keys are
+// cut into fixed splits of kAttnSplit absolute positions; block (head, split)
+// computes, for each row, the split's score maximum, sum of exponentials and
+// unnormalised weighted V sum; attn_combine_kernel merges the splits of a row
+// in increasing order.  Row r sees keys 0..len + r; keys it must not see get
+// weight exactly 0, so a row's numbers do not depend on M.
+// Lane layout: a key's head_dim elements are spread over DH/8 lanes (16 bytes
+// of bf16 each), so a wave reads 64*8 consecutive elements of the page.
+// part: [head][split][max_window][DH + 2] = (o[DH], max, denominator).
+// grid: (n_heads, n_splits), 4 waves.
+template <typename KT, int DH>
+__global__ __launch_bounds__(256) void attn_kernel(const float *__restrict__ qkv, const KT *__restrict__ pool,
+                                                    const int32_t *__restrict__ page_table,
+                                                    const int32_t *__restrict__ len_ptr, int M, int layer, int n_layers,
+                                                    int n_heads, int page_tokens, int max_window, int max_splits,
+                                                    float scale, float *__restrict__ part)
+{
+    constexpr int LPK = DH / 8;        // lanes per key
+    constexpr int KPG = 64 / LPK;      // keys per wave group
+    constexpr int NG = kAttnSplit / KPG;
+    __shared__ float sc[8][kAttnSplit];
+    __shared__ float stat[8][2];
+    __shared__ float red[4][8][DH];
+
+    const int head = blockIdx.x, split = blockIdx.y;
+    const int L = *len_ptr;
+    const int s0 = split * kAttnSplit;
+    if (s0 >= L + M) return;  // no key of this split exists for any row
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int ksub = lane / LPK, dg = lane % LPK;
+    const int d = n_heads * DH;
+
+    for (int m0 = 0; m0 < M; m0 += 8) {
+        // ---- scores
+        float qv[8][8];
+#pragma unroll
+        for (int mm = 0; mm < 8; ++mm) {
+            if (m0 + mm < M) {
+                load8(qkv + (size_t)(m0 + mm) * 3 * d + head * DH + dg * 8, qv[mm]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) qv[mm][i] = 0.f;
+            }
+        }
+        for (int g = wave; g < NG; g += 4) {
+            const int jl = g * KPG + ksub, j = s0 + jl;
+            const bool exists = j < L + M;
+            float kv[8];
+            if (exists) {
+                int page = page_table[j / page_tokens];
+                load8(pool + kv_offset(page, layer, n_layers, 0, head, n_heads, j % page_tokens, page_tokens, DH) + dg * 8, kv);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) kv[i] = 0.f;
+            }
+#pragma unroll
+            for (int mm = 0; mm < 8; ++mm) {
+                float p = 0.f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) p = fmaf(qv[mm][i], kv[i], p);
+#pragma unroll
+                for (int off = LPK / 2; off >= 1; off >>= 1) p += __shfl_xor(p, off, kWave);
+                if (dg == 0) sc[mm][jl] = (exists && m0 + mm < M && j <= L + m0 + mm) ? p * scale : kMasked;
+            }
+        }
+        __syncthreads();
+        // ---- per-row maximum, exponentials, denominator (one key per lane)
+        for (int mm = wave; mm < 8; mm += 4) {
+            float s = sc[mm][lane];
+            float mx = wave_max(s);
+            float p = (s > 0.5f * kMasked) ? expf(s - mx) : 0.f;
+            sc[mm][lane] = p;
+            float den = wave_sum(p);
+            if (lane == 0) { stat[mm][0] = mx; stat[mm][1] = den; }
+        }
+        __syncthreads();
+        // ---- weighted V
+        float acc[8][8];
+#pragma unroll
+        for (int mm = 0; mm < 8; ++mm)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[mm][i] = 0.f;
+        for (int g = wave; g < NG; g += 4) {
+            const int jl = g * KPG + ksub, j = s0 + jl;
+            if (j < L + M) {
+                float vv[8];
+                int page = page_table[j / page_tokens];
+                load8(pool + kv_offset(page, layer, n_layers, 1, head, n_heads, j % page_tokens, page_tokens, DH) + dg * 8, vv);
+#pragma unroll
+                for (int mm = 0; mm < 8; ++mm) {
+                    float p = sc[mm][jl];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) acc[mm][i] = fmaf(p, vv[i], acc[mm][i]);
+                }
+            }
+        }
+        // sum the KPG key streams of the wave (lanes that differ in ksub), then the waves in order
+#pragma unroll
+        for (int mm = 0; mm < 8; ++mm)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float v = acc[mm][i];
+#pragma unroll
+                for (int off = 32; off >= LPK; off >>= 1) v += __shfl_xor(v, off, kWave);
+                acc[mm][i] = v;
+            }
+        if (ksub == 0) {
+#pragma unroll
+            for (int mm = 0; mm < 8; ++mm)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) red[wave][mm][dg * 8 + i] = acc[mm][i];
+        }
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < 8 * DH; idx += 256) {
+            int mm = idx / DH, e = idx - mm * DH;
+            if (m0 + mm < M) {
+                float o = ((red[0][mm][e] + red[1][mm][e]) + red[2][mm][e]) + red[3][mm][e];
+                part[(((size_t)head * max_splits + split) * max_window + (m0 + mm)) * (DH + 2) + e] = o;
+            }
+        }
+        if (threadIdx.x < 8 && m0 + threadIdx.x < M) {
+            size_t base = (((size_t)head * max_splits + split) * max_window + (m0 + threadIdx.x)) * (DH + 2) + DH;
+            part[base] = stat[threadIdx.x][0];
+            part[base + 1] = stat[threadIdx.x][1];
+        }
+        __syncthreads();
+    }
+}
+
+// Merge the splits of (row, head) in increasing split order.  Row r has keys in
+// splits 0..(len + r) / kAttnSplit.  Writes att as fp32 and optionally as the
+// split bf16 operand of the output projection.  grid: (M, n_heads), DH threads.
+template <int DH>
+__global__ __launch_bounds__(DH) void attn_combine_kernel(const float *__restrict__ part,
+                                                           const int32_t *__restrict__ len_ptr, int n_heads,
+                                                           int max_window, int max_splits, float *__restrict__ att,
+                                                           bf16_t *__restrict__ atts, int cls)
+{
+    const int r = blockIdx.x, head = blockIdx.y, e = threadIdx.x;
+    const int ns = (*len_ptr + r) / kAttnSplit + 1;
+    const float *p = part + (((size_t)head * max_splits) * max_window + r) * (DH + 2);
+    const size_t stride = (size_t)max_window * (DH + 2);
+    float gm = kMasked;
+    for (int s = 0; s < ns; ++s) gm = fmaxf(gm, p[s * stride + DH]);
+    float o = 0.f, den = 0.f;
+    for (int s = 0; s < ns; ++s) {
+        float w = expf(p[s * stride + DH] - gm);
+        o = fmaf(w, p[s * stride + e], o);
+        den = fmaf(w, p[s * stride + DH + 1], den);
+    }
+    float v = o / den;
+    const int d = n_heads * DH;
+    att[(size_t)r * d + head * DH + e] = v;
+    if (atts) split_store(atts, d, cls, r, head * DH + e, v);
+}
+
+// ------------------------------------------------------------------ SwiGLU
+
+// a[r][i] = silu(gu[r][i]) * gu[r][F + i]    grid: (ceil(F/256), M)
+__global__ __launch_bounds__(256) void swiglu_kernel(const float *__restrict__ gu, float *__restrict__ a,
+                                                      bf16_t *__restrict__ as, int F, int cls)
+{
+    int r = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= F) return;
+    float g = gu[(size_t)r * 2 * F + i], u = gu[(size_t)r * 2 * F + F + i];
+    float v = g / (1.0f + expf(-g)) * u;
+    a[(size_t)r * F + i] = v;
+    if (as) split_store(as, F, cls, r, i, v);
+}
+
+// ------------------------------------------- argmax + acceptance + commit
+//
+// Block r finds argmax(logits[r]) (lowest index among equal maxima).  The last
+// block to finish applies Algorithm 1's accept rule: a = longest prefix with
+// window[i + 1] == pred[i]; next = pred[a]; the cache length advances by 1 + a
+// (rejected rows are simply left beyond the length and overwritten later).
+// result: [0] = a, [1] = next, [2..2+M) = pred.   grid: M blocks of 1024.
+__global__ __launch_bounds__(1024) void argmax_accept_kernel(const float *__restrict__ logits, int V, int M,
+                                                              const int32_t *__restrict__ window, int mode,
+                                                              int32_t *__restrict__ result, int32_t *__restrict__ len_ptr,
+                                                              uint32_t *__restrict__ counter)
+{
+    __shared__ float bv[16];
+    __shared__ int bi[16];
+    __shared__ bool last;
+    const int r = blockIdx.x;
+    const float *row = logits + (size_t)r * V;
+    float best = -INFINITY;
+    int besti = 0x7fffffff;
+    for (int i = threadIdx.x; i < V; i += 1024) {
+        float v = row[i];
+        if (v > best || besti == 0x7fffffff) { best = v; besti = i; }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        float ov = __shfl_xor(best, off, kWave);
+        int oi = __shfl_xor(besti, off, kWave);
+        if (ov > best || (ov == best && oi < besti)) { best = ov; besti = oi; }
+    }
+    if ((threadIdx.x & 63) == 0) { bv[threadIdx.x >> 6] = best; bi[threadIdx.x >> 6] = besti; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 16; ++w)
+            if (bv[w] > best || (bv[w] == best && bi[w] < besti)) { best = bv[w]; besti = bi[w]; }
+        result[2 + r] = besti;
+        __threadfence();
+        last = (atomicAdd(counter, 1u) == (uint32_t)(M - 1));
+    }
+    __syncthreads();
+    if (last && threadIdx.x == 0) {
+        __threadfence();
+        volatile int32_t *pred = result + 2;
+        int a = 0;
+        if (mode == 0) {
+            while (a < M - 1 && window[a + 1] == pred[a]) ++a;
+        } else {
+            a = M - 1;
+        }
+        result[0] = a;
+        result[1] = pred[a];
+        *len_ptr += 1 + a;
+        *counter = 0u;
+    }
+}
+
+// ----------------------------------------------------- cache import/export
+
+// Copies n positions of one layer between fp32 [n][d] arrays and the cache.
+template <typename KT, bool TO_CACHE>
+__global__ __launch_bounds__(256) void kv_copy_kernel(KT *__restrict__ pool, const int32_t *__restrict__ page_table,
+                                                       float *__restrict__ k, float *__restrict__ v, int pos0, int layer,
+                                                       int n_layers, int n_heads, int head_dim, int page_tokens)
+{
+    const int r = blockIdx.x, pos = pos0 + r, d = n_heads * head_dim;
+    const int page = page_table[pos / page_tokens], tip = pos % page_tokens;
+    for (int e = threadIdx.x; e < d; e += 256) {
+        int hd = e / head_dim, i = e - hd * head_dim;
+        size_t ko = kv_offset(page, layer, n_layers, 0, hd, n_heads, tip, page_tokens, head_dim) + i;
+        size_t vo = kv_offset(page, layer, n_layers, 1, hd, n_heads, tip, page_tokens, head_dim) + i;
+        if (TO_CACHE) {
+            store_kv(pool, ko, k[(size_t)r * d + e]);
+            store_kv(pool, vo, v[(size_t)r * d + e]);
+        } else {
+            k[(size_t)r * d + e] = load_f32(pool, ko);
+            v[(size_t)r * d + e] = load_f32(pool, vo);
+        }
+    }
+}
+
+}  // namespace anpd
