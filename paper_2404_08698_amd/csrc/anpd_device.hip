@@ -436,7 +436,7 @@ int32_t anpd_kv_truncate(anpd_kv_t *kv, int32_t new_len, void *stream)
 
 static int32_t kv_copy(anpd_kv *kv, int32_t layer, int32_t pos0, int32_t n, float *k, float *v, bool to_cache, void *stream)
 {
-    if (!kv || !k || !v) return fail(ANPD_E_INVAL, "anpd_kv_read/write: NULL argument");
+    if (!kv || ((!k || !v) && n != 0)) return fail(ANPD_E_INVAL, "anpd_kv_read/write: NULL argument");
     const anpd_model_cfg &c = kv->m->cfg;
     if (layer < 0 || layer >= c.n_layers || pos0 < 0 || n < 0 || pos0 + n > kv->max_tokens)
         return fail(ANPD_E_CAPACITY, "anpd_kv_read/write: layer %d, positions %d..%d out of range", layer, pos0, pos0 + n);
