@@ -46,7 +46,11 @@ enum {
 
 enum { ANPD_F32 = 0, ANPD_BF16 = 1 };               /* storage type of weights and of cached K/V */
 enum { ANPD_VERIFY = 0, ANPD_APPEND = 1 };          /* anpd_verify modes */
-enum { ANPD_GEMM_AUTO = 0, ANPD_GEMM_DOT = 1, ANPD_GEMM_MFMA = 2 };
+/* GEMM forms.  DOT: wavefront dot products on the caller's row-major weights (any dtype).
+ * MFMA: matrix cores on bf16 weights repacked into fragment order.  MFMA_STREAM (anpd_linear
+ * only) forces the MFMA form that streams the activation operand instead of holding it in
+ * registers; both MFMA forms give bit-identical results. */
+enum { ANPD_GEMM_AUTO = 0, ANPD_GEMM_DOT = 1, ANPD_GEMM_MFMA = 2, ANPD_GEMM_MFMA_STREAM = 3 };
 
 #define ANPD_MAX_WINDOW 32
 
@@ -126,7 +130,10 @@ typedef struct {
     const void *const *ffn_norm, *const *w_gate, *const *w_up, *const *w_down;
 } anpd_weights;
 
-/* Bytes of device workspace anpd_model_create needs for cfg (0 on bad cfg). */
+/* Bytes of device workspace anpd_model_create needs for cfg (0 on bad cfg).  With the MFMA
+ * path this includes a repacked copy of every matrix (about the size of the model): after
+ * anpd_model_create returns, only `embed` and the norm gains are still read from the
+ * caller's tensors. */
 size_t anpd_model_workspace_bytes(const anpd_model_cfg *cfg);
 /* workspace: DEVICE, 256-byte aligned, >= anpd_model_workspace_bytes(cfg);
  * used for activations and tables for the model's lifetime.  stream: used to
@@ -183,14 +190,36 @@ int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32
                     int32_t mode, int32_t *out_accepted, int32_t *out_next, int32_t *out_predicts,
                     float *out_logits, void *stream);
 
+/* Per-kernel timing of anpd_verify with events recorded on the launch stream
+ * between kernel groups.  While enabled, every step accumulates the elapsed
+ * milliseconds and the number of timed intervals per category; enabling or
+ * disabling resets the sums.  out_ms, out_launches: host arrays of
+ * ANPD_PROF_NCAT entries; *out_steps: steps accumulated. */
+enum {
+    ANPD_PROF_GEMM_QKV = 0, ANPD_PROF_GEMM_O, ANPD_PROF_GEMM_GATE_UP, ANPD_PROF_GEMM_DOWN,
+    ANPD_PROF_GEMM_LM_HEAD, ANPD_PROF_ATTN, ANPD_PROF_OTHER, ANPD_PROF_NCAT
+};
+int32_t anpd_model_profile(anpd_model_t *m, int32_t enable);
+int32_t anpd_model_profile_read(const anpd_model_t *m, double *out_ms, int64_t *out_launches,
+                                int64_t *out_steps);
+
 /* The dominant kernel on its own, for per-kernel parity and bandwidth
  * measurement: Y[M][N] = X[M][K] * W[N][K]^T with fp32 accumulation.
- *   X: DEVICE float32 [M][K]; W: DEVICE [N][K] in `dtype`; Y: DEVICE float32
- *   [M][N]; workspace: DEVICE, >= anpd_linear_workspace_bytes(M, K) bytes
- *   (holds the bf16 split of X for the MFMA path; may be NULL for DOT).
- *   path: ANPD_GEMM_DOT (any dtype) or ANPD_GEMM_MFMA (bf16 only).
+ *   X: DEVICE float32 [M][K]; Y: DEVICE float32 [M][N];
+ *   path ANPD_GEMM_DOT: W is DEVICE [N][K] row-major in `dtype`; workspace may be NULL.
+ *   path ANPD_GEMM_MFMA / ANPD_GEMM_MFMA_STREAM (bf16 only): W is the DEVICE buffer
+ *   written by anpd_pack_weights for the same N and K; workspace: DEVICE,
+ *   >= anpd_linear_workspace_bytes(M, K) bytes (holds the split bf16 form of X).
  *   1 <= M <= ANPD_MAX_WINDOW, K % 8 == 0, N % 16 == 0.  Asynchronous on stream. */
 size_t anpd_linear_workspace_bytes(int32_t M, int32_t K);
+/* Bytes of the repacked form of an [N][K] bf16 matrix (0 on bad N, K). */
+size_t anpd_packed_bytes(int32_t N, int32_t K);
+/* Repack W (DEVICE, [N][K] row-major bf16) into MFMA-fragment order:
+ * packed[tile][k-step][lane][8], lane = 16 * kg + r holding
+ * W[16 * tile + r][32 * ks + 8 * kg .. + 8], K padded with zeros to a multiple of 32.
+ * Asynchronous on stream. */
+int32_t anpd_pack_weights(const void *W, int32_t N, int32_t K, void *packed, size_t packed_bytes,
+                          void *stream);
 int32_t anpd_linear(const float *X, const void *W, float *Y, int32_t M, int32_t N, int32_t K,
                     int32_t dtype, int32_t path, void *workspace, size_t workspace_bytes,
                     void *stream);

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "libanpd.so")
 OK, E_INVAL, E_RANGE, E_CAPACITY, E_NOMEM, E_HIP, E_UNIMPLEMENTED = 0, -1, -2, -3, -4, -5, -6
 F32, BF16 = 0, 1
 VERIFY, APPEND = 0, 1
-GEMM_AUTO, GEMM_DOT, GEMM_MFMA = 0, 1, 2
+GEMM_AUTO, GEMM_DOT, GEMM_MFMA, GEMM_MFMA_STREAM = 0, 1, 2, 3
 MAX_WINDOW = 32
 
 _PER_LAYER = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
@@ -31,7 +31,9 @@ EXPORTS = (
     "anpd_kv_pool_bytes", "anpd_kv_create", "anpd_kv_destroy", "anpd_kv_length", "anpd_kv_truncate",
     "anpd_kv_set_page_order", "anpd_kv_num_pages", "anpd_kv_write", "anpd_kv_read",
     "anpd_verify", "anpd_linear_workspace_bytes", "anpd_linear",
+    "anpd_model_profile", "anpd_model_profile_read", "anpd_packed_bytes", "anpd_pack_weights",
 )
+PROF_CATEGORIES = ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "attn", "other")
 
 
 class AnpdError(RuntimeError):
@@ -112,6 +114,14 @@ def lib():
     L.anpd_linear_workspace_bytes.argtypes = [C.c_int32, C.c_int32]
     L.anpd_linear.restype = C.c_int32
     L.anpd_linear.argtypes = [vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, C.c_size_t, vp]
+    L.anpd_packed_bytes.restype = C.c_size_t
+    L.anpd_packed_bytes.argtypes = [C.c_int32, C.c_int32]
+    L.anpd_pack_weights.restype = C.c_int32
+    L.anpd_pack_weights.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_size_t, vp]
+    L.anpd_model_profile.restype = C.c_int32
+    L.anpd_model_profile.argtypes = [vp, C.c_int32]
+    L.anpd_model_profile_read.restype = C.c_int32
+    L.anpd_model_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     _lib = L
     return L
 
@@ -215,6 +225,16 @@ class Model:
             lib().anpd_model_destroy(self._h)
             self._h = None
 
+    def profile(self, enable: bool) -> None:
+        _check(lib().anpd_model_profile(self._h, 1 if enable else 0))
+
+    def profile_read(self) -> Dict[str, object]:
+        n = len(PROF_CATEGORIES)
+        ms, cnt, steps = (C.c_double * n)(), (C.c_int64 * n)(), C.c_int64(0)
+        _check(lib().anpd_model_profile_read(self._h, ms, cnt, C.byref(steps)))
+        return {"steps": steps.value, "ms": dict(zip(PROF_CATEGORIES, list(ms))),
+                "intervals": dict(zip(PROF_CATEGORIES, list(cnt)))}
+
     __del__ = close
 
 
@@ -288,17 +308,40 @@ def verify(model: Model, kv: KVCache, window: Sequence[int], mode: int = VERIFY,
     return acc.value, nxt.value
 
 
-def linear(X, W, path: int, stream=None):
-    """anpd_linear: Y = X @ W.T.  X: CUDA float32 [M][K]; W: CUDA [N][K] float32 or bfloat16."""
+def pack_weights(W, stream=None):
+    """anpd_pack_weights: bf16 CUDA [N][K] -> fragment-order buffer (uint8 tensor)."""
+    import torch
+    N, K = W.shape
+    assert W.is_cuda and W.dtype == torch.bfloat16 and W.is_contiguous()
+    nb = lib().anpd_packed_bytes(N, K)
+    if nb == 0:
+        _check(E_INVAL)
+    out = torch.empty(nb, dtype=torch.uint8, device=W.device)
+    _check(lib().anpd_pack_weights(W.data_ptr(), N, K, out.data_ptr(), nb, _stream_ptr(stream)))
+    return out
+
+
+def linear(X, W, path: int, stream=None, packed=None, Y=None, workspace=None):
+    """anpd_linear: Y = X @ W.T.  X: CUDA float32 [M][K]; W: CUDA [N][K] float32 or bfloat16.
+    For the MFMA paths the weights are repacked first unless ``packed`` (from pack_weights) is given."""
     import torch
     M, K = X.shape
     N = W.shape[0]
     assert X.is_cuda and X.dtype == torch.float32 and X.is_contiguous() and W.is_contiguous() and W.shape[1] == K
     dtype = BF16 if W.dtype == torch.bfloat16 else F32
-    Y = torch.empty(M, N, dtype=torch.float32, device=X.device)
+    if Y is None:
+        Y = torch.empty(M, N, dtype=torch.float32, device=X.device)
     nb = lib().anpd_linear_workspace_bytes(M, K)
-    ws = torch.empty(max(nb, 256), dtype=torch.uint8, device=X.device)
-    _check(lib().anpd_linear(X.data_ptr(), W.data_ptr(), Y.data_ptr(), M, N, K, dtype, path, ws.data_ptr(), nb,
+    ws = workspace if workspace is not None else torch.empty(max(nb, 256), dtype=torch.uint8, device=X.device)
+    wptr = W.data_ptr()
+    if path in (GEMM_MFMA, GEMM_MFMA_STREAM):
+        if dtype != BF16:
+            _check(lib().anpd_linear(X.data_ptr(), wptr, Y.data_ptr(), M, N, K, dtype, path, ws.data_ptr(), nb,
+                                     _stream_ptr(stream)))
+        if packed is None:
+            packed = pack_weights(W, stream)
+        wptr = packed.data_ptr()
+    _check(lib().anpd_linear(X.data_ptr(), wptr, Y.data_ptr(), M, N, K, dtype, path, ws.data_ptr(), nb,
                              _stream_ptr(stream)))
     return Y
 

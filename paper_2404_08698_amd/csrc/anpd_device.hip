@@ -14,6 +14,7 @@
 
 #include "anpd_common.h"
 #include "anpd_kernels.h"
+#include "anpd_fast.h"
 
 using namespace anpd;
 
@@ -28,9 +29,19 @@ namespace {
 size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct Layout {  // byte offsets into the model workspace
-    size_t rope_tab, tok, result, counter, x, h, y, qkv, att, gu, a, logits, hs, atts, as, part, total;
+    size_t rope_tab, tok, result, counter, x, h, y, qkv, att, gu, a, logits, part;
+    // fast path: packed operands, partial sums of squares, packed weights
+    size_t xp_d, xp_att, xp_f, ssp_a, ssp_b, wp_lm, total;
+    std::vector<size_t> wp_qkv, wp_o, wp_gu, wp_down;
     int max_splits;
 };
+
+bool wants_mfma(const anpd_model_cfg *c)
+{
+    return c->gemm_path == ANPD_GEMM_MFMA || (c->gemm_path == ANPD_GEMM_AUTO && c->dtype == ANPD_BF16);
+}
+
+size_t packed_bytes(size_t n_tiles, int K) { return n_tiles * (size_t)((K + 31) / 32) * 1024; }
 
 bool cfg_ok(const anpd_model_cfg *c, const char **why)
 {
@@ -55,7 +66,6 @@ Layout make_layout(const anpd_model_cfg *c)
 {
     Layout L;
     const size_t MW = (size_t)c->max_window, d = (size_t)c->d_model, F = (size_t)c->d_ffn, V = (size_t)c->vocab;
-    const size_t tiles = 64;  // split operand: up to 4 tiles of 16 rows
     L.max_splits = (c->max_positions + kAttnSplit - 1) / kAttnSplit + 1;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
@@ -71,10 +81,22 @@ Layout make_layout(const anpd_model_cfg *c)
     L.gu = take(MW * 2 * F * 4);
     L.a = take(MW * F * 4);
     L.logits = take(MW * V * 4);
-    L.hs = take(tiles * d * 2);
-    L.atts = take(tiles * d * 2);
-    L.as = take(tiles * F * 2);
     L.part = take((size_t)c->n_heads * L.max_splits * MW * (c->head_dim + 2) * 4);
+    L.xp_d = L.xp_att = L.xp_f = L.ssp_a = L.ssp_b = L.wp_lm = 0;
+    if (wants_mfma(c)) {
+        L.xp_d = take(((d + 31) / 32) * 4 * 1024);
+        L.xp_att = take(((d + 31) / 32) * 4 * 1024);
+        L.xp_f = take(((F + 31) / 32) * 4 * 1024);
+        L.ssp_a = take((d / 16) * 32 * 4);
+        L.ssp_b = take((d / 16) * 32 * 4);
+        L.wp_lm = take(packed_bytes(V / 16, (int)d));
+        for (int l = 0; l < c->n_layers; ++l) {
+            L.wp_qkv.push_back(take(packed_bytes(3 * d / 16, (int)d)));
+            L.wp_o.push_back(take(packed_bytes(d / 16, (int)d)));
+            L.wp_gu.push_back(take(packed_bytes(F / 8, (int)d)));
+            L.wp_down.push_back(take(packed_bytes(d / 16, (int)F)));
+        }
+    }
     L.total = o;
     return L;
 }
@@ -86,9 +108,18 @@ struct anpd_model {
     Layout lay;
     char *ws;
     bool mfma;
+    int n_cu;
     const void *embed, *final_norm, *lm_head;
     std::vector<const void *> attn_norm, wq, wk, wv, wo, ffn_norm, w_gate, w_up, w_down;
     int32_t *pin;  // pinned host staging: [0..32) window, [32..66) result
+    // optional per-kernel timing with events on the launch stream
+    bool prof;
+    std::vector<hipEvent_t> ev;
+    std::vector<int> ev_cat;
+    int ev_used;
+    double prof_ms[ANPD_PROF_NCAT];
+    int64_t prof_launches[ANPD_PROF_NCAT];
+    int64_t prof_steps;
 };
 
 struct anpd_kv {
@@ -129,35 +160,40 @@ int32_t launch_gemm_dot(const float *X, int M, int K, const void *W0, const void
     return ANPD_OK;
 }
 
-int32_t launch_gemm_mfma(const bf16_t *Xs, int M, int K, const void *W0, const void *W1, const void *W2, int nseg,
-                         int n_seg, float *Y, int ldy, hipStream_t st)
+// ---- fast path: packed MFMA GEMMs ---------------------------------------------
+
+template <int EPI>
+int32_t launch_fast(FastArgs &a, int n_cu, bool force_stream, hipStream_t st)
 {
-    const int cls = window_class(M);
-    const int tiles = nseg * n_seg / 16;
-    // More waves per block when there are few blocks, so every SIMD still has loads in flight.
-    // The wave count fixes the summation order, so it may depend on the matrix shape only,
-    // never on the window size.
-    int nw = tiles >= 1024 ? 4 : (tiles >= 512 ? 8 : 16);
-    const int nks = (K + 31) / 32;
-    while (nw > 1 && (nw - 1) * kMfmaU >= nks) nw >>= 1;
-    dim3 grid((unsigned)tiles), block((unsigned)nw * 64);
-    size_t smem = (size_t)nw * (cls / 8) * 64 * 4 * sizeof(float);
-    const bf16_t *w0 = (const bf16_t *)W0, *w1 = (const bf16_t *)W1, *w2 = (const bf16_t *)W2;
-    if (cls == 8)
-        hipLaunchKernelGGL((gemm_mfma_kernel<8>), grid, block, smem, st, Xs, M, K, w0, w1, w2, n_seg, Y, ldy);
-    else if (cls == 16)
-        hipLaunchKernelGGL((gemm_mfma_kernel<16>), grid, block, smem, st, Xs, M, K, w0, w1, w2, n_seg, Y, ldy);
-    else
-        hipLaunchKernelGGL((gemm_mfma_kernel<32>), grid, block, smem, st, Xs, M, K, w0, w1, w2, n_seg, Y, ldy);
+    const int kpw = (a.nks + kFastWaves - 1) / kFastWaves;
+    if (a.cls == 8 && kpw <= 10 && !force_stream) {
+        dim3 grid((unsigned)(a.n_tiles < n_cu ? a.n_tiles : n_cu)), block(kFastWaves * 64);
+        if (kpw <= 1) hipLaunchKernelGGL((gemm_xs_kernel<1, EPI>), grid, block, 0, st, a);
+        else if (kpw <= 2) hipLaunchKernelGGL((gemm_xs_kernel<2, EPI>), grid, block, 0, st, a);
+        else if (kpw <= 4) hipLaunchKernelGGL((gemm_xs_kernel<4, EPI>), grid, block, 0, st, a);
+        else if (kpw <= 8) hipLaunchKernelGGL((gemm_xs_kernel<8, EPI>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((gemm_xs_kernel<10, EPI>), grid, block, 0, st, a);
+    } else {
+        dim3 grid((unsigned)a.n_tiles), block(kFastWaves * 64);
+        const int nt = a.cls / 8;
+        size_t smem = (size_t)kFastWaves * nt * 256 * sizeof(float);
+        if (nt == 1) hipLaunchKernelGGL((gemm_stream_kernel<1, EPI>), grid, block, smem, st, a);
+        else if (nt == 2) hipLaunchKernelGGL((gemm_stream_kernel<2, EPI>), grid, block, smem, st, a);
+        else hipLaunchKernelGGL((gemm_stream_kernel<4, EPI>), grid, block, smem, st, a);
+    }
     HIP_TRY(hipGetLastError());
     return ANPD_OK;
 }
 
-int32_t gemm(const anpd_model *m, const float *X, const bf16_t *Xs, int M, int K, const void *W0, const void *W1,
-             const void *W2, int nseg, int n_seg, float *Y, int ldy, hipStream_t st)
+int32_t launch_pack(const void *s0, const void *s1, const void *s2, void *dst, int mode, int n_tiles, int K, int d,
+                    int head_dim, hipStream_t st)
 {
-    if (m->mfma) return launch_gemm_mfma(Xs, M, K, W0, W1, W2, nseg, n_seg, Y, ldy, st);
-    return launch_gemm_dot(X, M, K, W0, W1, W2, nseg, n_seg, Y, ldy, m->cfg.dtype, st);
+    const int nks = (K + 31) / 32;
+    size_t total = (size_t)n_tiles * nks * 64;
+    hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t *)s0,
+                       (const bf16_t *)s1, (const bf16_t *)s2, (uint4 *)dst, mode, n_tiles, K, nks, d, head_dim);
+    HIP_TRY(hipGetLastError());
+    return ANPD_OK;
 }
 
 // ---- cache pages ---------------------------------------------------------------
@@ -199,20 +235,31 @@ void release_pages(anpd_kv *kv, int32_t len)
     }
 }
 
+// Timing mark: an event after the launches of category `cat` (-1 = start of the step).
+inline void mark(anpd_model *m, int cat, hipStream_t st)
+{
+    if (!m->prof) return;
+    if (m->ev_used == (int)m->ev.size()) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return;
+        m->ev.push_back(e);
+        m->ev_cat.push_back(cat);
+    }
+    m->ev_cat[(size_t)m->ev_used] = cat;
+    (void)hipEventRecord(m->ev[(size_t)m->ev_used], st);
+    m->ev_used += 1;
+}
+
 template <typename KT>
-int32_t run_step(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t st)
+int32_t run_step_generic(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t st)
 {
     const anpd_model_cfg &c = m->cfg;
     const Layout &L = m->lay;
     char *ws = m->ws;
     const int d = c.d_model, F = c.d_ffn, V = c.vocab, H = c.n_heads, dh = c.head_dim;
-    const int cls = window_class(M);
     float *x = (float *)(ws + L.x), *h = (float *)(ws + L.h), *y = (float *)(ws + L.y);
     float *qkv = (float *)(ws + L.qkv), *att = (float *)(ws + L.att), *gu = (float *)(ws + L.gu);
     float *a = (float *)(ws + L.a), *logits = (float *)(ws + L.logits), *part = (float *)(ws + L.part);
-    bf16_t *hs = m->mfma ? (bf16_t *)(ws + L.hs) : nullptr;
-    bf16_t *atts = m->mfma ? (bf16_t *)(ws + L.atts) : nullptr;
-    bf16_t *as = m->mfma ? (bf16_t *)(ws + L.as) : nullptr;
     const float2 *rope = (const float2 *)(ws + L.rope_tab);
     const int32_t *tok = (const int32_t *)(ws + L.tok);
     int32_t *result = (int32_t *)(ws + L.result);
@@ -222,36 +269,179 @@ int32_t run_step(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t st)
     const int n_splits = (kv->len + M + kAttnSplit - 1) / kAttnSplit;
     int32_t rc;
 
+    m->ev_used = 0;
+    mark(m, -1, st);
     hipLaunchKernelGGL((embed_kernel<KT>), dim3(M), dim3(256), 0, st, (const KT *)m->embed, tok, x, d);
     for (int l = 0; l < c.n_layers; ++l) {
         hipLaunchKernelGGL((addnorm_kernel<KT>), dim3(M), dim3(256), 0, st, x, l == 0 ? (const float *)nullptr : y,
-                           (const KT *)m->attn_norm[l], h, hs, d, c.rms_eps, cls);
-        if ((rc = gemm(m, h, hs, M, d, m->wq[l], m->wk[l], m->wv[l], 3, d, qkv, 3 * d, st)) != ANPD_OK) return rc;
+                           (const KT *)m->attn_norm[l], h, d, c.rms_eps);
+        mark(m, ANPD_PROF_OTHER, st);
+        if ((rc = launch_gemm_dot(h, M, d, m->wq[l], m->wk[l], m->wv[l], 3, d, qkv, 3 * d, c.dtype, st)) != ANPD_OK) return rc;
+        mark(m, ANPD_PROF_GEMM_QKV, st);
         hipLaunchKernelGGL((rope_kv_kernel<KT>), dim3(M), dim3(256), 0, st, qkv, rope, pool, kv->d_table, kv->d_len, l,
                            c.n_layers, H, dh, c.page_tokens);
+        mark(m, ANPD_PROF_OTHER, st);
         if (dh == 128) {
-            hipLaunchKernelGGL((attn_kernel<KT, 128>), dim3(H, n_splits), dim3(256), 0, st, qkv, pool, kv->d_table,
+            hipLaunchKernelGGL((attn_kernel<KT, 128>), dim3(H, n_splits), dim3(256), 0, st, qkv, 3 * d, pool, kv->d_table,
                                kv->d_len, M, l, c.n_layers, H, c.page_tokens, c.max_window, L.max_splits, scale, part);
             hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(M, H), dim3(128), 0, st, part, kv->d_len, H,
-                               c.max_window, L.max_splits, att, atts, cls);
+                               c.max_window, L.max_splits, att, (bf16_t *)nullptr, 8);
         } else {
-            hipLaunchKernelGGL((attn_kernel<KT, 64>), dim3(H, n_splits), dim3(256), 0, st, qkv, pool, kv->d_table,
+            hipLaunchKernelGGL((attn_kernel<KT, 64>), dim3(H, n_splits), dim3(256), 0, st, qkv, 3 * d, pool, kv->d_table,
                                kv->d_len, M, l, c.n_layers, H, c.page_tokens, c.max_window, L.max_splits, scale, part);
             hipLaunchKernelGGL((attn_combine_kernel<64>), dim3(M, H), dim3(64), 0, st, part, kv->d_len, H, c.max_window,
-                               L.max_splits, att, atts, cls);
+                               L.max_splits, att, (bf16_t *)nullptr, 8);
         }
-        if ((rc = gemm(m, att, atts, M, d, m->wo[l], nullptr, nullptr, 1, d, y, d, st)) != ANPD_OK) return rc;
-        hipLaunchKernelGGL((addnorm_kernel<KT>), dim3(M), dim3(256), 0, st, x, y, (const KT *)m->ffn_norm[l], h, hs, d,
-                           c.rms_eps, cls);
-        if ((rc = gemm(m, h, hs, M, d, m->w_gate[l], m->w_up[l], nullptr, 2, F, gu, 2 * F, st)) != ANPD_OK) return rc;
-        hipLaunchKernelGGL(swiglu_kernel, dim3((F + 255) / 256, M), dim3(256), 0, st, gu, a, as, F, cls);
-        if ((rc = gemm(m, a, as, M, F, m->w_down[l], nullptr, nullptr, 1, d, y, d, st)) != ANPD_OK) return rc;
+        mark(m, ANPD_PROF_ATTN, st);
+        if ((rc = launch_gemm_dot(att, M, d, m->wo[l], nullptr, nullptr, 1, d, y, d, c.dtype, st)) != ANPD_OK) return rc;
+        mark(m, ANPD_PROF_GEMM_O, st);
+        hipLaunchKernelGGL((addnorm_kernel<KT>), dim3(M), dim3(256), 0, st, x, y, (const KT *)m->ffn_norm[l], h, d,
+                           c.rms_eps);
+        mark(m, ANPD_PROF_OTHER, st);
+        if ((rc = launch_gemm_dot(h, M, d, m->w_gate[l], m->w_up[l], nullptr, 2, F, gu, 2 * F, c.dtype, st)) != ANPD_OK) return rc;
+        mark(m, ANPD_PROF_GEMM_GATE_UP, st);
+        hipLaunchKernelGGL(swiglu_kernel, dim3((F + 255) / 256, M), dim3(256), 0, st, gu, a, F);
+        mark(m, ANPD_PROF_OTHER, st);
+        if ((rc = launch_gemm_dot(a, M, F, m->w_down[l], nullptr, nullptr, 1, d, y, d, c.dtype, st)) != ANPD_OK) return rc;
+        mark(m, ANPD_PROF_GEMM_DOWN, st);
     }
-    hipLaunchKernelGGL((addnorm_kernel<KT>), dim3(M), dim3(256), 0, st, x, y, (const KT *)m->final_norm, h, hs, d,
-                       c.rms_eps, cls);
-    if ((rc = gemm(m, h, hs, M, d, m->lm_head, nullptr, nullptr, 1, V, logits, V, st)) != ANPD_OK) return rc;
+    hipLaunchKernelGGL((addnorm_kernel<KT>), dim3(M), dim3(256), 0, st, x, y, (const KT *)m->final_norm, h, d,
+                       c.rms_eps);
+    mark(m, ANPD_PROF_OTHER, st);
+    if ((rc = launch_gemm_dot(h, M, d, m->lm_head, nullptr, nullptr, 1, V, logits, V, c.dtype, st)) != ANPD_OK) return rc;
+    mark(m, ANPD_PROF_GEMM_LM_HEAD, st);
     hipLaunchKernelGGL(argmax_accept_kernel, dim3(M), dim3(1024), 0, st, logits, V, M, tok, mode, result, kv->d_len,
                        counter);
+    mark(m, ANPD_PROF_OTHER, st);
+    HIP_TRY(hipGetLastError());
+    return ANPD_OK;
+}
+
+// The fused bf16 step: per layer QKV(+norm, RoPE, cache write) -> attention -> combine -> O(+residual)
+// -> gate/up(+norm, SwiGLU) -> down(+residual); then LM head(+norm) -> argmax / accept.
+int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t st)
+{
+    const anpd_model_cfg &c = m->cfg;
+    const Layout &L = m->lay;
+    char *ws = m->ws;
+    const int d = c.d_model, F = c.d_ffn, V = c.vocab, H = c.n_heads, dh = c.head_dim;
+    const int cls = window_class(M);
+    float *x = (float *)(ws + L.x), *q = (float *)(ws + L.qkv), *att = (float *)(ws + L.att);
+    float *logits = (float *)(ws + L.logits), *part = (float *)(ws + L.part);
+    bf16_t *xp_d = (bf16_t *)(ws + L.xp_d), *xp_att = (bf16_t *)(ws + L.xp_att), *xp_f = (bf16_t *)(ws + L.xp_f);
+    float *ssp_a = (float *)(ws + L.ssp_a), *ssp_b = (float *)(ws + L.ssp_b);
+    const int32_t *tok = (const int32_t *)(ws + L.tok);
+    int32_t *result = (int32_t *)(ws + L.result);
+    uint32_t *counter = (uint32_t *)(ws + L.counter);
+    const float scale = 1.0f / sqrtf((float)dh);
+    const int n_splits = (kv->len + M + kAttnSplit - 1) / kAttnSplit;
+    const int nks_d = (d + 31) / 32, nks_f = (F + 31) / 32;
+    int32_t rc;
+
+    FastArgs base;
+    std::memset(&base, 0, sizeof(base));
+    base.M = M;
+    base.cls = cls;
+    base.inv_d = 1.0f / (float)d;
+    base.eps = c.rms_eps;
+    base.n_ss = d / 16;
+    base.d = d;
+    base.x = x;
+    base.pool = (bf16_t *)kv->pool;
+    base.page_table = kv->d_table;
+    base.len_ptr = kv->d_len;
+    base.rope = (const float2 *)(ws + L.rope_tab);
+    base.n_layers = c.n_layers;
+    base.n_heads = H;
+    base.head_dim = dh;
+    base.page_tokens = c.page_tokens;
+
+    m->ev_used = 0;
+    mark(m, -1, st);
+    {
+        FastArgs a = base;
+        a.gain = (const bf16_t *)m->attn_norm[0];
+        a.xp_next = xp_d;
+        a.ssp_next = ssp_a;
+        hipLaunchKernelGGL(embed_fast_kernel, dim3(d / 16), dim3(64), 0, st, (const bf16_t *)m->embed, tok, a);
+    }
+    mark(m, ANPD_PROF_OTHER, st);
+    for (int l = 0; l < c.n_layers; ++l) {
+        {
+            FastArgs a = base;
+            a.Wp = (const uint4 *)(ws + L.wp_qkv[(size_t)l]);
+            a.Xp = (const uint4 *)xp_d;
+            a.nks = nks_d;
+            a.n_tiles = 3 * d / 16;
+            a.ssp = ssp_a;
+            a.q = q;
+            a.layer = l;
+            if ((rc = launch_fast<EPI_QKV>(a, m->n_cu, false, st)) != ANPD_OK) return rc;
+        }
+        mark(m, ANPD_PROF_GEMM_QKV, st);
+        if (dh == 128) {
+            hipLaunchKernelGGL((attn_kernel<bf16_t, 128>), dim3(H, n_splits), dim3(256), 0, st, q, d, (const bf16_t *)kv->pool,
+                               kv->d_table, kv->d_len, M, l, c.n_layers, H, c.page_tokens, c.max_window, L.max_splits, scale, part);
+            hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(M, H), dim3(128), 0, st, part, kv->d_len, H, c.max_window,
+                               L.max_splits, att, xp_att, cls);
+        } else {
+            hipLaunchKernelGGL((attn_kernel<bf16_t, 64>), dim3(H, n_splits), dim3(256), 0, st, q, d, (const bf16_t *)kv->pool,
+                               kv->d_table, kv->d_len, M, l, c.n_layers, H, c.page_tokens, c.max_window, L.max_splits, scale, part);
+            hipLaunchKernelGGL((attn_combine_kernel<64>), dim3(M, H), dim3(64), 0, st, part, kv->d_len, H, c.max_window,
+                               L.max_splits, att, xp_att, cls);
+        }
+        mark(m, ANPD_PROF_ATTN, st);
+        {
+            FastArgs a = base;
+            a.Wp = (const uint4 *)(ws + L.wp_o[(size_t)l]);
+            a.Xp = (const uint4 *)xp_att;
+            a.nks = nks_d;
+            a.n_tiles = d / 16;
+            a.gain = (const bf16_t *)m->ffn_norm[l];
+            a.xp_next = xp_d;
+            a.ssp_next = ssp_b;
+            if ((rc = launch_fast<EPI_RESIDUAL>(a, m->n_cu, false, st)) != ANPD_OK) return rc;
+        }
+        mark(m, ANPD_PROF_GEMM_O, st);
+        {
+            FastArgs a = base;
+            a.Wp = (const uint4 *)(ws + L.wp_gu[(size_t)l]);
+            a.Xp = (const uint4 *)xp_d;
+            a.nks = nks_d;
+            a.n_tiles = F / 8;
+            a.ssp = ssp_b;
+            a.ap = xp_f;
+            if ((rc = launch_fast<EPI_GATE_UP>(a, m->n_cu, false, st)) != ANPD_OK) return rc;
+        }
+        mark(m, ANPD_PROF_GEMM_GATE_UP, st);
+        {
+            FastArgs a = base;
+            a.Wp = (const uint4 *)(ws + L.wp_down[(size_t)l]);
+            a.Xp = (const uint4 *)xp_f;
+            a.nks = nks_f;
+            a.n_tiles = d / 16;
+            a.gain = (const bf16_t *)(l + 1 < c.n_layers ? m->attn_norm[(size_t)l + 1] : m->final_norm);
+            a.xp_next = xp_d;
+            a.ssp_next = ssp_a;
+            if ((rc = launch_fast<EPI_RESIDUAL>(a, m->n_cu, false, st)) != ANPD_OK) return rc;
+        }
+        mark(m, ANPD_PROF_GEMM_DOWN, st);
+    }
+    {
+        FastArgs a = base;
+        a.Wp = (const uint4 *)(ws + L.wp_lm);
+        a.Xp = (const uint4 *)xp_d;
+        a.nks = nks_d;
+        a.n_tiles = V / 16;
+        a.ssp = ssp_a;
+        a.Y = logits;
+        a.ldy = V;
+        if ((rc = launch_fast<EPI_LOGITS>(a, m->n_cu, false, st)) != ANPD_OK) return rc;
+    }
+    mark(m, ANPD_PROF_GEMM_LM_HEAD, st);
+    hipLaunchKernelGGL(argmax_accept_kernel, dim3(M), dim3(1024), 0, st, logits, V, M, tok, mode, result, kv->d_len,
+                       counter);
+    mark(m, ANPD_PROF_OTHER, st);
     HIP_TRY(hipGetLastError());
     return ANPD_OK;
 }
@@ -292,7 +482,14 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
     m->cfg = *cfg;
     m->lay = lay;
     m->ws = (char *)workspace;
-    m->mfma = cfg->gemm_path == ANPD_GEMM_MFMA || (cfg->gemm_path == ANPD_GEMM_AUTO && cfg->dtype == ANPD_BF16);
+    m->mfma = wants_mfma(cfg);
+    {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        m->n_cu = 256;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+            m->n_cu = prop.multiProcessorCount;
+    }
     m->embed = w->embed;
     m->final_norm = w->final_norm;
     m->lm_head = w->lm_head;
@@ -307,6 +504,10 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
     m->w_up.assign(w->w_up, w->w_up + nl);
     m->w_down.assign(w->w_down, w->w_down + nl);
     m->pin = nullptr;
+    m->prof = false;
+    m->ev_used = 0;
+    m->prof_steps = 0;
+    for (int i = 0; i < ANPD_PROF_NCAT; ++i) { m->prof_ms[i] = 0.0; m->prof_launches[i] = 0; }
 
     hipStream_t st = (hipStream_t)stream;
     // cos/sin of pos * base^(-2i/head_dim), evaluated in double, stored as float
@@ -321,13 +522,25 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
     }
     hipError_t e = hipHostMalloc((void **)&m->pin, 128 * sizeof(int32_t), hipHostMallocDefault);
     if (e != hipSuccess) { delete m; return fail(ANPD_E_HIP, "hipHostMalloc: %s", hipGetErrorString(e)); }
-    e = hipMemsetAsync(m->ws, 0, lay.total, st);
+    e = hipMemsetAsync(m->ws, 0, m->mfma ? lay.wp_lm : lay.total, st);
     if (e == hipSuccess) e = hipMemcpyAsync(m->ws + lay.rope_tab, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice, st);
+    int32_t prc = ANPD_OK;
+    if (e == hipSuccess && m->mfma) {
+        // repack every matrix into MFMA-fragment order inside the workspace
+        const int d = cfg->d_model, F = cfg->d_ffn, dh = cfg->head_dim;
+        for (int l = 0; l < cfg->n_layers && prc == ANPD_OK; ++l) {
+            prc = launch_pack(m->wq[l], m->wk[l], m->wv[l], m->ws + lay.wp_qkv[(size_t)l], PACK_QKV, 3 * d / 16, d, d, dh, st);
+            if (prc == ANPD_OK) prc = launch_pack(m->wo[l], nullptr, nullptr, m->ws + lay.wp_o[(size_t)l], PACK_PLAIN, d / 16, d, d, dh, st);
+            if (prc == ANPD_OK) prc = launch_pack(m->w_gate[l], m->w_up[l], nullptr, m->ws + lay.wp_gu[(size_t)l], PACK_GATE_UP, F / 8, d, d, dh, st);
+            if (prc == ANPD_OK) prc = launch_pack(m->w_down[l], nullptr, nullptr, m->ws + lay.wp_down[(size_t)l], PACK_PLAIN, d / 16, F, d, dh, st);
+        }
+        if (prc == ANPD_OK) prc = launch_pack(m->lm_head, nullptr, nullptr, m->ws + lay.wp_lm, PACK_PLAIN, cfg->vocab / 16, d, d, dh, st);
+    }
     if (e == hipSuccess) e = hipStreamSynchronize(st);
-    if (e != hipSuccess) {
+    if (e != hipSuccess || prc != ANPD_OK) {
         (void)hipHostFree(m->pin);
         delete m;
-        return fail(ANPD_E_HIP, "anpd_model_create: %s", hipGetErrorString(e));
+        return prc != ANPD_OK ? prc : fail(ANPD_E_HIP, "anpd_model_create: %s", hipGetErrorString(e));
     }
     *out = m;
     return ANPD_OK;
@@ -337,7 +550,25 @@ void anpd_model_destroy(anpd_model_t *m)
 {
     if (!m) return;
     if (m->pin) (void)hipHostFree(m->pin);
+    for (hipEvent_t e : m->ev) (void)hipEventDestroy(e);
     delete m;
+}
+
+int32_t anpd_model_profile(anpd_model_t *m, int32_t enable)
+{
+    if (!m) return fail(ANPD_E_INVAL, "anpd_model_profile: NULL handle");
+    m->prof = enable != 0;
+    m->prof_steps = 0;
+    for (int i = 0; i < ANPD_PROF_NCAT; ++i) { m->prof_ms[i] = 0.0; m->prof_launches[i] = 0; }
+    return ANPD_OK;
+}
+
+int32_t anpd_model_profile_read(const anpd_model_t *m, double *out_ms, int64_t *out_launches, int64_t *out_steps)
+{
+    if (!m || !out_ms || !out_launches || !out_steps) return fail(ANPD_E_INVAL, "anpd_model_profile_read: NULL argument");
+    for (int i = 0; i < ANPD_PROF_NCAT; ++i) { out_ms[i] = m->prof_ms[i]; out_launches[i] = m->prof_launches[i]; }
+    *out_steps = m->prof_steps;
+    return ANPD_OK;
 }
 
 size_t anpd_kv_pool_bytes(const anpd_model_t *m, int32_t max_tokens)
@@ -491,7 +722,9 @@ int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32
     if (rc != ANPD_OK) return rc;
     std::memcpy(m->pin, window, sizeof(int32_t) * (size_t)n_window);
     HIP_TRY(hipMemcpyAsync(m->ws + m->lay.tok, m->pin, sizeof(int32_t) * (size_t)n_window, hipMemcpyHostToDevice, st));
-    rc = m->cfg.dtype == ANPD_BF16 ? run_step<bf16_t>(m, kv, n_window, mode, st) : run_step<float>(m, kv, n_window, mode, st);
+    if (m->mfma) rc = run_step_fast(m, kv, n_window, mode, st);
+    else if (m->cfg.dtype == ANPD_BF16) rc = run_step_generic<bf16_t>(m, kv, n_window, mode, st);
+    else rc = run_step_generic<float>(m, kv, n_window, mode, st);
     if (rc != ANPD_OK) return rc;
     int32_t *res = m->pin + 32;
     HIP_TRY(hipMemcpyAsync(res, m->ws + m->lay.result, sizeof(int32_t) * (size_t)(2 + n_window), hipMemcpyDeviceToHost, st));
@@ -499,6 +732,16 @@ int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32
         HIP_TRY(hipMemcpyAsync(out_logits, m->ws + m->lay.logits, sizeof(float) * (size_t)n_window * m->cfg.vocab,
                                hipMemcpyDeviceToDevice, st));
     HIP_TRY(hipStreamSynchronize(st));
+    if (m->prof) {
+        for (int i = 1; i < m->ev_used; ++i) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, m->ev[(size_t)i - 1], m->ev[(size_t)i]) == hipSuccess) {
+                m->prof_ms[m->ev_cat[(size_t)i]] += (double)ms;
+                m->prof_launches[m->ev_cat[(size_t)i]] += 1;
+            }
+        }
+        m->prof_steps += 1;
+    }
     *out_accepted = res[0];
     *out_next = res[1];
     if (out_predicts) std::memcpy(out_predicts, res + 2, sizeof(int32_t) * (size_t)n_window);
@@ -510,7 +753,22 @@ int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32
 size_t anpd_linear_workspace_bytes(int32_t M, int32_t K)
 {
     if (M < 1 || M > ANPD_MAX_WINDOW || K < 8) return 0;
-    return align_up((size_t)64 * (size_t)K * sizeof(bf16_t));
+    return align_up((size_t)((K + 31) / 32) * 4 * 1024);
+}
+
+size_t anpd_packed_bytes(int32_t N, int32_t K)
+{
+    if (N < 16 || N % 16 != 0 || K < 8 || K % 8 != 0) return 0;
+    return packed_bytes((size_t)N / 16, K);
+}
+
+int32_t anpd_pack_weights(const void *W, int32_t N, int32_t K, void *packed, size_t packed_bytes_given, void *stream)
+{
+    if (!W || !packed) return fail(ANPD_E_INVAL, "anpd_pack_weights: NULL argument");
+    size_t need = anpd_packed_bytes(N, K);
+    if (need == 0) return fail(ANPD_E_INVAL, "anpd_pack_weights: need N %% 16 == 0 and K %% 8 == 0");
+    if (packed_bytes_given < need) return fail(ANPD_E_CAPACITY, "anpd_pack_weights: buffer has %zu bytes, %zu needed", packed_bytes_given, need);
+    return launch_pack(W, nullptr, nullptr, packed, PACK_PLAIN, N / 16, K, 0, 0, (hipStream_t)stream);
 }
 
 int32_t anpd_linear(const float *X, const void *W, float *Y, int32_t M, int32_t N, int32_t K, int32_t dtype,
@@ -522,13 +780,29 @@ int32_t anpd_linear(const float *X, const void *W, float *Y, int32_t M, int32_t 
     if (dtype != ANPD_F32 && dtype != ANPD_BF16) return fail(ANPD_E_INVAL, "anpd_linear: unknown dtype");
     hipStream_t st = (hipStream_t)stream;
     if (path == ANPD_GEMM_DOT) return launch_gemm_dot(X, M, K, W, nullptr, nullptr, 1, N, Y, N, dtype, st);
-    if (path != ANPD_GEMM_MFMA) return fail(ANPD_E_INVAL, "anpd_linear: path must be ANPD_GEMM_DOT or ANPD_GEMM_MFMA");
+    if (path != ANPD_GEMM_MFMA && path != ANPD_GEMM_MFMA_STREAM)
+        return fail(ANPD_E_INVAL, "anpd_linear: unknown path %d", path);
     if (dtype != ANPD_BF16) return fail(ANPD_E_INVAL, "anpd_linear: the MFMA path needs bf16 weights");
     if (!workspace || workspace_bytes < anpd_linear_workspace_bytes(M, K))
         return fail(ANPD_E_CAPACITY, "anpd_linear: workspace too small");
+    int n_cu = 256, dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+        n_cu = prop.multiProcessorCount;
     const int cls = window_class(M);
-    hipLaunchKernelGGL(split_kernel, dim3((K + 255) / 256, M), dim3(256), 0, st, X, (bf16_t *)workspace, M, K, cls);
-    return launch_gemm_mfma((const bf16_t *)workspace, M, K, W, nullptr, nullptr, 1, N, Y, N, st);
+    HIP_TRY(hipMemsetAsync(workspace, 0, anpd_linear_workspace_bytes(M, K), st));
+    hipLaunchKernelGGL(split_packed_kernel, dim3((K / 4 + 255) / 256, M), dim3(256), 0, st, X, (bf16_t *)workspace, M, K, cls);
+    FastArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.Wp = (const uint4 *)W;
+    a.Xp = (const uint4 *)workspace;
+    a.nks = (K + 31) / 32;
+    a.n_tiles = N / 16;
+    a.M = M;
+    a.cls = cls;
+    a.Y = Y;
+    a.ldy = N;
+    return launch_fast<EPI_PLAIN>(a, n_cu, path == ANPD_GEMM_MFMA_STREAM, st);
 }
 
 }  // extern "C"

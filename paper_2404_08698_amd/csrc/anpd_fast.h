@@ -1,0 +1,401 @@
+// Fused bf16 fast path of the verification step for gfx950.
+//
+// Weights are repacked once, at model creation, into MFMA-fragment order:
+//   Wp[tile][k-step][lane][8 bf16]        (1 KiB per 16-row x 32-k block)
+// where lane = 16 * kg + r holds W[row(tile, r)][32 * ks + 8 * kg .. + 8].  A wave
+// then loads the A operand of v_mfma_f32_16x16x32_bf16 with one fully
+// coalesced 1 KiB read, and the row map lets each fused epilogue find its
+// partner element in lane ^ 32:
+//   QKV    tile rows 0..7 = dims 8j..8j+7 of a head, rows 8..15 = the same
+//          dims + head_dim/2: the two halves of a rotary pair;
+//   gate/up  rows 0..7 = gate rows 8t..8t+7, rows 8..15 = the matching up rows.
+//
+// Activations travel between kernels as a split-bf16 operand in the same
+// fragment order, Xp[k-step][frag][lane][8] (see xp_offset), written by the
+// producing epilogue.  RMSNorm is folded around the GEMM: the producer stores
+// x * gain and per-tile partial sums of x^2; the consumer multiplies its
+// accumulators by 1/sqrt(mean(x^2) + eps).
+//
+// Summation order of every output element: k-steps ks = wave + u * nw in
+// increasing u inside a wave (MFMA accumulation), then waves in increasing
+// order, then hi + lo.  nw depends on the matrix shape only, so a row's
+// result is bit-identical for every window size and window class.
+#pragma once
+#include "anpd_kernels.h"
+
+namespace anpd {
+
+constexpr int kFastWaves = 16;  // waves per block of every fast GEMM: part of the numerics
+
+// store four consecutive columns k..k+3 (k % 4 == 0) of row m as hi and lo terms
+__device__ __forceinline__ void xp_store4(bf16_t *xp, int cls, int m, int k, f32x4 v)
+{
+    bf16_t hi[4], lo[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        hi[i] = f32_to_bf16(v[i]);
+        lo[i] = f32_to_bf16(v[i] - bf16_to_f32(hi[i]));
+    }
+    uint2 ph = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+    uint2 pl = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+    *reinterpret_cast<uint2 *>(xp + xp_offset(cls, m, k, 0)) = ph;
+    *reinterpret_cast<uint2 *>(xp + xp_offset(cls, m, k, 1)) = pl;
+}
+
+// ------------------------------------------------------------------ packing
+
+enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
+
+// One thread per 16-byte fragment slot of the packed matrix.
+// PLAIN:   tile t row r = src0 row 16 t + r.
+// QKV:     tiles [0,T) from src0 (q), [T,2T) from src1 (k), [2T,3T) from src2 (v), T = d / 16;
+//          q/k tile (head h, j): row r < 8 -> dim 8j + r, r >= 8 -> dim head_dim/2 + 8j + r - 8.
+// GATE_UP: tile t row r < 8 -> src0 (gate) row 8t + r, r >= 8 -> src1 (up) row 8t + r - 8.
+__global__ __launch_bounds__(256) void pack_kernel(const bf16_t *__restrict__ src0, const bf16_t *__restrict__ src1,
+                                                    const bf16_t *__restrict__ src2, uint4 *__restrict__ dst, int mode,
+                                                    int n_tiles, int K, int nks, int d, int head_dim)
+{
+    size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    size_t total = (size_t)n_tiles * nks * 64;
+    if (idx >= total) return;
+    int lane = (int)(idx & 63);
+    size_t rest = idx >> 6;
+    int ks = (int)(rest % nks), tile = (int)(rest / nks);
+    int r = lane & 15, kg = lane >> 4;
+    const bf16_t *src = src0;
+    int row;
+    if (mode == PACK_PLAIN) {
+        row = tile * 16 + r;
+    } else if (mode == PACK_QKV) {
+        int T = d / 16, which = tile / T, t = tile - which * T;
+        src = which == 0 ? src0 : (which == 1 ? src1 : src2);
+        if (which < 2) {
+            int tph = head_dim / 16, h = t / tph, j = t - h * tph;
+            int dim = r < 8 ? 8 * j + r : head_dim / 2 + 8 * j + (r - 8);
+            row = h * head_dim + dim;
+        } else {
+            row = t * 16 + r;
+        }
+    } else {
+        src = r < 8 ? src0 : src1;
+        row = tile * 8 + (r & 7);
+    }
+    int k = ks * 32 + kg * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (k < K) v = *reinterpret_cast<const uint4 *>(src + (size_t)row * K + k);
+    dst[idx] = v;
+}
+
+// --------------------------------------------------------------- epilogues
+
+enum { EPI_PLAIN = 0, EPI_QKV = 1, EPI_RESIDUAL = 2, EPI_GATE_UP = 3, EPI_LOGITS = 4 };
+
+struct FastArgs {
+    // GEMM proper
+    const uint4 *Wp;      // packed weights
+    const uint4 *Xp;      // packed split operand
+    int nks, n_tiles, M, cls;
+    // RMSNorm folded around the GEMM (QKV, GATE_UP, LOGITS): partial sums of squares of the input rows
+    const float *ssp;     // [n_ss][32]
+    int n_ss;
+    float inv_d, eps;
+    // outputs
+    float *Y;             // PLAIN / LOGITS: fp32 [M][ldy]
+    int ldy;
+    // QKV
+    float *q;             // fp32 [M][d]
+    bf16_t *pool;
+    const int32_t *page_table, *len_ptr;
+    const float2 *rope;
+    int layer, n_layers, n_heads, head_dim, page_tokens;
+    // RESIDUAL
+    float *x;             // residual stream fp32 [M][d], updated in place
+    const bf16_t *gain;   // gain of the norm that follows
+    bf16_t *xp_next;      // operand for the next GEMM: split(x * gain)
+    float *ssp_next;      // [n_tiles][32] partial sums of x^2
+    int d;
+    // GATE_UP
+    bf16_t *ap;           // operand of the down projection: split(silu(gate) * up)
+};
+
+// rinv[m] = 1 / sqrt(mean(x[m]^2) + eps) for the window rows, from the producer's per-tile partial
+// sums.  All 1024 threads of the block take part: thread (m = tid % 32, g = tid / 32) adds the
+// partials of tiles g, g + 32, ... in increasing order, then row m adds the 32 group sums in
+// increasing g.  The order depends on the tile count only.  Ends with a block barrier.
+__device__ __forceinline__ void compute_rinv(const FastArgs &a, float *rinv /* LDS [32] */, float *scratch /* LDS [32][32] */)
+{
+    const int m = threadIdx.x & 31, g = threadIdx.x >> 5;
+    float s = 0.f;
+    if (m < a.M)
+        for (int t = g; t < a.n_ss; t += 32) s += a.ssp[(size_t)t * 32 + m];
+    scratch[g * 32 + m] = s;
+    __syncthreads();
+    if (threadIdx.x < 32) {
+        float tot = 0.f;
+#pragma unroll
+        for (int gg = 0; gg < 32; ++gg) tot += scratch[gg * 32 + threadIdx.x];
+        rinv[threadIdx.x] = 1.0f / sqrtf(tot * a.inv_d + a.eps);
+    }
+    __syncthreads();
+}
+
+// y: this lane's four outputs D[4 kg + i][m] of tile `tile` for window row m (valid says whether the row exists).
+// Every lane of the wave must call this (the fused forms exchange values with lane ^ 32).
+template <int EPI>
+__device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int kg, f32x4 y, bool valid,
+                                         const float *rinv)
+{
+    if (EPI == EPI_PLAIN) {
+        if (valid) *reinterpret_cast<f32x4 *>(a.Y + (size_t)m * a.ldy + tile * 16 + 4 * kg) = y;
+    } else if (EPI == EPI_LOGITS) {
+        if (valid) *reinterpret_cast<f32x4 *>(a.Y + (size_t)m * a.ldy + tile * 16 + 4 * kg) = y * rinv[m];
+    } else if (EPI == EPI_RESIDUAL) {
+        const int n = tile * 16 + 4 * kg;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (valid) {
+            float *xr = a.x + (size_t)m * a.d + n;
+            v = *reinterpret_cast<const f32x4 *>(xr) + y;
+            *reinterpret_cast<f32x4 *>(xr) = v;
+            uint2 gb = *reinterpret_cast<const uint2 *>(a.gain + n);
+            f32x4 g = {__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xffff0000u), __uint_as_float(gb.y << 16),
+                       __uint_as_float(gb.y & 0xffff0000u)};
+            xp_store4(a.xp_next, a.cls, m, n, v * g);
+        }
+        float s = fmaf(v[3], v[3], fmaf(v[2], v[2], fmaf(v[1], v[1], v[0] * v[0])));
+        s += __shfl_xor(s, 16, kWave);
+        s += __shfl_xor(s, 32, kWave);
+        if (valid && kg == 0) a.ssp_next[(size_t)tile * 32 + m] = s;
+    } else if (EPI == EPI_QKV) {
+        const float r = valid ? rinv[m] : 0.f;
+        y = y * r;
+        const int T = a.n_heads * a.head_dim / 16;
+        const int which = tile / T, t = tile - which * T;
+        const int pos = *a.len_ptr + m;
+        f32x4 other;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) other[i] = __shfl_xor(y[i], 32, kWave);
+        if (!valid) return;
+        const int page = a.page_table[pos / a.page_tokens], tip = pos % a.page_tokens;
+        if (which < 2) {
+            const int tph = a.head_dim / 16, half = a.head_dim / 2;
+            const int h = t / tph, j = t - h * tph;
+            const int i0 = 8 * j + 4 * (kg & 1);
+            f32x4 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float2 cs = a.rope[(size_t)pos * half + i0 + i];
+                o[i] = kg < 2 ? y[i] * cs.x - other[i] * cs.y : y[i] * cs.x + other[i] * cs.y;
+            }
+            const int dim = i0 + (kg < 2 ? 0 : half);
+            if (which == 0) {
+                *reinterpret_cast<f32x4 *>(a.q + (size_t)m * a.d + h * a.head_dim + dim) = o;
+            } else {
+                bf16_t *dst = a.pool + kv_offset(page, a.layer, a.n_layers, 0, h, a.n_heads, tip, a.page_tokens, a.head_dim) + dim;
+                uint2 p = make_uint2((uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16),
+                                     (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16));
+                *reinterpret_cast<uint2 *>(dst) = p;
+            }
+        } else {
+            const int n = t * 16 + 4 * kg, h = n / a.head_dim, dim = n - h * a.head_dim;
+            bf16_t *dst = a.pool + kv_offset(page, a.layer, a.n_layers, 1, h, a.n_heads, tip, a.page_tokens, a.head_dim) + dim;
+            uint2 p = make_uint2((uint32_t)f32_to_bf16(y[0]) | ((uint32_t)f32_to_bf16(y[1]) << 16),
+                                 (uint32_t)f32_to_bf16(y[2]) | ((uint32_t)f32_to_bf16(y[3]) << 16));
+            *reinterpret_cast<uint2 *>(dst) = p;
+        }
+    } else if (EPI == EPI_GATE_UP) {
+        const float r = valid ? rinv[m] : 0.f;
+        y = y * r;
+        f32x4 up;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) up[i] = __shfl_xor(y[i], 32, kWave);
+        if (valid && kg < 2) {
+            f32x4 act;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) act[i] = y[i] / (1.0f + expf(-y[i])) * up[i];
+            xp_store4(a.ap, a.cls, m, tile * 8 + 4 * kg, act);
+        }
+    }
+}
+
+// Sum the per-wave partial tiles (wave order), add hi + lo, run the epilogue.  One wave calls this.
+template <int NT, int EPI>
+__device__ __forceinline__ void reduce_and_finish(const FastArgs &a, int tile, const float *red /* [nw][NT][256] */,
+                                                  int nw, int lane, const float *rinv)
+{
+    const int slot = lane & 15, kg = lane >> 4;
+    f32x4 tot[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        tot[t] = *reinterpret_cast<const f32x4 *>(red + ((size_t)t * 64 + lane) * 4);
+        for (int w = 1; w < nw; ++w)
+            tot[t] += *reinterpret_cast<const f32x4 *>(red + (((size_t)w * NT + t) * 64 + lane) * 4);
+    }
+    if (NT == 1) {
+        f32x4 lo;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lo[i] = __shfl_down(tot[0][i], 8, kWave);
+        epilogue<EPI>(a, tile, slot, kg, tot[0] + lo, slot < 8 && slot < a.M, rinv);
+    } else {
+#pragma unroll
+        for (int p = 0; p < NT / 2; ++p) {
+            int m = p * 16 + slot;
+            epilogue<EPI>(a, tile, m, kg, tot[2 * p] + tot[2 * p + 1], m < a.M, rinv);
+        }
+    }
+}
+
+// ---------------------------------------------------- GEMM, X-stationary
+//
+// Window class 8 only.  One block per compute unit; a wave keeps its slice of
+// the activation operand (k-steps wave, wave + 16, ...) in registers for the
+// whole kernel and streams the weight tiles block, block + grid, ... past it,
+// always one half-tile ahead, so the only memory traffic of the main loop is
+// the weights.  The partial tiles of the 16 waves meet in LDS (double
+// buffered, one barrier per tile); a different wave finishes each tile.
+template <int KPW, int EPI>
+__global__ __launch_bounds__(1024) void gemm_xs_kernel(FastArgs a)
+{
+    __shared__ float red[2][kFastWaves][256];
+    __shared__ float rinv[32];
+    constexpr int C = (KPW + 1) / 2;  // k-steps per pipeline stage
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nks = a.nks;
+    int tile = blockIdx.x;
+    uint4 w0[C], w1[KPW - C > 0 ? KPW - C : 1];
+    // first stage of the first tile goes out before anything else
+    if (tile < a.n_tiles) {
+        const uint4 *W = a.Wp + (size_t)tile * nks * 64 + lane;
+#pragma unroll
+        for (int u = 0; u < C; ++u) {
+            int ks = wave + u * kFastWaves;
+            w0[u] = ks < nks ? W[(size_t)ks * 64] : make_uint4(0, 0, 0, 0);
+        }
+    }
+    uint4 x[KPW];
+#pragma unroll
+    for (int u = 0; u < KPW; ++u) {
+        int ks = wave + u * kFastWaves;
+        x[u] = ks < nks ? a.Xp[(size_t)ks * 64 + lane] : make_uint4(0, 0, 0, 0);
+    }
+    if (EPI == EPI_QKV || EPI == EPI_GATE_UP || EPI == EPI_LOGITS) compute_rinv(a, rinv, &red[1][0][0]);
+
+    for (int it = 0; tile < a.n_tiles; tile += gridDim.x, ++it) {
+        const uint4 *W = a.Wp + (size_t)tile * nks * 64 + lane;
+        if (KPW > C) {
+#pragma unroll
+            for (int u = C; u < KPW; ++u) {
+                int ks = wave + u * kFastWaves;
+                w1[u - C] = ks < nks ? W[(size_t)ks * 64] : make_uint4(0, 0, 0, 0);
+            }
+        }
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < C; ++u)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w0[u]),
+                                                          __builtin_bit_cast(bf16x8, x[u]), acc, 0, 0, 0);
+        const int next = tile + gridDim.x;
+        if (next < a.n_tiles) {
+            const uint4 *Wn = a.Wp + (size_t)next * nks * 64 + lane;
+#pragma unroll
+            for (int u = 0; u < C; ++u) {
+                int ks = wave + u * kFastWaves;
+                w0[u] = ks < nks ? Wn[(size_t)ks * 64] : make_uint4(0, 0, 0, 0);
+            }
+        }
+        if (KPW > C) {
+#pragma unroll
+            for (int u = C; u < KPW; ++u)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w1[u - C]),
+                                                              __builtin_bit_cast(bf16x8, x[u]), acc, 0, 0, 0);
+        }
+        float *r = &red[it & 1][0][0];
+        *reinterpret_cast<f32x4 *>(r + ((size_t)wave * 64 + lane) * 4) = acc;
+        __syncthreads();
+        if (wave == (it & (kFastWaves - 1))) reduce_and_finish<1, EPI>(a, tile, r, kFastWaves, lane, rinv);
+    }
+}
+
+// ------------------------------------------------------ GEMM, streaming X
+//
+// Any window class and any K: one block per weight tile, the activation
+// fragments are read from global memory (L2-resident) next to the weights.
+// Same k-step assignment and summation order as the X-stationary form.
+template <int NT, int EPI>
+__global__ __launch_bounds__(1024) void gemm_stream_kernel(FastArgs a)
+{
+    extern __shared__ float red_dyn[];  // [16][NT][256]
+    __shared__ float rinv[32];
+    constexpr int C = NT == 1 ? 4 : (NT == 2 ? 2 : 1);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nks = a.nks, tile = blockIdx.x;
+    const uint4 *W = a.Wp + (size_t)tile * nks * 64 + lane;
+    const uint4 *X = a.Xp + lane;
+    if (EPI == EPI_QKV || EPI == EPI_GATE_UP || EPI == EPI_LOGITS) compute_rinv(a, rinv, red_dyn);
+    f32x4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int u0 = 0; wave + u0 * kFastWaves < nks; u0 += C) {
+        uint4 wv[C], xv[C][NT];
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            int ks = wave + (u0 + c) * kFastWaves;
+            bool ok = ks < nks;
+            wv[c] = ok ? W[(size_t)ks * 64] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) xv[c][t] = ok ? X[((size_t)ks * NT + t) * 64] : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wv[c]),
+                                                                 __builtin_bit_cast(bf16x8, xv[c][t]), acc[t], 0, 0, 0);
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+        *reinterpret_cast<f32x4 *>(red_dyn + (((size_t)wave * NT + t) * 64 + lane) * 4) = acc[t];
+    __syncthreads();
+    if (wave == 0) reduce_and_finish<NT, EPI>(a, tile, red_dyn, kFastWaves, lane, rinv);
+}
+
+// ------------------------------------------------------------------ embed
+//
+// x[m] = E[token[m]] plus what the residual epilogue would leave behind for the
+// first layer: split(x * attn_gain[0]) and the partial sums of squares.
+// grid: d / 16 blocks of one wave.
+__global__ __launch_bounds__(64) void embed_fast_kernel(const bf16_t *__restrict__ E, const int32_t *__restrict__ tok,
+                                                         FastArgs a)
+{
+    const int lane = threadIdx.x, slot = lane & 15, kg = lane >> 4, tile = blockIdx.x;
+    const int n = tile * 16 + 4 * kg;
+    for (int p = 0; p < (a.M + 15) / 16; ++p) {
+        const int m = p * 16 + slot;
+        const bool valid = m < a.M;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (valid) {
+            uint2 eb = *reinterpret_cast<const uint2 *>(E + (size_t)tok[m] * a.d + n);
+            v = (f32x4){__uint_as_float(eb.x << 16), __uint_as_float(eb.x & 0xffff0000u), __uint_as_float(eb.y << 16),
+                        __uint_as_float(eb.y & 0xffff0000u)};
+            *reinterpret_cast<f32x4 *>(a.x + (size_t)m * a.d + n) = v;
+            uint2 gb = *reinterpret_cast<const uint2 *>(a.gain + n);
+            f32x4 g = {__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xffff0000u), __uint_as_float(gb.y << 16),
+                       __uint_as_float(gb.y & 0xffff0000u)};
+            xp_store4(a.xp_next, a.cls, m, n, v * g);
+        }
+        float s = fmaf(v[3], v[3], fmaf(v[2], v[2], fmaf(v[1], v[1], v[0] * v[0])));
+        s += __shfl_xor(s, 16, kWave);
+        s += __shfl_xor(s, 32, kWave);
+        if (valid && kg == 0) a.ssp_next[(size_t)tile * 32 + m] = s;
+    }
+}
+
+// fp32 [M][K] -> packed split operand (stand-alone linear entry point)
+__global__ __launch_bounds__(256) void split_packed_kernel(const float *__restrict__ X, bf16_t *__restrict__ xp, int M,
+                                                            int K, int cls)
+{
+    int m = blockIdx.y;
+    int k = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (m < M && k < K) xp_store4(xp, cls, m, k, *reinterpret_cast<const f32x4 *>(X + (size_t)m * K + k));
+}
+
+}  // namespace anpd

@@ -70,31 +70,24 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
-// ------------------------------------------------- split bf16 GEMM operand
-//
-// The MFMA GEMM takes its activation operand as two bf16 terms, v ~= hi + lo
-// (hi = bf16(v), lo = bf16(v - hi)), which keeps ~16 mantissa bits of the fp32
-// activation.  The operand buffer is a stack of 16-row bf16 tiles [tile][16][K].
-// Window class 8  (M <= 8):  one tile, rows m = hi, rows m + 8 = lo.
-// Window class 16 (M <= 16): tile 0 = hi, tile 1 = lo.
-// Window class 32 (M <= 32): tiles (0,1) = (hi,lo) of rows 0..15, (2,3) of rows 16..31.
+// Window class: how many 16-row MFMA slots a window of M rows occupies (8 = half a tile).
 __host__ __device__ __forceinline__ int window_class(int M) { return M <= 8 ? 8 : (M <= 16 ? 16 : 32); }
 
-__device__ __forceinline__ void split_store(bf16_t *xs, int K, int cls, int m, int k, float v)
+// The MFMA GEMMs take their activation operand as two bf16 terms, v ~= hi + lo
+// (hi = bf16(v), lo = bf16(v - hi)), which keeps ~16 mantissa bits of the fp32
+// activation, laid out in MFMA B-fragment order Xp[k-step][frag][lane][8]:
+// lane = 16 * kg + slot holds columns 32 * ks + 8 * kg .. + 8 of the row in `slot`.
+//   class 8:  one fragment; slot m = hi of row m, slot m + 8 = lo of row m;
+//   class 16: fragments (hi, lo) of rows 0..15;
+//   class 32: fragments (hi, lo) of rows 0..15, then (hi, lo) of rows 16..31.
+// Returns the bf16-element offset of (row m, column k, hi|lo).
+__host__ __device__ __forceinline__ size_t xp_offset(int cls, int m, int k, int lo)
 {
-    bf16_t hi = f32_to_bf16(v);
-    bf16_t lo = f32_to_bf16(v - bf16_to_f32(hi));
-    size_t hi_row, lo_row;
-    if (cls == 8) {
-        hi_row = (size_t)m;
-        lo_row = (size_t)m + 8;
-    } else {
-        size_t t = (size_t)(m >> 4) * 2;
-        hi_row = t * 16 + (size_t)(m & 15);
-        lo_row = (t + 1) * 16 + (size_t)(m & 15);
-    }
-    xs[hi_row * (size_t)K + (size_t)k] = hi;
-    xs[lo_row * (size_t)K + (size_t)k] = lo;
+    const int ks = k >> 5, kg = (k >> 3) & 3, j = k & 7;
+    int nt, frag, slot;
+    if (cls == 8) { nt = 1; frag = 0; slot = m + 8 * lo; }
+    else { nt = cls >> 3; frag = 2 * (m >> 4) + lo; slot = m & 15; }
+    return ((((size_t)ks * nt + frag) * 64) + (size_t)kg * 16 + slot) * 8 + j;
 }
 
 // ------------------------------------------------------------------ embed
@@ -112,12 +105,11 @@ __global__ __launch_bounds__(256) void embed_kernel(const WT *__restrict__ E, co
 // --------------------------------------------------- residual add + RMSNorm
 
 // x[r] += y[r] (if y), then h[r] = x[r] * g / sqrt(mean(x[r]^2) + eps).
-// Writes h as fp32 and, if hs != nullptr, as the split bf16 operand.
 // grid: M blocks, one row each; the reduction order depends on d only.
 template <typename WT>
 __global__ __launch_bounds__(256) void addnorm_kernel(float *__restrict__ x, const float *__restrict__ y,
-                                                       const WT *__restrict__ g, float *__restrict__ h,
-                                                       bf16_t *__restrict__ hs, int d, float eps, int cls)
+                                                       const WT *__restrict__ g, float *__restrict__ h, int d,
+                                                       float eps)
 {
     __shared__ float part[4];
     int r = blockIdx.x;
@@ -139,7 +131,6 @@ __global__ __launch_bounds__(256) void addnorm_kernel(float *__restrict__ x, con
     for (int i = threadIdx.x; i < d; i += 256) {
         float v = xr[i] * load_f32(g, (size_t)i) * rinv;
         h[(size_t)r * d + i] = v;
-        if (hs) split_store(hs, d, cls, r, i, v);
     }
 }
 
@@ -197,103 +188,6 @@ __global__ __launch_bounds__(256) void gemm_dot_kernel(const float *__restrict__
     }
 }
 
-// -------------------------------------------------------------- GEMM (MFMA)
-//
-// Matrix-core form for bf16 weights.  A block owns one 16-row tile of W (16
-// output columns of Y) and all of K; its waves take interleaved chunks of
-// kU 32-wide k-steps.  The weight tile is the A operand straight from global
-// memory: lane (row = lane % 16, kg = lane / 16) loads the 8 bf16 at
-// W[n0 + row][32 * ks + 8 * kg ..], exactly the layout
-// v_mfma_f32_16x16x32_bf16 wants, so weights go HBM -> VGPR -> MFMA with no
-// staging.  The B operand is the split activation tile (see split_store).
-// hi and lo products are accumulated separately and added once at the end,
-// after the per-wave partial tiles have been summed through LDS in wave order:
-// the arithmetic per output element is the same for every window class.
-// grid: (nseg * n_seg) / 16 blocks of NW waves (NW = blockDim.x / 64 <= 16).
-constexpr int kMfmaU = 4;
-
-template <int CLS>
-__global__ __launch_bounds__(1024) void gemm_mfma_kernel(const bf16_t *__restrict__ Xs, int M, int K,
-                                                          const bf16_t *__restrict__ W0,
-                                                          const bf16_t *__restrict__ W1,
-                                                          const bf16_t *__restrict__ W2, int n_seg,
-                                                          float *__restrict__ Y, int ldy)
-{
-    constexpr int NT = CLS / 8;  // activation tiles: 1, 2, 4
-    extern __shared__ float red[];  // [NW][NT][64][4]
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-    const int row = lane & 15, kg = lane >> 4;
-    const int n0 = blockIdx.x * 16;
-    const int seg = n0 / n_seg;
-    const bf16_t *W = (seg == 0 ? W0 : (seg == 1 ? W1 : W2)) + (size_t)(n0 - seg * n_seg + row) * K;
-    const bf16_t *Xr = Xs + (size_t)row * K;
-    const int nks = (K + 31) >> 5;
-
-    f32x4 acc[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-
-    for (int ks0 = wave * kMfmaU; ks0 < nks; ks0 += nw * kMfmaU) {
-        uint4 a[kMfmaU], b[kMfmaU][NT];
-#pragma unroll
-        for (int u = 0; u < kMfmaU; ++u) {
-            int k = (ks0 + u) * 32 + kg * 8;
-            bool ok = k < K;
-            a[u] = ok ? *reinterpret_cast<const uint4 *>(W + k) : make_uint4(0, 0, 0, 0);
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-                b[u][t] = ok ? *reinterpret_cast<const uint4 *>(Xr + (size_t)t * 16 * K + k) : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int u = 0; u < kMfmaU; ++u)
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[u]),
-                                                                 __builtin_bit_cast(bf16x8, b[u][t]), acc[t], 0, 0, 0);
-    }
-
-    // acc[t][i] = D[n0 + 4 * kg + i][slot = row] of this wave's share of K
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-        *reinterpret_cast<f32x4 *>(red + ((size_t)(wave * NT + t) * 64 + lane) * 4) = acc[t];
-    __syncthreads();
-    if (wave != 0) return;
-    f32x4 tot[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        tot[t] = *reinterpret_cast<const f32x4 *>(red + ((size_t)t * 64 + lane) * 4);
-        for (int w = 1; w < nw; ++w) tot[t] += *reinterpret_cast<const f32x4 *>(red + ((size_t)(w * NT + t) * 64 + lane) * 4);
-    }
-    const int ncol = n0 + 4 * kg;
-    if (CLS == 8) {
-        f32x4 lo;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) lo[i] = __shfl_down(tot[0][i], 8, kWave);
-        if (row < 8 && row < M) {
-            f32x4 r = tot[0] + lo;
-            *reinterpret_cast<f32x4 *>(Y + (size_t)row * ldy + ncol) = r;
-        }
-    } else {
-#pragma unroll
-        for (int p = 0; p < NT / 2; ++p) {
-            int m = p * 16 + row;
-            if (m < M) {
-                f32x4 r = tot[2 * p] + tot[2 * p + 1];
-                *reinterpret_cast<f32x4 *>(Y + (size_t)m * ldy + ncol) = r;
-            }
-        }
-    }
-}
-
-// fp32 [M][K] -> split bf16 operand (used by the stand-alone linear entry point)
-__global__ __launch_bounds__(256) void split_kernel(const float *__restrict__ X, bf16_t *__restrict__ xs, int M, int K,
-                                                     int cls)
-{
-    int m = blockIdx.y;
-    int k = blockIdx.x * 256 + threadIdx.x;
-    if (m < M && k < K) split_store(xs, K, cls, m, k, X[(size_t)m * K + k]);
-}
-
 // ------------------------------------------------------- RoPE + KV write
 //
 // Page layout: [page][layer][k|v][head][token in page][head_dim].
@@ -348,7 +242,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(float *__restrict__ qkv, c
 // part: [head][split][max_window][DH + 2] = (o[DH], max, denominator).
 // grid: (n_heads, n_splits), 4 waves.
 template <typename KT, int DH>
-__global__ __launch_bounds__(256) void attn_kernel(const float *__restrict__ qkv, const KT *__restrict__ pool,
+__global__ __launch_bounds__(256) void attn_kernel(const float *__restrict__ qkv, int q_stride, const KT *__restrict__ pool,
                                                     const int32_t *__restrict__ page_table,
                                                     const int32_t *__restrict__ len_ptr, int M, int layer, int n_layers,
                                                     int n_heads, int page_tokens, int max_window, int max_splits,
@@ -367,7 +261,6 @@ __global__ __launch_bounds__(256) void attn_kernel(const float *__restrict__ qkv
     if (s0 >= L + M) return;  // no key of this split exists for any row
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ksub = lane / LPK, dg = lane % LPK;
-    const int d = n_heads * DH;
 
     for (int m0 = 0; m0 < M; m0 += 8) {
         // ---- scores
@@ -375,7 +268,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const float *__restrict__ qkv
 #pragma unroll
         for (int mm = 0; mm < 8; ++mm) {
             if (m0 + mm < M) {
-                load8(qkv + (size_t)(m0 + mm) * 3 * d + head * DH + dg * 8, qv[mm]);
+                load8(qkv + (size_t)(m0 + mm) * q_stride + head * DH + dg * 8, qv[mm]);
             } else {
 #pragma unroll
                 for (int i = 0; i < 8; ++i) qv[mm][i] = 0.f;
@@ -490,21 +383,24 @@ __global__ __launch_bounds__(DH) void attn_combine_kernel(const float *__restric
     float v = o / den;
     const int d = n_heads * DH;
     att[(size_t)r * d + head * DH + e] = v;
-    if (atts) split_store(atts, d, cls, r, head * DH + e, v);
+    if (atts) {
+        bf16_t hi = f32_to_bf16(v);
+        atts[xp_offset(cls, r, head * DH + e, 0)] = hi;
+        atts[xp_offset(cls, r, head * DH + e, 1)] = f32_to_bf16(v - bf16_to_f32(hi));
+    }
 }
 
 // ------------------------------------------------------------------ SwiGLU
 
 // a[r][i] = silu(gu[r][i]) * gu[r][F + i]    grid: (ceil(F/256), M)
 __global__ __launch_bounds__(256) void swiglu_kernel(const float *__restrict__ gu, float *__restrict__ a,
-                                                      bf16_t *__restrict__ as, int F, int cls)
+                                                      int F)
 {
     int r = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
     if (i >= F) return;
     float g = gu[(size_t)r * 2 * F + i], u = gu[(size_t)r * 2 * F + F + i];
     float v = g / (1.0f + expf(-g)) * u;
     a[(size_t)r * F + i] = v;
-    if (as) split_store(as, F, cls, r, i, v);
 }
 
 // ------------------------------------------- argmax + acceptance + commit

@@ -109,6 +109,8 @@ class ModelShape:
 
 TINY = ModelShape(2, 256, 4, 64, 688, 1024, "f32")
 TINY_BF16 = dataclasses.replace(TINY, dtype="bf16")
+# head_dim 128 like the LLaMA shapes, small enough for the oracle: used by parity tests
+MID_BF16 = ModelShape(3, 512, 4, 128, 1408, 2048, "bf16")
 LLAMA_7B = ModelShape(32, 4096, 32, 128, 11008, 32000, "bf16")
 LLAMA_13B = ModelShape(40, 5120, 40, 128, 13824, 32000, "bf16")
 

@@ -6,7 +6,7 @@ from oracle import decoder as od
 from paper_2404_08698_amd import binding as B
 from paper_2404_08698_amd import synth
 
-TOL = {"f32": 1e-4, "bf16": 2e-2}   # max-abs on logits, stated by the build target
+TOL = {"f32": 1e-4, "bf16": 2e-2, "mid": 2e-2}   # max-abs on logits, stated by the build target
 
 
 def to_cuda(weights):

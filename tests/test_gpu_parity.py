@@ -13,16 +13,17 @@ from helpers import TOL, gpu_logits, make_pair, seed_kv_both, to_cuda, top2_gap
 
 pytestmark = pytest.mark.gpu
 
-PATHS = [("f32", B.GEMM_DOT), ("bf16", B.GEMM_DOT), ("bf16", B.GEMM_MFMA)]
+PATHS = [("f32", B.GEMM_DOT), ("bf16", B.GEMM_DOT), ("bf16", B.GEMM_MFMA), ("mid", B.GEMM_MFMA), ("mid", B.GEMM_DOT)]
+LINEAR_PATHS = PATHS[:3] + [("bf16", B.GEMM_MFMA_STREAM)]
 
 
 def _shape(dt):
-    return synth.TINY if dt == "f32" else synth.TINY_BF16
+    return {"f32": synth.TINY, "bf16": synth.TINY_BF16, "mid": synth.MID_BF16}[dt]
 
 
 # ------------------------------------------------------------------ GEMM
 
-@pytest.mark.parametrize("dt,path", PATHS)
+@pytest.mark.parametrize("dt,path", LINEAR_PATHS)
 @pytest.mark.parametrize("M,N,K", [(1, 64, 256), (6, 688, 256), (5, 256, 688), (8, 1024, 512),
                                    (9, 48, 1000), (16, 256, 4096), (17, 32, 40), (32, 128, 1032)])
 def test_linear_against_oracle(dt, path, M, N, K):
@@ -36,9 +37,9 @@ def test_linear_against_oracle(dt, path, M, N, K):
     assert np.std(ref) > 0.05
 
 
-@pytest.mark.parametrize("dt,path", PATHS)
-def test_linear_rows_do_not_depend_on_window_size(dt, path):
-    K, N = 688, 256
+@pytest.mark.parametrize("dt,path", LINEAR_PATHS)
+@pytest.mark.parametrize("K,N", [(688, 256), (4096, 512), (5120, 64), (11008, 32)])
+def test_linear_rows_do_not_depend_on_window_size(dt, path, K, N):
     X = synth.approx_normal(13, 1, 32 * K, 1.0).reshape(32, K).cuda()
     W = synth.approx_normal(14, 2, N * K, 0.02).reshape(N, K)
     W = (W.to(torch.bfloat16) if dt == "bf16" else W).cuda()
@@ -46,6 +47,17 @@ def test_linear_rows_do_not_depend_on_window_size(dt, path):
     for M in (1, 2, 6, 8, 9, 16, 17, 31):
         part = B.linear(X[:M].contiguous(), W, path)
         assert torch.equal(part, full[:M]), M
+
+
+def test_both_mfma_forms_are_bit_identical():
+    for K, N in [(256, 64), (4096, 4096 + 16), (5120, 48), (11008, 32)]:
+        X = synth.approx_normal(15, K, 8 * K, 1.0).reshape(8, K).cuda()
+        W = synth.approx_normal(16, K, N * K, 0.02).reshape(N, K).to(torch.bfloat16).cuda()
+        Wp = B.pack_weights(W)
+        for M in (1, 5, 8):
+            a = B.linear(X[:M].contiguous(), W, B.GEMM_MFMA, packed=Wp)
+            b = B.linear(X[:M].contiguous(), W, B.GEMM_MFMA_STREAM, packed=Wp)
+            assert torch.equal(a, b), (K, N, M)
 
 
 # -------------------------------------------------------------- whole step
@@ -128,7 +140,7 @@ def test_anpd_is_lossless_on_the_gpu(dt, path, N, K):
     assert res["n_steps"] + res["accepted"] >= 64
     if K == 0:
         assert res["n_steps"] == 64
-    if K >= 4:
+    if K >= 4 and dt != "mid":
         assert res["accepted"] > 0       # the tiny model loops, drafts do hit
 
 
