@@ -144,10 +144,13 @@ void anpd_model_destroy(anpd_model_t *m);
 
 /* Bytes of device pool a cache of max_tokens positions needs (0 on bad args). */
 size_t anpd_kv_pool_bytes(const anpd_model_t *m, int32_t max_tokens);
-/* pool: DEVICE, 256-byte aligned, >= anpd_kv_pool_bytes().  Pages hold
- * page_tokens positions of every layer's K and V, laid out
- * [page][layer][k|v][head][token in page][head_dim] in cfg.dtype; a page table
- * maps logical to physical pages.  max_tokens <= cfg.max_positions. */
+/* pool: DEVICE, 256-byte aligned, >= anpd_kv_pool_bytes(); cleared by this call.
+ * Pages hold page_tokens positions of every layer's K and V as blocks
+ * [page][layer][k|v][head] of page_tokens x head_dim elements in cfg.dtype; a page
+ * table maps logical to physical pages.  Inside a block the DOT path stores
+ * [token][dim]; the MFMA path (page_tokens == 16) stores K and V in the order the
+ * matrix-core fragments want (use anpd_kv_read / anpd_kv_write to exchange
+ * contents).  max_tokens <= cfg.max_positions. */
 int32_t anpd_kv_create(const anpd_model_t *m, void *pool, size_t pool_bytes, int32_t max_tokens,
                        anpd_kv_t **out);
 void anpd_kv_destroy(anpd_kv_t *kv);

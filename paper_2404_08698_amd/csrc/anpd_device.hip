@@ -31,7 +31,7 @@ size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 struct Layout {  // byte offsets into the model workspace
     size_t rope_tab, tok, result, counter, x, h, y, qkv, att, gu, a, logits, part;
     // fast path: packed operands, partial sums of squares, packed weights
-    size_t xp_d, xp_att, xp_f, ssp_a, ssp_b, wp_lm, total;
+    size_t xp_d, xp_att, xp_f, ssp_a, ssp_b, qp, head_ctr, wp_lm, total;
     std::vector<size_t> wp_qkv, wp_o, wp_gu, wp_down;
     int max_splits;
 };
@@ -42,6 +42,8 @@ bool wants_mfma(const anpd_model_cfg *c)
 }
 
 size_t packed_bytes(size_t n_tiles, int K) { return n_tiles * (size_t)((K + 31) / 32) * 1024; }
+
+bool wants_mfma(const anpd_model_cfg *c);
 
 bool cfg_ok(const anpd_model_cfg *c, const char **why)
 {
@@ -58,6 +60,7 @@ bool cfg_ok(const anpd_model_cfg *c, const char **why)
     REQ(c->gemm_path >= ANPD_GEMM_AUTO && c->gemm_path <= ANPD_GEMM_MFMA, "unknown gemm_path");
     REQ(!(c->gemm_path == ANPD_GEMM_MFMA && c->dtype != ANPD_BF16), "the MFMA path needs bf16 weights");
     REQ(c->rms_eps > 0.f && c->rope_base > 1.f, "rms_eps / rope_base out of range");
+    REQ(!(wants_mfma(c) && c->page_tokens != 16), "the MFMA path needs page_tokens == 16");
 #undef REQ
     return true;
 }
@@ -81,14 +84,16 @@ Layout make_layout(const anpd_model_cfg *c)
     L.gu = take(MW * 2 * F * 4);
     L.a = take(MW * F * 4);
     L.logits = take(MW * V * 4);
-    L.part = take((size_t)c->n_heads * L.max_splits * MW * (c->head_dim + 2) * 4);
-    L.xp_d = L.xp_att = L.xp_f = L.ssp_a = L.ssp_b = L.wp_lm = 0;
+    L.part = take((size_t)c->n_heads * L.max_splits * (wants_mfma(c) ? 32 : MW) * (c->head_dim + 2) * 4);
+    L.xp_d = L.xp_att = L.xp_f = L.ssp_a = L.ssp_b = L.qp = L.head_ctr = L.wp_lm = 0;
     if (wants_mfma(c)) {
         L.xp_d = take(((d + 31) / 32) * 4 * 1024);
         L.xp_att = take(((d + 31) / 32) * 4 * 1024);
         L.xp_f = take(((F + 31) / 32) * 4 * 1024);
         L.ssp_a = take((d / 16) * 32 * 4);
         L.ssp_b = take((d / 16) * 32 * 4);
+        L.qp = take((size_t)c->n_heads * 4 * (c->head_dim / 32) * 1024);
+        L.head_ctr = take((size_t)c->n_heads * sizeof(uint32_t));
         L.wp_lm = take(packed_bytes(V / 16, (int)d));
         for (int l = 0; l < c->n_layers; ++l) {
             L.wp_qkv.push_back(take(packed_bytes(3 * d / 16, (int)d)));
@@ -326,15 +331,17 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
     char *ws = m->ws;
     const int d = c.d_model, F = c.d_ffn, V = c.vocab, H = c.n_heads, dh = c.head_dim;
     const int cls = window_class(M);
-    float *x = (float *)(ws + L.x), *q = (float *)(ws + L.qkv), *att = (float *)(ws + L.att);
+    float *x = (float *)(ws + L.x);
     float *logits = (float *)(ws + L.logits), *part = (float *)(ws + L.part);
+    bf16_t *qp = (bf16_t *)(ws + L.qp);
+    uint32_t *head_ctr = (uint32_t *)(ws + L.head_ctr);
     bf16_t *xp_d = (bf16_t *)(ws + L.xp_d), *xp_att = (bf16_t *)(ws + L.xp_att), *xp_f = (bf16_t *)(ws + L.xp_f);
     float *ssp_a = (float *)(ws + L.ssp_a), *ssp_b = (float *)(ws + L.ssp_b);
     const int32_t *tok = (const int32_t *)(ws + L.tok);
     int32_t *result = (int32_t *)(ws + L.result);
     uint32_t *counter = (uint32_t *)(ws + L.counter);
     const float scale = 1.0f / sqrtf((float)dh);
-    const int n_splits = (kv->len + M + kAttnSplit - 1) / kAttnSplit;
+    const int n_splits = (kv->len + M + kFastSplit - 1) / kFastSplit;
     const int nks_d = (d + 31) / 32, nks_f = (F + 31) / 32;
     int32_t rc;
 
@@ -354,7 +361,6 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
     base.n_layers = c.n_layers;
     base.n_heads = H;
     base.head_dim = dh;
-    base.page_tokens = c.page_tokens;
 
     m->ev_used = 0;
     mark(m, -1, st);
@@ -374,22 +380,19 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
             a.nks = nks_d;
             a.n_tiles = 3 * d / 16;
             a.ssp = ssp_a;
-            a.q = q;
+            a.qp = qp;
             a.layer = l;
             if ((rc = launch_fast<EPI_QKV>(a, m->n_cu, false, st)) != ANPD_OK) return rc;
         }
         mark(m, ANPD_PROF_GEMM_QKV, st);
-        if (dh == 128) {
-            hipLaunchKernelGGL((attn_kernel<bf16_t, 128>), dim3(H, n_splits), dim3(256), 0, st, q, d, (const bf16_t *)kv->pool,
-                               kv->d_table, kv->d_len, M, l, c.n_layers, H, c.page_tokens, c.max_window, L.max_splits, scale, part);
-            hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(M, H), dim3(128), 0, st, part, kv->d_len, H, c.max_window,
-                               L.max_splits, att, xp_att, cls);
-        } else {
-            hipLaunchKernelGGL((attn_kernel<bf16_t, 64>), dim3(H, n_splits), dim3(256), 0, st, q, d, (const bf16_t *)kv->pool,
-                               kv->d_table, kv->d_len, M, l, c.n_layers, H, c.page_tokens, c.max_window, L.max_splits, scale, part);
-            hipLaunchKernelGGL((attn_combine_kernel<64>), dim3(M, H), dim3(64), 0, st, part, kv->d_len, H, c.max_window,
-                               L.max_splits, att, xp_att, cls);
-        }
+        if (dh == 128)
+            hipLaunchKernelGGL((attn_fast_kernel<128>), dim3(H, n_splits), dim3(1024), 0, st, (const uint4 *)qp,
+                               (const bf16_t *)kv->pool, kv->d_table, kv->d_len, M, l, c.n_layers, H, L.max_splits, scale, part,
+                               head_ctr, xp_att, cls);
+        else
+            hipLaunchKernelGGL((attn_fast_kernel<64>), dim3(H, n_splits), dim3(1024), 0, st, (const uint4 *)qp,
+                               (const bf16_t *)kv->pool, kv->d_table, kv->d_len, M, l, c.n_layers, H, L.max_splits, scale, part,
+                               head_ctr, xp_att, cls);
         mark(m, ANPD_PROF_ATTN, st);
         {
             FastArgs a = base;
@@ -610,6 +613,7 @@ int32_t anpd_kv_create(const anpd_model_t *m, void *pool, size_t pool_bytes, int
     kv->table_dirty = true;
     kv->pin = nullptr;
     hipError_t e = hipHostMalloc((void **)&kv->pin, ((size_t)kv->n_pages + 1) * sizeof(int32_t), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipMemset(kv->pool, 0, need);  // unwritten slots must read as zeros, never as NaN patterns
     if (e == hipSuccess) {
         kv->pin[0] = 0;
         e = hipMemcpy(kv->d_len, kv->pin, sizeof(int32_t), hipMemcpyHostToDevice);
@@ -684,7 +688,14 @@ static int32_t kv_copy(anpd_kv *kv, int32_t layer, int32_t pos0, int32_t n, floa
 #define KV_COPY(KT, TO)                                                                                          \
     hipLaunchKernelGGL((kv_copy_kernel<KT, TO>), dim3(n), dim3(256), 0, st, (KT *)kv->pool, kv->d_table, k, v, pos0, \
                        layer, c.n_layers, c.n_heads, c.head_dim, c.page_tokens)
-    if (c.dtype == ANPD_BF16) { if (to_cache) KV_COPY(bf16_t, true); else KV_COPY(bf16_t, false); }
+    if (kv->m->mfma) {
+        if (to_cache)
+            hipLaunchKernelGGL((kvf_copy_kernel<true>), dim3(n), dim3(256), 0, st, (bf16_t *)kv->pool, kv->d_table, k, v, pos0,
+                               layer, c.n_layers, c.n_heads, c.head_dim);
+        else
+            hipLaunchKernelGGL((kvf_copy_kernel<false>), dim3(n), dim3(256), 0, st, (bf16_t *)kv->pool, kv->d_table, k, v, pos0,
+                               layer, c.n_layers, c.n_heads, c.head_dim);
+    } else if (c.dtype == ANPD_BF16) { if (to_cache) KV_COPY(bf16_t, true); else KV_COPY(bf16_t, false); }
     else { if (to_cache) KV_COPY(float, true); else KV_COPY(float, false); }
 #undef KV_COPY
     HIP_TRY(hipGetLastError());

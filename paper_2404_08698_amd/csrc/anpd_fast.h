@@ -42,6 +42,36 @@ __device__ __forceinline__ void xp_store4(bf16_t *xp, int cls, int m, int k, f32
     *reinterpret_cast<uint2 *>(xp + xp_offset(cls, m, k, 1)) = pl;
 }
 
+// ------------------------------------------------------ fast-path KV cache
+//
+// The fast path keeps K and V in MFMA-fragment order inside each (page, layer,
+// k|v, head) block of 16 tokens x head_dim (page_tokens is 16 on this path):
+//   K: [dim / 32][lane = 16 * ((dim % 32) / 8) + token][dim % 8]     A operand of 16x16x32 (rows = keys)
+//   V: [dim / 16][lane = 16 * (token / 4) + dim % 16][token % 4]     A operand of 16x16x16 (rows = dims)
+// so a wave loads a page's K (and V) tile with fully coalesced reads.
+__host__ __device__ __forceinline__ size_t kvf_base(int page, int layer, int n_layers, int kv, int head, int n_heads,
+                                                    int head_dim)
+{
+    return ((((size_t)page * n_layers + layer) * 2 + kv) * n_heads + head) * ((size_t)16 * head_dim);
+}
+__host__ __device__ __forceinline__ size_t kf_elem(int tok, int dim)
+{
+    return ((size_t)(dim >> 5) * 64 + (size_t)((dim >> 3) & 3) * 16 + tok) * 8 + (dim & 7);
+}
+__host__ __device__ __forceinline__ size_t vf_elem(int tok, int dim)
+{
+    return ((size_t)(dim >> 4) * 64 + (size_t)(tok >> 2) * 16 + (dim & 15)) * 4 + (tok & 3);
+}
+
+// bf16-element offset of q (row m, head, dim, hi|lo) in the packed query operand
+// qp[head][m / 8][dim / 32][lane][8]: groups of 8 window rows in class-8 packing.
+__host__ __device__ __forceinline__ size_t qp_offset(int head, int head_dim, int m, int dim, int lo)
+{
+    const int nksq = head_dim >> 5;
+    return ((((size_t)head * 4 + (m >> 3)) * nksq + (dim >> 5)) * 64 + (size_t)((dim >> 3) & 3) * 16 + (m & 7) + 8 * lo) * 8 +
+           (dim & 7);
+}
+
 // ------------------------------------------------------------------ packing
 
 enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
@@ -103,11 +133,11 @@ struct FastArgs {
     float *Y;             // PLAIN / LOGITS: fp32 [M][ldy]
     int ldy;
     // QKV
-    float *q;             // fp32 [M][d]
+    bf16_t *qp;           // packed split query operand (see qp_offset)
     bf16_t *pool;
     const int32_t *page_table, *len_ptr;
     const float2 *rope;
-    int layer, n_layers, n_heads, head_dim, page_tokens;
+    int layer, n_layers, n_heads, head_dim;
     // RESIDUAL
     float *x;             // residual stream fp32 [M][d], updated in place
     const bf16_t *gain;   // gain of the norm that follows
@@ -175,7 +205,7 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
 #pragma unroll
         for (int i = 0; i < 4; ++i) other[i] = __shfl_xor(y[i], 32, kWave);
         if (!valid) return;
-        const int page = a.page_table[pos / a.page_tokens], tip = pos % a.page_tokens;
+        const int page = a.page_table[pos >> 4], tok = pos & 15;
         if (which < 2) {
             const int tph = a.head_dim / 16, half = a.head_dim / 2;
             const int h = t / tph, j = t - h * tph;
@@ -188,19 +218,26 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
             }
             const int dim = i0 + (kg < 2 ? 0 : half);
             if (which == 0) {
-                *reinterpret_cast<f32x4 *>(a.q + (size_t)m * a.d + h * a.head_dim + dim) = o;
+                bf16_t hi[4], lo[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    hi[i] = f32_to_bf16(o[i]);
+                    lo[i] = f32_to_bf16(o[i] - bf16_to_f32(hi[i]));
+                }
+                *reinterpret_cast<uint2 *>(a.qp + qp_offset(h, a.head_dim, m, dim, 0)) =
+                    make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+                *reinterpret_cast<uint2 *>(a.qp + qp_offset(h, a.head_dim, m, dim, 1)) =
+                    make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
             } else {
-                bf16_t *dst = a.pool + kv_offset(page, a.layer, a.n_layers, 0, h, a.n_heads, tip, a.page_tokens, a.head_dim) + dim;
-                uint2 p = make_uint2((uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16),
-                                     (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16));
-                *reinterpret_cast<uint2 *>(dst) = p;
+                bf16_t *dst = a.pool + kvf_base(page, a.layer, a.n_layers, 0, h, a.n_heads, a.head_dim) + kf_elem(tok, dim);
+                *reinterpret_cast<uint2 *>(dst) = make_uint2((uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16),
+                                                             (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16));
             }
         } else {
             const int n = t * 16 + 4 * kg, h = n / a.head_dim, dim = n - h * a.head_dim;
-            bf16_t *dst = a.pool + kv_offset(page, a.layer, a.n_layers, 1, h, a.n_heads, tip, a.page_tokens, a.head_dim) + dim;
-            uint2 p = make_uint2((uint32_t)f32_to_bf16(y[0]) | ((uint32_t)f32_to_bf16(y[1]) << 16),
-                                 (uint32_t)f32_to_bf16(y[2]) | ((uint32_t)f32_to_bf16(y[3]) << 16));
-            *reinterpret_cast<uint2 *>(dst) = p;
+            bf16_t *dst = a.pool + kvf_base(page, a.layer, a.n_layers, 1, h, a.n_heads, a.head_dim);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dst[vf_elem(tok, dim + i)] = f32_to_bf16(y[i]);
         }
     } else if (EPI == EPI_GATE_UP) {
         const float r = valid ? rinv[m] : 0.f;
@@ -396,6 +433,239 @@ __global__ __launch_bounds__(256) void split_packed_kernel(const float *__restri
     int m = blockIdx.y;
     int k = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (m < M && k < K) xp_store4(xp, cls, m, k, *reinterpret_cast<const f32x4 *>(X + (size_t)m * K + k));
+}
+
+
+typedef short bf16x4s __attribute__((ext_vector_type(4)));
+
+// Window-causal attention on the matrix cores.  Block (head, split) covers
+// kFastSplit = 256 absolute key positions, one 16-token page per wave.  Per
+// group of 8 window rows: S = K q^T with the query as a split-bf16 B operand
+// (scores land with keys in registers and rows across lanes), softmax
+// statistics over the split with the block maximum, P as a split-bf16 B
+// operand straight from those registers, O = V^T P; the 16 waves' tiles are
+// added in a fixed order through LDS.  Each block stores (o, max, denominator)
+// of its split; the last block of a head to finish merges the head's splits
+// in increasing order and writes the packed operand of the output projection.
+// Row r sees keys 0..len + r; keys it must not see get weight exactly 0.
+constexpr int kFastSplit = 256;
+
+template <int DH>
+struct AttnShared {
+    float red[8][8][DH];
+    float wmax[16][8], wden[16][8];
+    float gm[32], gden[32];
+    bool last;
+};
+
+// One (head, split) task; every thread of the 16-wave block calls it.
+template <int DH>
+__device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int split, int L, const uint4 *__restrict__ qp,
+                                          const bf16_t *__restrict__ pool, const int32_t *__restrict__ page_table, int M,
+                                          int layer, int n_layers, int n_heads, int max_splits, float scale,
+                                          float *__restrict__ part, uint32_t *__restrict__ head_counter,
+                                          bf16_t *__restrict__ xp_att, int cls)
+{
+    constexpr int NKS = DH / 32, NDT = DH / 16;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, slot = lane & 15, kg = lane >> 4;
+    const int key0 = split * kFastSplit + wave * 16;
+    const bool active = key0 < L + M;
+
+    uint4 kf[NKS];
+    uint2 vf[NDT];
+#pragma unroll
+    for (int i = 0; i < NKS; ++i) kf[i] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < NDT; ++i) vf[i] = make_uint2(0, 0);
+    if (active) {
+        const int page = page_table[key0 >> 4];
+        const uint4 *kp = reinterpret_cast<const uint4 *>(pool + kvf_base(page, layer, n_layers, 0, head, n_heads, DH)) + lane;
+        const uint2 *vp = reinterpret_cast<const uint2 *>(pool + kvf_base(page, layer, n_layers, 1, head, n_heads, DH)) + lane;
+#pragma unroll
+        for (int i = 0; i < NKS; ++i) kf[i] = ld_coherent(kp + i * 64);
+#pragma unroll
+        for (int i = 0; i < NDT; ++i) vf[i] = ld_coherent(vp + i * 64);
+    }
+
+    for (int rg = 0; rg * 8 < M; ++rg) {
+        // ---- scores S[key][row]
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        const uint4 *q = qp + ((size_t)(head * 4 + rg) * NKS) * 64 + lane;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[ks]),
+                                                          __builtin_bit_cast(bf16x8, ld_coherent(q + ks * 64)), acc, 0, 0, 0);
+        const int m = rg * 8 + (slot & 7);
+        float sc[4], mx = kMasked;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float lo = __shfl_down(acc[i], 8, kWave);
+            const int key = key0 + 4 * kg + i;
+            const bool ok = active && slot < 8 && m < M && key <= L + m;
+            sc[i] = ok ? (acc[i] + lo) * scale : kMasked;
+            mx = fmaxf(mx, sc[i]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        if (kg == 0 && slot < 8) sh.wmax[wave][slot] = mx;
+        __syncthreads();
+        float bm = sh.wmax[0][slot & 7];
+#pragma unroll
+        for (int w = 1; w < 16; ++w) bm = fmaxf(bm, sh.wmax[w][slot & 7]);
+        // ---- exponentials, denominators, P operand (hi rows in slots 0..7, lo rows in 8..15)
+        float p[4], den = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            p[i] = (slot < 8 && sc[i] > 0.5f * kMasked) ? expf(sc[i] - bm) : 0.f;
+            den += p[i];
+        }
+        den += __shfl_xor(den, 16, kWave);
+        den += __shfl_xor(den, 32, kWave);
+        if (kg == 0 && slot < 8) sh.wden[wave][slot] = den;
+        bf16x4s pb;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float up = __shfl_up(p[i], 8, kWave);
+            float pv = slot < 8 ? p[i] : up;
+            bf16_t hi = f32_to_bf16(pv);
+            bf16_t o = slot < 8 ? hi : f32_to_bf16(pv - bf16_to_f32(hi));
+            pb[i] = (short)o;
+        }
+        // ---- O[dim][row] = V^T P, one 16-dim tile at a time
+        f32x4 ot[NDT];
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt) {
+            f32x4 o = {0.f, 0.f, 0.f, 0.f};
+            o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4s, vf[dt]), pb, o, 0, 0, 0);
+            f32x4 lo;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) lo[i] = __shfl_down(o[i], 8, kWave);
+            ot[dt] = o + lo;
+        }
+        // ---- add the 16 waves' tiles: wave w + 8 into wave w, then waves 0..7 in order
+        if (wave >= 8 && slot < 8) {
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt) *reinterpret_cast<f32x4 *>(&sh.red[wave - 8][slot][16 * dt + 4 * kg]) = ot[dt];
+        }
+        __syncthreads();
+        if (wave < 8 && slot < 8) {
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt) ot[dt] += *reinterpret_cast<const f32x4 *>(&sh.red[wave][slot][16 * dt + 4 * kg]);
+        }
+        __syncthreads();
+        if (wave < 8 && slot < 8) {
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt) *reinterpret_cast<f32x4 *>(&sh.red[wave][slot][16 * dt + 4 * kg]) = ot[dt];
+        }
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < 8 * DH; idx += 1024) {
+            const int mm = idx / DH, e = idx - mm * DH, row = rg * 8 + mm;
+            if (row < M) {
+                float o = sh.red[0][mm][e];
+#pragma unroll
+                for (int w = 1; w < 8; ++w) o += sh.red[w][mm][e];
+                st_agent(part + (((size_t)head * max_splits + split) * 32 + row) * (DH + 2) + e, o);
+            }
+        }
+        if (threadIdx.x < 8 && rg * 8 + threadIdx.x < M) {
+            const int mm = threadIdx.x;
+            size_t b2 = (((size_t)head * max_splits + split) * 32 + rg * 8 + mm) * (DH + 2) + DH;
+            float bmx = sh.wmax[0][mm], dsum = sh.wden[0][mm];
+#pragma unroll
+            for (int w = 1; w < 16; ++w) { bmx = fmaxf(bmx, sh.wmax[w][mm]); dsum += sh.wden[w][mm]; }
+            st_agent(part + b2, bmx);
+            st_agent(part + b2 + 1, dsum);
+        }
+        __syncthreads();
+    }
+
+    // ---- the last block of this head merges the splits
+    wait_stores();
+    __syncthreads();
+    const int n_blocks = (L + M + kFastSplit - 1) / kFastSplit;
+    if (threadIdx.x == 0)
+        sh.last = __hip_atomic_fetch_add(&head_counter[head], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                  (uint32_t)(n_blocks - 1);
+    __syncthreads();
+    if (!sh.last) return;
+    if (threadIdx.x == 0) st_agent(&head_counter[head], 0u);
+    const float *ph = part + ((size_t)head * max_splits) * 32 * (DH + 2);
+    const size_t stride = (size_t)32 * (DH + 2);
+    // global maximum and denominator of every row: wave w takes rows w, w + 16; lanes stride over the splits
+    for (int row = wave; row < M; row += 16) {
+        const int ns = (L + row) / kFastSplit + 1;
+        const float *pr = ph + (size_t)row * (DH + 2);
+        float g = kMasked;
+        for (int s2 = lane; s2 < ns; s2 += 64) g = fmaxf(g, ld_agent(pr + s2 * stride + DH));
+        g = wave_max(g);
+        float dsum = 0.f;
+        for (int s2 = lane; s2 < ns; s2 += 64)
+            dsum += expf(ld_agent(pr + s2 * stride + DH) - g) * ld_agent(pr + s2 * stride + DH + 1);
+        dsum = wave_sum(dsum);
+        if (lane == 0) { sh.gm[row] = g; sh.gden[row] = dsum; }
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < M * DH; idx += 1024) {
+        const int row = idx / DH, e = idx - row * DH;
+        const int ns = (L + row) / kFastSplit + 1;
+        const float *pr = ph + (size_t)row * (DH + 2);
+        const float g = sh.gm[row];
+        float o = 0.f;
+        for (int s0 = 0; s0 < ns; s0 += 4) {
+            float ov[4], bv[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool okj = s0 + j < ns;
+                ov[j] = okj ? ld_agent(pr + (s0 + j) * stride + e) : 0.f;
+                bv[j] = okj ? ld_agent(pr + (s0 + j) * stride + DH) : kMasked;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (s0 + j < ns) o = fmaf(expf(bv[j] - g), ov[j], o);
+        }
+        const float v = o / sh.gden[row];
+        const bf16_t hi = f32_to_bf16(v);
+        xp_att[xp_offset(cls, row, head * DH + e, 0)] = hi;
+        xp_att[xp_offset(cls, row, head * DH + e, 1)] = f32_to_bf16(v - bf16_to_f32(hi));
+    }
+}
+
+// grid: (n_heads, ceil((len + M) / 256)), 16 waves.
+template <int DH>
+__global__ __launch_bounds__(1024) void attn_fast_kernel(const uint4 *__restrict__ qp, const bf16_t *__restrict__ pool,
+                                                          const int32_t *__restrict__ page_table,
+                                                          const int32_t *__restrict__ len_ptr, int M, int layer, int n_layers,
+                                                          int n_heads, int max_splits, float scale, float *__restrict__ part,
+                                                          uint32_t *__restrict__ head_counter, bf16_t *__restrict__ xp_att,
+                                                          int cls)
+{
+    __shared__ AttnShared<DH> sh;
+    const int L = *len_ptr;
+    if ((int)blockIdx.y * kFastSplit >= L + M) return;
+    attn_task<DH>(sh, blockIdx.x, blockIdx.y, L, qp, pool, page_table, M, layer, n_layers, n_heads, max_splits, scale, part,
+                  head_counter, xp_att, cls);
+}
+
+// Copies n positions of one layer between fp32 [n][d] arrays and the fast-path cache layout.
+template <bool TO_CACHE>
+__global__ __launch_bounds__(256) void kvf_copy_kernel(bf16_t *__restrict__ pool, const int32_t *__restrict__ page_table,
+                                                        float *__restrict__ k, float *__restrict__ v, int pos0, int layer,
+                                                        int n_layers, int n_heads, int head_dim)
+{
+    const int r = blockIdx.x, pos = pos0 + r, d = n_heads * head_dim;
+    const int page = page_table[pos >> 4], tok = pos & 15;
+    for (int e = threadIdx.x; e < d; e += 256) {
+        int hd = e / head_dim, dim = e - hd * head_dim;
+        size_t ko = kvf_base(page, layer, n_layers, 0, hd, n_heads, head_dim) + kf_elem(tok, dim);
+        size_t vo = kvf_base(page, layer, n_layers, 1, hd, n_heads, head_dim) + vf_elem(tok, dim);
+        if (TO_CACHE) {
+            pool[ko] = f32_to_bf16(k[(size_t)r * d + e]);
+            pool[vo] = f32_to_bf16(v[(size_t)r * d + e]);
+        } else {
+            k[(size_t)r * d + e] = bf16_to_f32(pool[ko]);
+            v[(size_t)r * d + e] = bf16_to_f32(pool[vo]);
+        }
+    }
 }
 
 }  // namespace anpd

@@ -57,6 +57,22 @@ __device__ __forceinline__ void load8(const bf16_t *p, float (&o)[8])
     o[6] = __uint_as_float(r.w << 16); o[7] = __uint_as_float(r.w & 0xffff0000u);
 }
 
+// Device-coherent accesses (relaxed, agent scope): the store is written through and the load is
+// served from the coherence point, so blocks on different XCDs can hand small results to each
+// other through a counter without cache-wide write-back / invalidate fences.
+template <typename T>
+__device__ __forceinline__ void st_agent(T *p, T v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+template <typename T>
+__device__ __forceinline__ T ld_agent(const T *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+// Plain vector loads for data that another block may have written earlier in the same kernel
+// launch sequence.  Kernel boundaries make ordinary loads coherent, so this is an ordinary load.
+template <typename T>
+__device__ __forceinline__ T ld_coherent(const T *p) { return *p; }
+
+// Wait until this wave's outstanding global stores have been acknowledged.
+__device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll
@@ -437,24 +453,23 @@ __global__ __launch_bounds__(1024) void argmax_accept_kernel(const float *__rest
     if (threadIdx.x == 0) {
         for (int w = 1; w < 16; ++w)
             if (bv[w] > best || (bv[w] == best && bi[w] < besti)) { best = bv[w]; besti = bi[w]; }
-        result[2 + r] = besti;
-        __threadfence();
-        last = (atomicAdd(counter, 1u) == (uint32_t)(M - 1));
+        st_agent(result + 2 + r, (int32_t)besti);
+        wait_stores();
+        last = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)(M - 1);
     }
     __syncthreads();
     if (last && threadIdx.x == 0) {
-        __threadfence();
-        volatile int32_t *pred = result + 2;
+        const int32_t *pred = result + 2;
         int a = 0;
         if (mode == 0) {
-            while (a < M - 1 && window[a + 1] == pred[a]) ++a;
+            while (a < M - 1 && window[a + 1] == ld_agent(pred + a)) ++a;
         } else {
             a = M - 1;
         }
         result[0] = a;
-        result[1] = pred[a];
+        result[1] = ld_agent(pred + a);
         *len_ptr += 1 + a;
-        *counter = 0u;
+        st_agent(counter, 0u);
     }
 }
 
