@@ -270,7 +270,7 @@ __device__ __forceinline__ void reduce_and_finish(const FastArgs &a, int tile, c
     if (NT == 1) {
         f32x4 lo;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) lo[i] = __shfl_down(tot[0][i], 8, kWave);
+        for (int i = 0; i < 4; ++i) lo[i] = row_down8(tot[0][i]);
         epilogue<EPI>(a, tile, slot, kg, tot[0] + lo, slot < 8 && slot < a.M, rinv);
     } else {
 #pragma unroll
@@ -450,9 +450,16 @@ typedef short bf16x4s __attribute__((ext_vector_type(4)));
 // Row r sees keys 0..len + r; keys it must not see get weight exactly 0.
 constexpr int kFastSplit = 256;
 
+#ifdef ANPD_TIMING
+__device__ long long *g_anpd_dbg = nullptr;
+#define ANPD_STAMP(i) do { if (g_anpd_dbg && threadIdx.x == 0) g_anpd_dbg[(blockIdx.y * gridDim.x + blockIdx.x) * 16 + (i)] = wall_clock64(); } while (0)
+#else
+#define ANPD_STAMP(i) do { } while (0)
+#endif
+
 template <int DH>
 struct AttnShared {
-    float red[8][8][DH];
+    float red[8][DH / 16][32][4];
     float wmax[16][8], wden[16][8];
     float gm[32], gden[32];
     bool last;
@@ -470,6 +477,7 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, slot = lane & 15, kg = lane >> 4;
     const int key0 = split * kFastSplit + wave * 16;
     const bool active = key0 < L + M;
+    ANPD_STAMP(0);
 
     uint4 kf[NKS];
     uint2 vf[NDT];
@@ -499,7 +507,7 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
         float sc[4], mx = kMasked;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            float lo = __shfl_down(acc[i], 8, kWave);
+            float lo = row_down8(acc[i]);
             const int key = key0 + 4 * kg + i;
             const bool ok = active && slot < 8 && m < M && key <= L + m;
             sc[i] = ok ? (acc[i] + lo) * scale : kMasked;
@@ -509,6 +517,7 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
         mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
         if (kg == 0 && slot < 8) sh.wmax[wave][slot] = mx;
         __syncthreads();
+        ANPD_STAMP(1);
         float bm = sh.wmax[0][slot & 7];
 #pragma unroll
         for (int w = 1; w < 16; ++w) bm = fmaxf(bm, sh.wmax[w][slot & 7]);
@@ -522,10 +531,11 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
         den += __shfl_xor(den, 16, kWave);
         den += __shfl_xor(den, 32, kWave);
         if (kg == 0 && slot < 8) sh.wden[wave][slot] = den;
+        ANPD_STAMP(7);
         bf16x4s pb;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            float up = __shfl_up(p[i], 8, kWave);
+            float up = row_up8(p[i]);
             float pv = slot < 8 ? p[i] : up;
             bf16_t hi = f32_to_bf16(pv);
             bf16_t o = slot < 8 ? hi : f32_to_bf16(pv - bf16_to_f32(hi));
@@ -539,32 +549,35 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
             o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4s, vf[dt]), pb, o, 0, 0, 0);
             f32x4 lo;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) lo[i] = __shfl_down(o[i], 8, kWave);
+            for (int i = 0; i < 4; ++i) lo[i] = row_down8(o[i]);
             ot[dt] = o + lo;
         }
-        // ---- add the 16 waves' tiles: wave w + 8 into wave w, then waves 0..7 in order
+        // ---- add the 16 waves' tiles: wave w + 8 into wave w, then waves 0..7 in order (one dim tile
+        // per wave).  LDS is addressed by compacted lane (kg * 8 + slot), i.e. linearly.
+        const int cl = kg * 8 + (slot & 7);
         if (wave >= 8 && slot < 8) {
 #pragma unroll
-            for (int dt = 0; dt < NDT; ++dt) *reinterpret_cast<f32x4 *>(&sh.red[wave - 8][slot][16 * dt + 4 * kg]) = ot[dt];
+            for (int dt = 0; dt < NDT; ++dt) *reinterpret_cast<f32x4 *>(&sh.red[wave - 8][dt][cl][0]) = ot[dt];
         }
         __syncthreads();
         if (wave < 8 && slot < 8) {
 #pragma unroll
-            for (int dt = 0; dt < NDT; ++dt) ot[dt] += *reinterpret_cast<const f32x4 *>(&sh.red[wave][slot][16 * dt + 4 * kg]);
+            for (int dt = 0; dt < NDT; ++dt) {
+                f32x4 *r = reinterpret_cast<f32x4 *>(&sh.red[wave][dt][cl][0]);
+                *r = ot[dt] + *r;
+            }
         }
         __syncthreads();
-        if (wave < 8 && slot < 8) {
+        ANPD_STAMP(9);
+        if (wave < NDT && slot < 8) {
+            const int row = rg * 8 + slot;
+            f32x4 tot = *reinterpret_cast<const f32x4 *>(&sh.red[0][wave][cl][0]);
 #pragma unroll
-            for (int dt = 0; dt < NDT; ++dt) *reinterpret_cast<f32x4 *>(&sh.red[wave][slot][16 * dt + 4 * kg]) = ot[dt];
-        }
-        __syncthreads();
-        for (int idx = threadIdx.x; idx < 8 * DH; idx += 1024) {
-            const int mm = idx / DH, e = idx - mm * DH, row = rg * 8 + mm;
+            for (int w = 1; w < 8; ++w) tot += *reinterpret_cast<const f32x4 *>(&sh.red[w][wave][cl][0]);
             if (row < M) {
-                float o = sh.red[0][mm][e];
+                float *dst = part + (((size_t)head * max_splits + split) * 32 + row) * (DH + 2) + 16 * wave + 4 * kg;
 #pragma unroll
-                for (int w = 1; w < 8; ++w) o += sh.red[w][mm][e];
-                st_agent(part + (((size_t)head * max_splits + split) * 32 + row) * (DH + 2) + e, o);
+                for (int i = 0; i < 4; ++i) st_agent(dst + i, tot[i]);
             }
         }
         if (threadIdx.x < 8 && rg * 8 + threadIdx.x < M) {
@@ -576,17 +589,22 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
             st_agent(part + b2, bmx);
             st_agent(part + b2 + 1, dsum);
         }
+        ANPD_STAMP(10);
         __syncthreads();
+        ANPD_STAMP(11);
     }
 
     // ---- the last block of this head merges the splits
+    ANPD_STAMP(2);
     wait_stores();
     __syncthreads();
+    ANPD_STAMP(3);
     const int n_blocks = (L + M + kFastSplit - 1) / kFastSplit;
     if (threadIdx.x == 0)
         sh.last = __hip_atomic_fetch_add(&head_counter[head], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
                   (uint32_t)(n_blocks - 1);
     __syncthreads();
+    ANPD_STAMP(4);
     if (!sh.last) return;
     if (threadIdx.x == 0) st_agent(&head_counter[head], 0u);
     const float *ph = part + ((size_t)head * max_splits) * 32 * (DH + 2);
@@ -605,6 +623,7 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
         if (lane == 0) { sh.gm[row] = g; sh.gden[row] = dsum; }
     }
     __syncthreads();
+    ANPD_STAMP(5);
     for (int idx = threadIdx.x; idx < M * DH; idx += 1024) {
         const int row = idx / DH, e = idx - row * DH;
         const int ns = (L + row) / kFastSplit + 1;
@@ -628,6 +647,7 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
         xp_att[xp_offset(cls, row, head * DH + e, 0)] = hi;
         xp_att[xp_offset(cls, row, head * DH + e, 1)] = f32_to_bf16(v - bf16_to_f32(hi));
     }
+    ANPD_STAMP(6);
 }
 
 // grid: (n_heads, ceil((len + M) / 256)), 16 waves.

@@ -73,6 +73,17 @@ __device__ __forceinline__ T ld_coherent(const T *p) { return *p; }
 // Wait until this wave's outstanding global stores have been acknowledged.
 __device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// Value of lane + 8 / lane - 8 within each row of 16 lanes, as a DPP move on the vector ALU
+// (no trip through the LDS crossbar).  Lanes whose source falls outside the row read 0.
+__device__ __forceinline__ float row_down8(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x108, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float row_up8(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x118, 0xF, 0xF, true));
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll
