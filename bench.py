@@ -46,7 +46,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="llama7b", choices=["tiny", "llama7b", "llama13b", "long7b"])
-    ap.add_argument("--gemm-path", default="auto", choices=["auto", "dot", "mfma"])
+    ap.add_argument("--gemm-path", default="auto", choices=["auto", "dot", "mfma", "launches"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=2)
     args = ap.parse_args()
@@ -68,7 +68,7 @@ def main() -> int:
     shape = wl["shape"]
     K, n_min, n_max = wl["k"], wl["n_min"], wl["n_max"]
     prompt = synth.workload_prompt(args.workload)
-    path = {"auto": B.GEMM_AUTO, "dot": B.GEMM_DOT, "mfma": B.GEMM_MFMA}[args.gemm_path]
+    path = {"auto": B.GEMM_AUTO, "dot": B.GEMM_DOT, "mfma": B.GEMM_MFMA, "launches": B.GEMM_MFMA_LAUNCHES}[args.gemm_path]
     gen = wl["gen"]
     max_tokens = len(prompt) + gen + 2 * (K + 2) + 32
 

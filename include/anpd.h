@@ -49,8 +49,11 @@ enum { ANPD_VERIFY = 0, ANPD_APPEND = 1 };          /* anpd_verify modes */
 /* GEMM forms.  DOT: wavefront dot products on the caller's row-major weights (any dtype).
  * MFMA: matrix cores on bf16 weights repacked into fragment order.  MFMA_STREAM (anpd_linear
  * only) forces the MFMA form that streams the activation operand instead of holding it in
- * registers; both MFMA forms give bit-identical results. */
-enum { ANPD_GEMM_AUTO = 0, ANPD_GEMM_DOT = 1, ANPD_GEMM_MFMA = 2, ANPD_GEMM_MFMA_STREAM = 3 };
+ * registers; both MFMA forms give bit-identical results.  With MFMA, windows of up to 8 rows
+ * run as ONE persistent kernel per step when the model allows it (d_model <= 4096);
+ * MFMA_LAUNCHES (model option) keeps the same arithmetic as one launch per operation. */
+enum { ANPD_GEMM_AUTO = 0, ANPD_GEMM_DOT = 1, ANPD_GEMM_MFMA = 2, ANPD_GEMM_MFMA_STREAM = 3,
+       ANPD_GEMM_MFMA_LAUNCHES = 4 };
 
 #define ANPD_MAX_WINDOW 32
 
@@ -200,11 +203,18 @@ int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32
  * ANPD_PROF_NCAT entries; *out_steps: steps accumulated. */
 enum {
     ANPD_PROF_GEMM_QKV = 0, ANPD_PROF_GEMM_O, ANPD_PROF_GEMM_GATE_UP, ANPD_PROF_GEMM_DOWN,
-    ANPD_PROF_GEMM_LM_HEAD, ANPD_PROF_ATTN, ANPD_PROF_OTHER, ANPD_PROF_NCAT
+    ANPD_PROF_GEMM_LM_HEAD, ANPD_PROF_ATTN, ANPD_PROF_OTHER, ANPD_PROF_STEP /* the one-kernel step */,
+    ANPD_PROF_NCAT
 };
 int32_t anpd_model_profile(anpd_model_t *m, int32_t enable);
 int32_t anpd_model_profile_read(const anpd_model_t *m, double *out_ms, int64_t *out_launches,
                                 int64_t *out_steps);
+
+/* Barrier-level trace of the one-kernel step.  buffer: DEVICE, grid * 1024 int64 (NULL switches the
+ * trace off).  While set, block b stores 100 MHz timestamps at buffer[b * 1024 + e]: e = 0 kernel
+ * start, then for every grid barrier the moment the block arrives and the moment its wait ends.
+ * Returns the grid size (0 if this model does not use the one-kernel step). */
+int32_t anpd_model_trace(anpd_model_t *m, void *buffer, size_t bytes);
 
 /* The dominant kernel on its own, for per-kernel parity and bandwidth
  * measurement: Y[M][N] = X[M][K] * W[N][K]^T with fp32 accumulation.

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "libanpd.so")
 OK, E_INVAL, E_RANGE, E_CAPACITY, E_NOMEM, E_HIP, E_UNIMPLEMENTED = 0, -1, -2, -3, -4, -5, -6
 F32, BF16 = 0, 1
 VERIFY, APPEND = 0, 1
-GEMM_AUTO, GEMM_DOT, GEMM_MFMA, GEMM_MFMA_STREAM = 0, 1, 2, 3
+GEMM_AUTO, GEMM_DOT, GEMM_MFMA, GEMM_MFMA_STREAM, GEMM_MFMA_LAUNCHES = 0, 1, 2, 3, 4
 MAX_WINDOW = 32
 
 _PER_LAYER = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
@@ -32,8 +32,9 @@ EXPORTS = (
     "anpd_kv_set_page_order", "anpd_kv_num_pages", "anpd_kv_write", "anpd_kv_read",
     "anpd_verify", "anpd_linear_workspace_bytes", "anpd_linear",
     "anpd_model_profile", "anpd_model_profile_read", "anpd_packed_bytes", "anpd_pack_weights",
+    "anpd_model_trace",
 )
-PROF_CATEGORIES = ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "attn", "other")
+PROF_CATEGORIES = ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "attn", "other", "step")
 
 
 class AnpdError(RuntimeError):
@@ -118,6 +119,8 @@ def lib():
     L.anpd_packed_bytes.argtypes = [C.c_int32, C.c_int32]
     L.anpd_pack_weights.restype = C.c_int32
     L.anpd_pack_weights.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_size_t, vp]
+    L.anpd_model_trace.restype = C.c_int32
+    L.anpd_model_trace.argtypes = [vp, vp, C.c_size_t]
     L.anpd_model_profile.restype = C.c_int32
     L.anpd_model_profile.argtypes = [vp, C.c_int32]
     L.anpd_model_profile_read.restype = C.c_int32
@@ -224,6 +227,20 @@ class Model:
         if getattr(self, "_h", None):
             lib().anpd_model_destroy(self._h)
             self._h = None
+
+    def trace(self, enable: bool):
+        """Barrier timestamps of the one-kernel step: returns an int64 CUDA tensor [grid][1024] (or None)."""
+        import torch
+        if not enable:
+            _check(lib().anpd_model_trace(self._h, None, 0))
+            self._trace = None
+            return None
+        grid = _check(lib().anpd_model_trace(self._h, None, 0))
+        if grid == 0:
+            return None
+        self._trace = torch.zeros(grid, 1024, dtype=torch.int64, device=self.device)
+        _check(lib().anpd_model_trace(self._h, self._trace.data_ptr(), self._trace.numel() * 8))
+        return self._trace
 
     def profile(self, enable: bool) -> None:
         _check(lib().anpd_model_profile(self._h, 1 if enable else 0))

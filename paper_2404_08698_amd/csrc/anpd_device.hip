@@ -15,6 +15,7 @@
 #include "anpd_common.h"
 #include "anpd_kernels.h"
 #include "anpd_fast.h"
+#include "anpd_mega.h"
 
 using namespace anpd;
 
@@ -31,14 +32,15 @@ size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 struct Layout {  // byte offsets into the model workspace
     size_t rope_tab, tok, result, counter, x, h, y, qkv, att, gu, a, logits, part;
     // fast path: packed operands, partial sums of squares, packed weights
-    size_t xp_d, xp_att, xp_f, ssp_a, ssp_b, qp, head_ctr, wp_lm, total;
+    size_t xp_d, xp_att, xp_f, ssp_a, ssp_b, qp, head_ctr, layer_tab, amax, row_ctr, bar, err, wp_lm, total;
     std::vector<size_t> wp_qkv, wp_o, wp_gu, wp_down;
     int max_splits;
 };
 
 bool wants_mfma(const anpd_model_cfg *c)
 {
-    return c->gemm_path == ANPD_GEMM_MFMA || (c->gemm_path == ANPD_GEMM_AUTO && c->dtype == ANPD_BF16);
+    return c->gemm_path == ANPD_GEMM_MFMA || c->gemm_path == ANPD_GEMM_MFMA_LAUNCHES ||
+           (c->gemm_path == ANPD_GEMM_AUTO && c->dtype == ANPD_BF16);
 }
 
 size_t packed_bytes(size_t n_tiles, int K) { return n_tiles * (size_t)((K + 31) / 32) * 1024; }
@@ -57,8 +59,10 @@ bool cfg_ok(const anpd_model_cfg *c, const char **why)
     REQ(c->page_tokens >= 8 && c->page_tokens <= 256 && (c->page_tokens & (c->page_tokens - 1)) == 0, "page_tokens must be a power of two in 8..256");
     REQ(c->max_window >= 1 && c->max_window <= ANPD_MAX_WINDOW, "max_window must be in 1..ANPD_MAX_WINDOW");
     REQ(c->max_positions >= 1 && c->max_positions <= (1 << 20), "max_positions must be in 1..2^20");
-    REQ(c->gemm_path >= ANPD_GEMM_AUTO && c->gemm_path <= ANPD_GEMM_MFMA, "unknown gemm_path");
-    REQ(!(c->gemm_path == ANPD_GEMM_MFMA && c->dtype != ANPD_BF16), "the MFMA path needs bf16 weights");
+    REQ(c->gemm_path == ANPD_GEMM_AUTO || c->gemm_path == ANPD_GEMM_DOT || c->gemm_path == ANPD_GEMM_MFMA ||
+            c->gemm_path == ANPD_GEMM_MFMA_LAUNCHES, "unknown gemm_path");
+    REQ(!((c->gemm_path == ANPD_GEMM_MFMA || c->gemm_path == ANPD_GEMM_MFMA_LAUNCHES) && c->dtype != ANPD_BF16),
+        "the MFMA path needs bf16 weights");
     REQ(c->rms_eps > 0.f && c->rope_base > 1.f, "rms_eps / rope_base out of range");
     REQ(!(wants_mfma(c) && c->page_tokens != 16), "the MFMA path needs page_tokens == 16");
 #undef REQ
@@ -86,6 +90,7 @@ Layout make_layout(const anpd_model_cfg *c)
     L.logits = take(MW * V * 4);
     L.part = take((size_t)c->n_heads * L.max_splits * (wants_mfma(c) ? 32 : MW) * (c->head_dim + 2) * 4);
     L.xp_d = L.xp_att = L.xp_f = L.ssp_a = L.ssp_b = L.qp = L.head_ctr = L.wp_lm = 0;
+    L.layer_tab = L.amax = L.row_ctr = L.bar = L.err = 0;
     if (wants_mfma(c)) {
         L.xp_d = take(((d + 31) / 32) * 4 * 1024);
         L.xp_att = take(((d + 31) / 32) * 4 * 1024);
@@ -94,6 +99,11 @@ Layout make_layout(const anpd_model_cfg *c)
         L.ssp_b = take((d / 16) * 32 * 4);
         L.qp = take((size_t)c->n_heads * 4 * (c->head_dim / 32) * 1024);
         L.head_ctr = take((size_t)c->n_heads * sizeof(uint32_t));
+        L.layer_tab = take((size_t)c->n_layers * sizeof(LayerW));
+        L.amax = take((V / 16) * 32 * sizeof(unsigned long long));
+        L.row_ctr = take(sizeof(uint32_t));
+        L.bar = take(kBarStride * 9 * sizeof(uint32_t));
+        L.err = take(sizeof(int32_t));
         L.wp_lm = take(packed_bytes(V / 16, (int)d));
         for (int l = 0; l < c->n_layers; ++l) {
             L.wp_qkv.push_back(take(packed_bytes(3 * d / 16, (int)d)));
@@ -114,6 +124,10 @@ struct anpd_model {
     char *ws;
     bool mfma;
     int n_cu;
+    bool mega;            // the one-kernel step is available
+    long long *trace;     // optional device buffer for barrier timestamps
+    int mega_grid;
+    uint32_t bar_epoch;
     const void *embed, *final_norm, *lm_head;
     std::vector<const void *> attn_norm, wq, wk, wv, wo, ffn_norm, w_gate, w_up, w_down;
     int32_t *pin;  // pinned host staging: [0..32) window, [32..66) result
@@ -171,13 +185,13 @@ template <int EPI>
 int32_t launch_fast(FastArgs &a, int n_cu, bool force_stream, hipStream_t st)
 {
     const int kpw = (a.nks + kFastWaves - 1) / kFastWaves;
-    if (a.cls == 8 && kpw <= 10 && !force_stream) {
+    if (a.cls == 8 && kpw <= 20 && !force_stream) {
         dim3 grid((unsigned)(a.n_tiles < n_cu ? a.n_tiles : n_cu)), block(kFastWaves * 64);
-        if (kpw <= 1) hipLaunchKernelGGL((gemm_xs_kernel<1, EPI>), grid, block, 0, st, a);
-        else if (kpw <= 2) hipLaunchKernelGGL((gemm_xs_kernel<2, EPI>), grid, block, 0, st, a);
+        if (kpw <= 2) hipLaunchKernelGGL((gemm_xs_kernel<2, EPI>), grid, block, 0, st, a);
         else if (kpw <= 4) hipLaunchKernelGGL((gemm_xs_kernel<4, EPI>), grid, block, 0, st, a);
         else if (kpw <= 8) hipLaunchKernelGGL((gemm_xs_kernel<8, EPI>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((gemm_xs_kernel<10, EPI>), grid, block, 0, st, a);
+        else if (kpw <= 16) hipLaunchKernelGGL((gemm_xs_kernel<16, EPI>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((gemm_xs_kernel<20, EPI>), grid, block, 0, st, a);
     } else {
         dim3 grid((unsigned)a.n_tiles), block(kFastWaves * 64);
         const int nt = a.cls / 8;
@@ -386,11 +400,11 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
         }
         mark(m, ANPD_PROF_GEMM_QKV, st);
         if (dh == 128)
-            hipLaunchKernelGGL((attn_fast_kernel<128>), dim3(H, n_splits), dim3(1024), 0, st, (const uint4 *)qp,
+            hipLaunchKernelGGL((attn_fast_kernel<128>), dim3(H, n_splits), dim3(kFastThreads), 0, st, (const uint4 *)qp,
                                (const bf16_t *)kv->pool, kv->d_table, kv->d_len, M, l, c.n_layers, H, L.max_splits, scale, part,
                                head_ctr, xp_att, cls);
         else
-            hipLaunchKernelGGL((attn_fast_kernel<64>), dim3(H, n_splits), dim3(1024), 0, st, (const uint4 *)qp,
+            hipLaunchKernelGGL((attn_fast_kernel<64>), dim3(H, n_splits), dim3(kFastThreads), 0, st, (const uint4 *)qp,
                                (const bf16_t *)kv->pool, kv->d_table, kv->d_len, M, l, c.n_layers, H, L.max_splits, scale, part,
                                head_ctr, xp_att, cls);
         mark(m, ANPD_PROF_ATTN, st);
@@ -446,6 +460,51 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
                        counter);
     mark(m, ANPD_PROF_OTHER, st);
     HIP_TRY(hipGetLastError());
+    return ANPD_OK;
+}
+
+// The step as one persistent kernel (window class 8).
+int32_t run_step_mega(anpd_model *m, anpd_kv *kv, int M, int mode, bool want_logits, hipStream_t st)
+{
+    const anpd_model_cfg &c = m->cfg;
+    const Layout &L = m->lay;
+    char *ws = m->ws;
+    MegaArgs g;
+    std::memset(&g, 0, sizeof(g));
+    g.layers = (const LayerW *)(ws + L.layer_tab);
+    g.n_layers = c.n_layers;
+    g.wp_lm = (const uint4 *)(ws + L.wp_lm);
+    g.final_gain = (const bf16_t *)m->final_norm;
+    g.embed = (const bf16_t *)m->embed;
+    g.d = c.d_model; g.F = c.d_ffn; g.V = c.vocab; g.n_heads = c.n_heads; g.head_dim = c.head_dim;
+    g.M = M; g.mode = mode;
+    g.inv_d = 1.0f / (float)c.d_model; g.eps = c.rms_eps; g.scale = 1.0f / sqrtf((float)c.head_dim);
+    g.x = (float *)(ws + L.x);
+    g.xp_d = (bf16_t *)(ws + L.xp_d); g.xp_att = (bf16_t *)(ws + L.xp_att); g.xp_f = (bf16_t *)(ws + L.xp_f);
+    g.qp = (bf16_t *)(ws + L.qp);
+    g.ssp_a = (float *)(ws + L.ssp_a); g.ssp_b = (float *)(ws + L.ssp_b); g.part = (float *)(ws + L.part);
+    g.head_counter = (uint32_t *)(ws + L.head_ctr);
+    g.pool = (bf16_t *)kv->pool; g.page_table = kv->d_table; g.len_ptr = kv->d_len;
+    g.rope = (const float2 *)(ws + L.rope_tab);
+    g.max_splits = L.max_splits;
+    g.logits = want_logits ? (float *)(ws + L.logits) : nullptr;
+    g.amax = (unsigned long long *)(ws + L.amax);
+    g.tok = (const int32_t *)(ws + L.tok);
+    g.result = (int32_t *)(ws + L.result);
+    g.row_counter = (uint32_t *)(ws + L.row_ctr);
+    g.bar = (uint32_t *)(ws + L.bar);
+    g.bar_epoch = m->bar_epoch;
+    g.error = (int32_t *)(ws + L.err);
+    g.trace = m->trace;
+    m->ev_used = 0;
+    mark(m, -1, st);
+    void *args[] = {&g};
+    if (c.head_dim == 128)
+        HIP_TRY(hipLaunchCooperativeKernel((const void *)verify_mega_kernel<128>, dim3((unsigned)m->mega_grid), dim3(kFastThreads), args, 0, st));
+    else
+        HIP_TRY(hipLaunchCooperativeKernel((const void *)verify_mega_kernel<64>, dim3((unsigned)m->mega_grid), dim3(kFastThreads), args, 0, st));
+    m->bar_epoch += (uint32_t)kMegaBarriers(c.n_layers);
+    mark(m, ANPD_PROF_STEP, st);
     return ANPD_OK;
 }
 
@@ -528,6 +587,34 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
     e = hipMemsetAsync(m->ws, 0, m->mfma ? lay.wp_lm : lay.total, st);
     if (e == hipSuccess) e = hipMemcpyAsync(m->ws + lay.rope_tab, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice, st);
     int32_t prc = ANPD_OK;
+    m->mega = false;
+    m->trace = nullptr;
+    m->mega_grid = 0;
+    m->bar_epoch = 0;
+    if (e == hipSuccess && m->mfma && cfg->gemm_path != ANPD_GEMM_MFMA_LAUNCHES && (cfg->d_model + 31) / 32 <= 2 * kChunk * kFastWaves) {
+        // the persistent step needs every block resident at once: one block per compute unit
+        int per_cu = 0;
+        hipError_t oe = cfg->head_dim == 128
+                            ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, verify_mega_kernel<128>, kFastThreads, 0)
+                            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, verify_mega_kernel<64>, kFastThreads, 0);
+        if (oe == hipSuccess && per_cu >= 1) {
+            std::vector<LayerW> tab((size_t)cfg->n_layers);
+            for (int l = 0; l < cfg->n_layers; ++l) {
+                tab[(size_t)l].qkv = (const uint4 *)(m->ws + lay.wp_qkv[(size_t)l]);
+                tab[(size_t)l].o = (const uint4 *)(m->ws + lay.wp_o[(size_t)l]);
+                tab[(size_t)l].gu = (const uint4 *)(m->ws + lay.wp_gu[(size_t)l]);
+                tab[(size_t)l].down = (const uint4 *)(m->ws + lay.wp_down[(size_t)l]);
+                tab[(size_t)l].attn_gain = (const bf16_t *)m->attn_norm[(size_t)l];
+                tab[(size_t)l].ffn_gain = (const bf16_t *)m->ffn_norm[(size_t)l];
+            }
+            e = hipMemcpyAsync(m->ws + lay.layer_tab, tab.data(), tab.size() * sizeof(LayerW), hipMemcpyHostToDevice, st);
+            if (e == hipSuccess) e = hipStreamSynchronize(st);  // `tab` is about to go out of scope
+            m->mega = true;
+            m->mega_grid = m->n_cu;
+        } else {
+            (void)hipGetLastError();
+        }
+    }
     if (e == hipSuccess && m->mfma) {
         // repack every matrix into MFMA-fragment order inside the workspace
         const int d = cfg->d_model, F = cfg->d_ffn, dh = cfg->head_dim;
@@ -555,6 +642,16 @@ void anpd_model_destroy(anpd_model_t *m)
     if (m->pin) (void)hipHostFree(m->pin);
     for (hipEvent_t e : m->ev) (void)hipEventDestroy(e);
     delete m;
+}
+
+int32_t anpd_model_trace(anpd_model_t *m, void *buffer, size_t bytes)
+{
+    if (!m) return fail(ANPD_E_INVAL, "anpd_model_trace: NULL handle");
+    if (buffer && (!m->mega || bytes < (size_t)m->mega_grid * kTraceEvents * sizeof(long long)))
+        return fail(ANPD_E_CAPACITY, "anpd_model_trace: needs %zu bytes and the one-kernel step",
+                    (size_t)m->mega_grid * kTraceEvents * sizeof(long long));
+    m->trace = (long long *)buffer;
+    return m->mega ? m->mega_grid : 0;
 }
 
 int32_t anpd_model_profile(anpd_model_t *m, int32_t enable)
@@ -733,7 +830,8 @@ int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32
     if (rc != ANPD_OK) return rc;
     std::memcpy(m->pin, window, sizeof(int32_t) * (size_t)n_window);
     HIP_TRY(hipMemcpyAsync(m->ws + m->lay.tok, m->pin, sizeof(int32_t) * (size_t)n_window, hipMemcpyHostToDevice, st));
-    if (m->mfma) rc = run_step_fast(m, kv, n_window, mode, st);
+    if (m->mega && n_window <= 8) rc = run_step_mega(m, kv, n_window, mode, out_logits != nullptr, st);
+    else if (m->mfma) rc = run_step_fast(m, kv, n_window, mode, st);
     else if (m->cfg.dtype == ANPD_BF16) rc = run_step_generic<bf16_t>(m, kv, n_window, mode, st);
     else rc = run_step_generic<float>(m, kv, n_window, mode, st);
     if (rc != ANPD_OK) return rc;
@@ -742,7 +840,16 @@ int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32
     if (out_logits)
         HIP_TRY(hipMemcpyAsync(out_logits, m->ws + m->lay.logits, sizeof(float) * (size_t)n_window * m->cfg.vocab,
                                hipMemcpyDeviceToDevice, st));
+    if (m->mega) HIP_TRY(hipMemcpyAsync(m->pin + 100, m->ws + m->lay.err, sizeof(int32_t), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
+    if (m->mega && m->pin[100] != 0) {
+        // a grid barrier gave up: the counters are no longer in step, start them over
+        (void)hipMemsetAsync(m->ws + m->lay.bar, 0, kBarStride * 9 * sizeof(uint32_t), st);
+        (void)hipMemsetAsync(m->ws + m->lay.err, 0, sizeof(int32_t), st);
+        (void)hipStreamSynchronize(st);
+        m->bar_epoch = 0;
+        return fail(ANPD_E_HIP, "anpd_verify: the persistent kernel timed out at a grid barrier");
+    }
     if (m->prof) {
         for (int i = 1; i < m->ev_used; ++i) {
             float ms = 0.f;

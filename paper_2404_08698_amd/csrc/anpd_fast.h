@@ -25,9 +25,11 @@
 
 namespace anpd {
 
-constexpr int kFastWaves = 16;  // waves per block of every fast GEMM: part of the numerics
+constexpr int kFastWaves = 8;   // waves per block of every fast-path kernel: part of the numerics
+constexpr int kFastThreads = kFastWaves * 64;
 
 // store four consecutive columns k..k+3 (k % 4 == 0) of row m as hi and lo terms
+template <bool COH = false>
 __device__ __forceinline__ void xp_store4(bf16_t *xp, int cls, int m, int k, f32x4 v)
 {
     bf16_t hi[4], lo[4];
@@ -38,8 +40,8 @@ __device__ __forceinline__ void xp_store4(bf16_t *xp, int cls, int m, int k, f32
     }
     uint2 ph = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
     uint2 pl = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
-    *reinterpret_cast<uint2 *>(xp + xp_offset(cls, m, k, 0)) = ph;
-    *reinterpret_cast<uint2 *>(xp + xp_offset(cls, m, k, 1)) = pl;
+    stc8<COH>(xp + xp_offset(cls, m, k, 0), ph);
+    stc8<COH>(xp + xp_offset(cls, m, k, 1), pl);
 }
 
 // ------------------------------------------------------ fast-path KV cache
@@ -118,7 +120,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const bf16_t *__restrict__ sr
 
 // --------------------------------------------------------------- epilogues
 
-enum { EPI_PLAIN = 0, EPI_QKV = 1, EPI_RESIDUAL = 2, EPI_GATE_UP = 3, EPI_LOGITS = 4 };
+enum { EPI_PLAIN = 0, EPI_QKV = 1, EPI_RESIDUAL = 2, EPI_GATE_UP = 3, EPI_LOGITS = 4, EPI_LM_ARGMAX = 5 };
 
 struct FastArgs {
     // GEMM proper
@@ -146,39 +148,61 @@ struct FastArgs {
     int d;
     // GATE_UP
     bf16_t *ap;           // operand of the down projection: split(silu(gate) * up)
+    // LM_ARGMAX: Y (nullable) receives the logits; amax the per-tile best (value bits << 32 | index)
+    unsigned long long *amax;  // [n_tiles][32]
 };
 
 // rinv[m] = 1 / sqrt(mean(x[m]^2) + eps) for the window rows, from the producer's per-tile partial
-// sums.  All 1024 threads of the block take part: thread (m = tid % 32, g = tid / 32) adds the
-// partials of tiles g, g + 32, ... in increasing order, then row m adds the 32 group sums in
-// increasing g.  The order depends on the tile count only.  Ends with a block barrier.
-__device__ __forceinline__ void compute_rinv(const FastArgs &a, float *rinv /* LDS [32] */, float *scratch /* LDS [32][32] */)
+// sums.  All threads of the block take part: thread (m = tid % 32, g = tid / 32) adds the
+// partials of tiles g, g + G, ... (G = kFastThreads / 32) in increasing order, then row m adds
+// the G group sums in increasing g.  The order depends on the tile count only.  Ends with a block barrier.
+template <bool COH = false>
+__device__ __forceinline__ void compute_rinv(const FastArgs &a, float *rinv /* LDS [32] */, float *scratch /* LDS [kFastThreads] */)
 {
     const int m = threadIdx.x & 31, g = threadIdx.x >> 5;
     float s = 0.f;
     if (m < a.M)
-        for (int t = g; t < a.n_ss; t += 32) s += a.ssp[(size_t)t * 32 + m];
+        for (int t = g; t < a.n_ss; t += kFastThreads / 32) s += ldf_at<COH>(a.ssp, (uint32_t)(t * 32 + m));
     scratch[g * 32 + m] = s;
-    __syncthreads();
+    block_sync_lds();
     if (threadIdx.x < 32) {
         float tot = 0.f;
 #pragma unroll
-        for (int gg = 0; gg < 32; ++gg) tot += scratch[gg * 32 + threadIdx.x];
+        for (int gg = 0; gg < kFastThreads / 32; ++gg) tot += scratch[gg * 32 + threadIdx.x];
         rinv[threadIdx.x] = 1.0f / sqrtf(tot * a.inv_d + a.eps);
     }
-    __syncthreads();
+    block_sync_lds();
 }
 
 // y: this lane's four outputs D[4 kg + i][m] of tile `tile` for window row m (valid says whether the row exists).
 // Every lane of the wave must call this (the fused forms exchange values with lane ^ 32).
-template <int EPI>
+template <int EPI, bool COH = false>
 __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int kg, f32x4 y, bool valid,
                                          const float *rinv)
 {
     if (EPI == EPI_PLAIN) {
-        if (valid) *reinterpret_cast<f32x4 *>(a.Y + (size_t)m * a.ldy + tile * 16 + 4 * kg) = y;
+        if (valid) stc16<COH>(a.Y + (size_t)m * a.ldy + tile * 16 + 4 * kg, y);
     } else if (EPI == EPI_LOGITS) {
-        if (valid) *reinterpret_cast<f32x4 *>(a.Y + (size_t)m * a.ldy + tile * 16 + 4 * kg) = y * rinv[m];
+        if (valid) stc16<COH>(a.Y + (size_t)m * a.ldy + tile * 16 + 4 * kg, y * rinv[m]);
+    } else if (EPI == EPI_LM_ARGMAX) {
+        // besides (optionally) storing the logits, keep the best (value, lowest index) of the
+        // tile's 16 columns for every row
+        f32x4 v = y * (valid ? rinv[m] : 0.f);
+        const int n = tile * 16 + 4 * kg;
+        if (valid && a.Y) stc16<COH>(a.Y + (size_t)m * a.ldy + n, v);
+        float best = v[0];
+        int bi = n;
+#pragma unroll
+        for (int i = 1; i < 4; ++i)
+            if (v[i] > best) { best = v[i]; bi = n + i; }
+#pragma unroll
+        for (int off = 16; off <= 32; off <<= 1) {
+            float ov = __shfl_xor(best, off, kWave);
+            int oi = __shfl_xor(bi, off, kWave);
+            if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+        }
+        if (valid && kg == 0)
+            st_agent(a.amax + (size_t)tile * 32 + m, ((unsigned long long)__float_as_uint(best) << 32) | (uint32_t)bi);
     } else if (EPI == EPI_RESIDUAL) {
         const int n = tile * 16 + 4 * kg;
         f32x4 v = {0.f, 0.f, 0.f, 0.f};
@@ -189,12 +213,12 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
             uint2 gb = *reinterpret_cast<const uint2 *>(a.gain + n);
             f32x4 g = {__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xffff0000u), __uint_as_float(gb.y << 16),
                        __uint_as_float(gb.y & 0xffff0000u)};
-            xp_store4(a.xp_next, a.cls, m, n, v * g);
+            xp_store4<COH>(a.xp_next, a.cls, m, n, v * g);
         }
         float s = fmaf(v[3], v[3], fmaf(v[2], v[2], fmaf(v[1], v[1], v[0] * v[0])));
         s += __shfl_xor(s, 16, kWave);
         s += __shfl_xor(s, 32, kWave);
-        if (valid && kg == 0) a.ssp_next[(size_t)tile * 32 + m] = s;
+        if (valid && kg == 0) stc<COH>(a.ssp_next + (size_t)tile * 32 + m, s);
     } else if (EPI == EPI_QKV) {
         const float r = valid ? rinv[m] : 0.f;
         y = y * r;
@@ -224,20 +248,20 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
                     hi[i] = f32_to_bf16(o[i]);
                     lo[i] = f32_to_bf16(o[i] - bf16_to_f32(hi[i]));
                 }
-                *reinterpret_cast<uint2 *>(a.qp + qp_offset(h, a.head_dim, m, dim, 0)) =
-                    make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
-                *reinterpret_cast<uint2 *>(a.qp + qp_offset(h, a.head_dim, m, dim, 1)) =
-                    make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+                stc8<COH>(a.qp + qp_offset(h, a.head_dim, m, dim, 0),
+                          make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16)));
+                stc8<COH>(a.qp + qp_offset(h, a.head_dim, m, dim, 1),
+                          make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)));
             } else {
                 bf16_t *dst = a.pool + kvf_base(page, a.layer, a.n_layers, 0, h, a.n_heads, a.head_dim) + kf_elem(tok, dim);
-                *reinterpret_cast<uint2 *>(dst) = make_uint2((uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16),
-                                                             (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16));
+                stc8<COH>(dst, make_uint2((uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16),
+                                          (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16)));
             }
         } else {
             const int n = t * 16 + 4 * kg, h = n / a.head_dim, dim = n - h * a.head_dim;
             bf16_t *dst = a.pool + kvf_base(page, a.layer, a.n_layers, 1, h, a.n_heads, a.head_dim);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dst[vf_elem(tok, dim + i)] = f32_to_bf16(y[i]);
+            for (int i = 0; i < 4; ++i) stc2<COH>(dst + vf_elem(tok, dim + i), f32_to_bf16(y[i]));
         }
     } else if (EPI == EPI_GATE_UP) {
         const float r = valid ? rinv[m] : 0.f;
@@ -249,13 +273,13 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
             f32x4 act;
 #pragma unroll
             for (int i = 0; i < 4; ++i) act[i] = y[i] / (1.0f + expf(-y[i])) * up[i];
-            xp_store4(a.ap, a.cls, m, tile * 8 + 4 * kg, act);
+            xp_store4<COH>(a.ap, a.cls, m, tile * 8 + 4 * kg, act);
         }
     }
 }
 
 // Sum the per-wave partial tiles (wave order), add hi + lo, run the epilogue.  One wave calls this.
-template <int NT, int EPI>
+template <int NT, int EPI, bool COH = false>
 __device__ __forceinline__ void reduce_and_finish(const FastArgs &a, int tile, const float *red /* [nw][NT][256] */,
                                                   int nw, int lane, const float *rinv)
 {
@@ -271,12 +295,12 @@ __device__ __forceinline__ void reduce_and_finish(const FastArgs &a, int tile, c
         f32x4 lo;
 #pragma unroll
         for (int i = 0; i < 4; ++i) lo[i] = row_down8(tot[0][i]);
-        epilogue<EPI>(a, tile, slot, kg, tot[0] + lo, slot < 8 && slot < a.M, rinv);
+        epilogue<EPI, COH>(a, tile, slot, kg, tot[0] + lo, slot < 8 && slot < a.M, rinv);
     } else {
 #pragma unroll
         for (int p = 0; p < NT / 2; ++p) {
             int m = p * 16 + slot;
-            epilogue<EPI>(a, tile, m, kg, tot[2 * p] + tot[2 * p + 1], m < a.M, rinv);
+            epilogue<EPI, COH>(a, tile, m, kg, tot[2 * p] + tot[2 * p + 1], m < a.M, rinv);
         }
     }
 }
@@ -284,13 +308,13 @@ __device__ __forceinline__ void reduce_and_finish(const FastArgs &a, int tile, c
 // ---------------------------------------------------- GEMM, X-stationary
 //
 // Window class 8 only.  One block per compute unit; a wave keeps its slice of
-// the activation operand (k-steps wave, wave + 16, ...) in registers for the
+// the activation operand (k-steps wave, wave + 8, ...) in registers for the
 // whole kernel and streams the weight tiles block, block + grid, ... past it,
 // always one half-tile ahead, so the only memory traffic of the main loop is
-// the weights.  The partial tiles of the 16 waves meet in LDS (double
+// the weights.  The partial tiles of the 8 waves meet in LDS (double
 // buffered, one barrier per tile); a different wave finishes each tile.
 template <int KPW, int EPI>
-__global__ __launch_bounds__(1024) void gemm_xs_kernel(FastArgs a)
+__global__ __launch_bounds__(kFastThreads) void gemm_xs_kernel(FastArgs a)
 {
     __shared__ float red[2][kFastWaves][256];
     __shared__ float rinv[32];
@@ -347,7 +371,7 @@ __global__ __launch_bounds__(1024) void gemm_xs_kernel(FastArgs a)
         }
         float *r = &red[it & 1][0][0];
         *reinterpret_cast<f32x4 *>(r + ((size_t)wave * 64 + lane) * 4) = acc;
-        __syncthreads();
+        block_sync_lds();
         if (wave == (it & (kFastWaves - 1))) reduce_and_finish<1, EPI>(a, tile, r, kFastWaves, lane, rinv);
     }
 }
@@ -358,9 +382,9 @@ __global__ __launch_bounds__(1024) void gemm_xs_kernel(FastArgs a)
 // fragments are read from global memory (L2-resident) next to the weights.
 // Same k-step assignment and summation order as the X-stationary form.
 template <int NT, int EPI>
-__global__ __launch_bounds__(1024) void gemm_stream_kernel(FastArgs a)
+__global__ __launch_bounds__(kFastThreads) void gemm_stream_kernel(FastArgs a)
 {
-    extern __shared__ float red_dyn[];  // [16][NT][256]
+    extern __shared__ float red_dyn[];  // [kFastWaves][NT][256]
     __shared__ float rinv[32];
     constexpr int C = NT == 1 ? 4 : (NT == 2 ? 2 : 1);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -400,10 +424,11 @@ __global__ __launch_bounds__(1024) void gemm_stream_kernel(FastArgs a)
 // x[m] = E[token[m]] plus what the residual epilogue would leave behind for the
 // first layer: split(x * attn_gain[0]) and the partial sums of squares.
 // grid: d / 16 blocks of one wave.
-__global__ __launch_bounds__(64) void embed_fast_kernel(const bf16_t *__restrict__ E, const int32_t *__restrict__ tok,
-                                                         FastArgs a)
+template <bool COH>
+__device__ __forceinline__ void embed_tile(const bf16_t *__restrict__ E, const int32_t *__restrict__ tok, const FastArgs &a,
+                                           int tile, int lane)
 {
-    const int lane = threadIdx.x, slot = lane & 15, kg = lane >> 4, tile = blockIdx.x;
+    const int slot = lane & 15, kg = lane >> 4;
     const int n = tile * 16 + 4 * kg;
     for (int p = 0; p < (a.M + 15) / 16; ++p) {
         const int m = p * 16 + slot;
@@ -417,13 +442,19 @@ __global__ __launch_bounds__(64) void embed_fast_kernel(const bf16_t *__restrict
             uint2 gb = *reinterpret_cast<const uint2 *>(a.gain + n);
             f32x4 g = {__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xffff0000u), __uint_as_float(gb.y << 16),
                        __uint_as_float(gb.y & 0xffff0000u)};
-            xp_store4(a.xp_next, a.cls, m, n, v * g);
+            xp_store4<COH>(a.xp_next, a.cls, m, n, v * g);
         }
         float s = fmaf(v[3], v[3], fmaf(v[2], v[2], fmaf(v[1], v[1], v[0] * v[0])));
         s += __shfl_xor(s, 16, kWave);
         s += __shfl_xor(s, 32, kWave);
-        if (valid && kg == 0) a.ssp_next[(size_t)tile * 32 + m] = s;
+        if (valid && kg == 0) stc<COH>(a.ssp_next + (size_t)tile * 32 + m, s);
     }
+}
+
+__global__ __launch_bounds__(64) void embed_fast_kernel(const bf16_t *__restrict__ E, const int32_t *__restrict__ tok,
+                                                         FastArgs a)
+{
+    embed_tile<false>(E, tok, a, blockIdx.x, threadIdx.x);
 }
 
 // fp32 [M][K] -> packed split operand (stand-alone linear entry point)
@@ -439,16 +470,16 @@ __global__ __launch_bounds__(256) void split_packed_kernel(const float *__restri
 typedef short bf16x4s __attribute__((ext_vector_type(4)));
 
 // Window-causal attention on the matrix cores.  Block (head, split) covers
-// kFastSplit = 256 absolute key positions, one 16-token page per wave.  Per
+// kFastSplit = 128 absolute key positions, one 16-token page per wave.  Per
 // group of 8 window rows: S = K q^T with the query as a split-bf16 B operand
 // (scores land with keys in registers and rows across lanes), softmax
 // statistics over the split with the block maximum, P as a split-bf16 B
-// operand straight from those registers, O = V^T P; the 16 waves' tiles are
+// operand straight from those registers, O = V^T P; the waves' tiles are
 // added in a fixed order through LDS.  Each block stores (o, max, denominator)
 // of its split; the last block of a head to finish merges the head's splits
 // in increasing order and writes the packed operand of the output projection.
 // Row r sees keys 0..len + r; keys it must not see get weight exactly 0.
-constexpr int kFastSplit = 256;
+constexpr int kFastSplit = kFastWaves * 16;
 
 #ifdef ANPD_TIMING
 __device__ long long *g_anpd_dbg = nullptr;
@@ -459,19 +490,25 @@ __device__ long long *g_anpd_dbg = nullptr;
 
 template <int DH>
 struct AttnShared {
-    float red[8][DH / 16][32][4];
-    float wmax[16][8], wden[16][8];
+    float red[kFastWaves / 2][DH / 16][32][4];
+    float wmax[kFastWaves][8], wden[kFastWaves][8];
     float gm[32], gden[32];
     bool last;
 };
 
-// One (head, split) task; every thread of the 16-wave block calls it.
-template <int DH>
+struct NoPrefetch {
+    __device__ __forceinline__ void operator()() const {}
+};
+
+// One (head, split) task; every thread of the block calls it.  `after_loads` runs right after the
+// task's own K / V loads have been issued (the persistent kernel puts its weight prefetch there, so
+// that the prefetch queues behind the loads attention is waiting for, not in front of them).
+template <int DH, bool COH = false, typename AfterLoads = NoPrefetch>
 __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int split, int L, const uint4 *__restrict__ qp,
                                           const bf16_t *__restrict__ pool, const int32_t *__restrict__ page_table, int M,
                                           int layer, int n_layers, int n_heads, int max_splits, float scale,
                                           float *__restrict__ part, uint32_t *__restrict__ head_counter,
-                                          bf16_t *__restrict__ xp_att, int cls)
+                                          bf16_t *__restrict__ xp_att, int cls, AfterLoads after_loads = AfterLoads())
 {
     constexpr int NKS = DH / 32, NDT = DH / 16;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, slot = lane & 15, kg = lane >> 4;
@@ -486,23 +523,27 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
 #pragma unroll
     for (int i = 0; i < NDT; ++i) vf[i] = make_uint2(0, 0);
     if (active) {
-        const int page = page_table[key0 >> 4];
-        const uint4 *kp = reinterpret_cast<const uint4 *>(pool + kvf_base(page, layer, n_layers, 0, head, n_heads, DH)) + lane;
-        const uint2 *vp = reinterpret_cast<const uint2 *>(pool + kvf_base(page, layer, n_layers, 1, head, n_heads, DH)) + lane;
+        const int page = __builtin_amdgcn_readfirstlane(page_table[key0 >> 4]);
+        const uint4 *kp = reinterpret_cast<const uint4 *>(pool + kvf_base(page, layer, n_layers, 0, head, n_heads, DH));
+        const uint2 *vp = reinterpret_cast<const uint2 *>(pool + kvf_base(page, layer, n_layers, 1, head, n_heads, DH));
 #pragma unroll
-        for (int i = 0; i < NKS; ++i) kf[i] = ld_coherent(kp + i * 64);
+        for (int i = 0; i < NKS; ++i) kf[i] = ld16_at<COH>(kp, (uint32_t)(i * 64 + lane));
 #pragma unroll
-        for (int i = 0; i < NDT; ++i) vf[i] = ld_coherent(vp + i * 64);
+        for (int i = 0; i < NDT; ++i) vf[i] = ld8_at<COH>(vp, (uint32_t)(i * 64 + lane));
     }
+    after_loads();
 
     for (int rg = 0; rg * 8 < M; ++rg) {
         // ---- scores S[key][row]
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        const uint4 *q = qp + ((size_t)(head * 4 + rg) * NKS) * 64 + lane;
+        const uint4 *q = qp + ((size_t)(head * 4 + rg) * NKS) * 64;
+        uint4 qf[NKS];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) qf[ks] = ld16_at<COH>(q, (uint32_t)(ks * 64 + lane));
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks)
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[ks]),
-                                                          __builtin_bit_cast(bf16x8, ld_coherent(q + ks * 64)), acc, 0, 0, 0);
+                                                          __builtin_bit_cast(bf16x8, qf[ks]), acc, 0, 0, 0);
         const int m = rg * 8 + (slot & 7);
         float sc[4], mx = kMasked;
 #pragma unroll
@@ -516,11 +557,11 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
         mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
         mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
         if (kg == 0 && slot < 8) sh.wmax[wave][slot] = mx;
-        __syncthreads();
+        block_sync_lds();
         ANPD_STAMP(1);
         float bm = sh.wmax[0][slot & 7];
 #pragma unroll
-        for (int w = 1; w < 16; ++w) bm = fmaxf(bm, sh.wmax[w][slot & 7]);
+        for (int w = 1; w < kFastWaves; ++w) bm = fmaxf(bm, sh.wmax[w][slot & 7]);
         // ---- exponentials, denominators, P operand (hi rows in slots 0..7, lo rows in 8..15)
         float p[4], den = 0.f;
 #pragma unroll
@@ -552,32 +593,35 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
             for (int i = 0; i < 4; ++i) lo[i] = row_down8(o[i]);
             ot[dt] = o + lo;
         }
-        // ---- add the 16 waves' tiles: wave w + 8 into wave w, then waves 0..7 in order (one dim tile
-        // per wave).  LDS is addressed by compacted lane (kg * 8 + slot), i.e. linearly.
+        // ---- add the waves' tiles: wave w + H into wave w (H = half the waves), then waves 0..H-1 in
+        // order, one or two dim tiles per wave.  LDS is addressed by compacted lane (kg * 8 + slot).
         const int cl = kg * 8 + (slot & 7);
-        if (wave >= 8 && slot < 8) {
+        constexpr int HW = kFastWaves / 2;
+        if (wave >= HW && slot < 8) {
 #pragma unroll
-            for (int dt = 0; dt < NDT; ++dt) *reinterpret_cast<f32x4 *>(&sh.red[wave - 8][dt][cl][0]) = ot[dt];
+            for (int dt = 0; dt < NDT; ++dt) *reinterpret_cast<f32x4 *>(&sh.red[wave - HW][dt][cl][0]) = ot[dt];
         }
-        __syncthreads();
-        if (wave < 8 && slot < 8) {
+        block_sync_lds();
+        if (wave < HW && slot < 8) {
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt) {
                 f32x4 *r = reinterpret_cast<f32x4 *>(&sh.red[wave][dt][cl][0]);
                 *r = ot[dt] + *r;
             }
         }
-        __syncthreads();
+        block_sync_lds();
         ANPD_STAMP(9);
-        if (wave < NDT && slot < 8) {
-            const int row = rg * 8 + slot;
-            f32x4 tot = *reinterpret_cast<const f32x4 *>(&sh.red[0][wave][cl][0]);
+        for (int dt = wave; dt < NDT; dt += kFastWaves) {
+            if (slot < 8) {
+                const int row = rg * 8 + slot;
+                f32x4 tot = *reinterpret_cast<const f32x4 *>(&sh.red[0][dt][cl][0]);
 #pragma unroll
-            for (int w = 1; w < 8; ++w) tot += *reinterpret_cast<const f32x4 *>(&sh.red[w][wave][cl][0]);
-            if (row < M) {
-                float *dst = part + (((size_t)head * max_splits + split) * 32 + row) * (DH + 2) + 16 * wave + 4 * kg;
+                for (int w = 1; w < HW; ++w) tot += *reinterpret_cast<const f32x4 *>(&sh.red[w][dt][cl][0]);
+                if (row < M) {
+                    float *dst = part + (((size_t)head * max_splits + split) * 32 + row) * (DH + 2) + 16 * dt + 4 * kg;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) st_agent(dst + i, tot[i]);
+                    for (int i = 0; i < 4; ++i) st_agent(dst + i, tot[i]);
+                }
             }
         }
         if (threadIdx.x < 8 && rg * 8 + threadIdx.x < M) {
@@ -585,49 +629,50 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
             size_t b2 = (((size_t)head * max_splits + split) * 32 + rg * 8 + mm) * (DH + 2) + DH;
             float bmx = sh.wmax[0][mm], dsum = sh.wden[0][mm];
 #pragma unroll
-            for (int w = 1; w < 16; ++w) { bmx = fmaxf(bmx, sh.wmax[w][mm]); dsum += sh.wden[w][mm]; }
+            for (int w = 1; w < kFastWaves; ++w) { bmx = fmaxf(bmx, sh.wmax[w][mm]); dsum += sh.wden[w][mm]; }
             st_agent(part + b2, bmx);
             st_agent(part + b2 + 1, dsum);
         }
         ANPD_STAMP(10);
-        __syncthreads();
+        block_sync_lds();
         ANPD_STAMP(11);
     }
 
     // ---- the last block of this head merges the splits
     ANPD_STAMP(2);
     wait_stores();
-    __syncthreads();
+    block_sync_lds();
     ANPD_STAMP(3);
     const int n_blocks = (L + M + kFastSplit - 1) / kFastSplit;
     if (threadIdx.x == 0)
         sh.last = __hip_atomic_fetch_add(&head_counter[head], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
                   (uint32_t)(n_blocks - 1);
-    __syncthreads();
+    block_sync_lds();
     ANPD_STAMP(4);
     if (!sh.last) return;
     if (threadIdx.x == 0) st_agent(&head_counter[head], 0u);
     const float *ph = part + ((size_t)head * max_splits) * 32 * (DH + 2);
     const size_t stride = (size_t)32 * (DH + 2);
-    // global maximum and denominator of every row: wave w takes rows w, w + 16; lanes stride over the splits
-    for (int row = wave; row < M; row += 16) {
+    // global maximum and denominator of every row: wave w takes rows w, w + 8, ...; lanes stride over the splits
+    for (int row = wave; row < M; row += kFastWaves) {
         const int ns = (L + row) / kFastSplit + 1;
-        const float *pr = ph + (size_t)row * (DH + 2);
+        const uint32_t ro = (uint32_t)row * (DH + 2);
         float g = kMasked;
-        for (int s2 = lane; s2 < ns; s2 += 64) g = fmaxf(g, ld_agent(pr + s2 * stride + DH));
+        for (int s2 = lane; s2 < ns; s2 += 64) g = fmaxf(g, ldf_at<true>(ph, ro + (uint32_t)(s2 * stride + DH)));
         g = wave_max(g);
         float dsum = 0.f;
         for (int s2 = lane; s2 < ns; s2 += 64)
-            dsum += expf(ld_agent(pr + s2 * stride + DH) - g) * ld_agent(pr + s2 * stride + DH + 1);
+            dsum += expf(ldf_at<true>(ph, ro + (uint32_t)(s2 * stride + DH)) - g) *
+                    ldf_at<true>(ph, ro + (uint32_t)(s2 * stride + DH + 1));
         dsum = wave_sum(dsum);
         if (lane == 0) { sh.gm[row] = g; sh.gden[row] = dsum; }
     }
-    __syncthreads();
+    block_sync_lds();
     ANPD_STAMP(5);
-    for (int idx = threadIdx.x; idx < M * DH; idx += 1024) {
+    for (int idx = threadIdx.x; idx < M * DH; idx += kFastThreads) {
         const int row = idx / DH, e = idx - row * DH;
         const int ns = (L + row) / kFastSplit + 1;
-        const float *pr = ph + (size_t)row * (DH + 2);
+        const uint32_t ro = (uint32_t)row * (DH + 2);
         const float g = sh.gm[row];
         float o = 0.f;
         for (int s0 = 0; s0 < ns; s0 += 4) {
@@ -635,8 +680,8 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const bool okj = s0 + j < ns;
-                ov[j] = okj ? ld_agent(pr + (s0 + j) * stride + e) : 0.f;
-                bv[j] = okj ? ld_agent(pr + (s0 + j) * stride + DH) : kMasked;
+                ov[j] = okj ? ldf_at<true>(ph, ro + (uint32_t)((s0 + j) * stride + e)) : 0.f;
+                bv[j] = okj ? ldf_at<true>(ph, ro + (uint32_t)((s0 + j) * stride + DH)) : kMasked;
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j)
@@ -644,15 +689,15 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
         }
         const float v = o / sh.gden[row];
         const bf16_t hi = f32_to_bf16(v);
-        xp_att[xp_offset(cls, row, head * DH + e, 0)] = hi;
-        xp_att[xp_offset(cls, row, head * DH + e, 1)] = f32_to_bf16(v - bf16_to_f32(hi));
+        stc2<COH>(xp_att + xp_offset(cls, row, head * DH + e, 0), hi);
+        stc2<COH>(xp_att + xp_offset(cls, row, head * DH + e, 1), f32_to_bf16(v - bf16_to_f32(hi)));
     }
     ANPD_STAMP(6);
 }
 
-// grid: (n_heads, ceil((len + M) / 256)), 16 waves.
+// grid: (n_heads, ceil((len + M) / kFastSplit)), kFastWaves waves.
 template <int DH>
-__global__ __launch_bounds__(1024) void attn_fast_kernel(const uint4 *__restrict__ qp, const bf16_t *__restrict__ pool,
+__global__ __launch_bounds__(kFastThreads) void attn_fast_kernel(const uint4 *__restrict__ qp, const bf16_t *__restrict__ pool,
                                                           const int32_t *__restrict__ page_table,
                                                           const int32_t *__restrict__ len_ptr, int M, int layer, int n_layers,
                                                           int n_heads, int max_splits, float scale, float *__restrict__ part,

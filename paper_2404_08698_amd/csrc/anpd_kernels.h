@@ -65,10 +65,90 @@ __device__ __forceinline__ void st_agent(T *p, T v) { __hip_atomic_store(p, v, _
 template <typename T>
 __device__ __forceinline__ T ld_agent(const T *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
-// Plain vector loads for data that another block may have written earlier in the same kernel
-// launch sequence.  Kernel boundaries make ordinary loads coherent, so this is an ordinary load.
-template <typename T>
-__device__ __forceinline__ T ld_coherent(const T *p) { return *p; }
+// Accessors for data that one block writes and another block reads.  COH = false: ordinary
+// accesses, for kernels whose producers ran in an earlier launch.  COH = true: device-coherent
+// accesses (see st_agent / ld_agent), for the persistent kernel where producer and consumer run in
+// the same launch on different XCDs.  Wider items are moved as 8-byte pieces.
+template <bool COH>
+__device__ __forceinline__ float ldc(const float *p) { return COH ? ld_agent(p) : *p; }
+template <bool COH>
+__device__ __forceinline__ void stc(float *p, float v)
+{
+    if (COH) st_agent(p, v);
+    else *p = v;
+}
+template <bool COH>
+__device__ __forceinline__ uint2 ldc8(const uint2 *p)
+{
+    if (!COH) return *p;
+    unsigned long long v = ld_agent(reinterpret_cast<const unsigned long long *>(p));
+    return make_uint2((uint32_t)v, (uint32_t)(v >> 32));
+}
+template <bool COH>
+__device__ __forceinline__ void stc8(void *p, uint2 v)
+{
+    if (COH) st_agent(reinterpret_cast<unsigned long long *>(p), (unsigned long long)v.x | ((unsigned long long)v.y << 32));
+    else *reinterpret_cast<uint2 *>(p) = v;
+}
+template <bool COH>
+__device__ __forceinline__ uint4 ldc16(const uint4 *p)
+{
+    if (!COH) return *p;
+    uint2 lo = ldc8<true>(reinterpret_cast<const uint2 *>(p)), hi = ldc8<true>(reinterpret_cast<const uint2 *>(p) + 1);
+    return make_uint4(lo.x, lo.y, hi.x, hi.y);
+}
+template <bool COH>
+__device__ __forceinline__ void stc16(float *p, f32x4 v)
+{
+    if (COH) {
+        stc8<true>(p, make_uint2(__float_as_uint(v[0]), __float_as_uint(v[1])));
+        stc8<true>(p + 2, make_uint2(__float_as_uint(v[2]), __float_as_uint(v[3])));
+    } else {
+        *reinterpret_cast<f32x4 *>(p) = v;
+    }
+}
+// 2-byte store; the coherent form is the same instruction with the write-through bits set
+template <bool COH>
+__device__ __forceinline__ void stc2(bf16_t *p, bf16_t v)
+{
+    if (COH) asm volatile("global_store_short %0, %1, off sc0 sc1" ::"v"(p), "v"((uint32_t)v) : "memory");
+    else *p = v;
+}
+
+// Indexed loads from a buffer whose base pointer is the same for the whole wave.  The coherent
+// form uses buffer instructions with the sc0 sc1 bits, which the compiler can keep in flight
+// together (atomic loads are issued one at a time); the plain form is an ordinary load.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+constexpr int kAuxCoherent = 17;  // sc0 | sc1
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t wave_buffer(const void *base)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0x7fffffff, 0x00020000);
+}
+template <bool COH>
+__device__ __forceinline__ uint4 ld16_at(const uint4 *base, uint32_t idx)
+{
+    if (!COH) return base[idx];
+    u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(wave_buffer(base), (int)(idx * 16u), 0, kAuxCoherent);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+template <bool COH>
+__device__ __forceinline__ uint2 ld8_at(const uint2 *base, uint32_t idx)
+{
+    if (!COH) return base[idx];
+    u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(wave_buffer(base), (int)(idx * 8u), 0, kAuxCoherent);
+    return make_uint2(v.x, v.y);
+}
+template <bool COH>
+__device__ __forceinline__ float ldf_at(const float *base, uint32_t idx)
+{
+    if (!COH) return base[idx];
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(wave_buffer(base), (int)(idx * 4u), 0, kAuxCoherent));
+}
+
+// Block barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding
+// global load of the wave, which would drain the weight prefetch at each tile boundary.
+__device__ __forceinline__ void block_sync_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 // Wait until this wave's outstanding global stores have been acknowledged.
 __device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }

@@ -1,0 +1,433 @@
+// The whole verification step as ONE persistent kernel (window class 8, d_model <= 4096).
+//
+// One 8-wave block per compute unit runs every phase of the step - embed, then
+// per layer QKV / attention / O / gate-up / down, then LM head and argmax+accept
+// (paper, Section 3.1 "Parallel Decoding" step 2; Algorithm 1) - separated by
+// grid barriers.  Because the weights do not depend on activations, a block
+// issues the loads of its first weight tile of the NEXT phase before it waits at
+// a barrier, so HBM keeps streaming across phase boundaries and through the
+// latency-bound attention phase; that is what separate launches cannot do.
+//
+// Blocks exchange activations through global memory with device-coherent
+// accesses (write-through stores, loads served at the coherence point): the
+// XCDs' L2 caches are not coherent with each other inside a launch, and
+// cache-wide write-back / invalidate fences cost tens of microseconds here.
+// The barrier is a two-level counter (groups of blocks, then one word every
+// block polls); counters only grow, the host passes the epoch.  Waits are
+// bounded: a block that gives up raises an error flag and every phase still
+// runs to its end, so the grid always drains.
+//
+// The arithmetic of every phase is the code of the multi-kernel fast path
+// (same tiles, same k-step assignment, same summation orders), so both paths
+// give bit-identical results.
+#pragma once
+#include "anpd_fast.h"
+
+namespace anpd {
+
+struct LayerW {
+    const uint4 *qkv, *o, *gu, *down;     // packed weights
+    const bf16_t *attn_gain, *ffn_gain;
+};
+
+struct MegaArgs {
+    const LayerW *layers;
+    int n_layers;
+    const uint4 *wp_lm;
+    const bf16_t *final_gain, *embed;
+    int d, F, V, n_heads, head_dim, M, mode;
+    float inv_d, eps, scale;
+    float *x;
+    bf16_t *xp_d, *xp_att, *xp_f, *qp;
+    float *ssp_a, *ssp_b, *part;
+    uint32_t *head_counter;
+    bf16_t *pool;
+    const int32_t *page_table;
+    int32_t *len_ptr;
+    const float2 *rope;
+    int max_splits;
+    float *logits;          // nullable: all logits [M][V]
+    unsigned long long *amax;  // [V / 16][32] per-tile (value bits << 32 | index) of the best logit
+    const int32_t *tok;
+    int32_t *result;
+    uint32_t *row_counter;  // argmax phase hand-off
+    uint32_t *bar;          // [0] = top counter, [kBarStride * (1 + g)] = group g
+    uint32_t bar_epoch;     // barriers completed by earlier launches
+    int32_t *error;         // set to 1 if a barrier wait gave up
+    long long *trace;       // nullable: [grid][kTraceEvents] timestamps (100 MHz) at barrier arrive / wait-done
+};
+
+constexpr int kTraceEvents = 1024;
+
+constexpr int kBarStride = 256;  // uint32 words between barrier counters (1 KiB: separate channels)
+constexpr int kMegaBarriers(int n_layers) { return 1 + 5 * n_layers + 1; }
+
+struct GridBarrier {
+    uint32_t *ctr;
+    uint32_t done;   // barriers this block has arrived at, including earlier launches
+    int32_t *error;
+    int grp, gsize, ngroups;
+    long long *trace;
+    int n_ev;
+};
+
+__device__ __forceinline__ void bar_init(GridBarrier &b, const MegaArgs &a)
+{
+    b.ctr = a.bar;
+    b.done = a.bar_epoch;
+    b.error = a.error;
+    b.ngroups = (gridDim.x % 8 == 0) ? 8 : 1;
+    b.gsize = gridDim.x / b.ngroups;
+    b.grp = blockIdx.x % b.ngroups;
+    b.trace = a.trace ? a.trace + (size_t)blockIdx.x * kTraceEvents : nullptr;
+    b.n_ev = 0;
+}
+
+__device__ __forceinline__ void bar_stamp(GridBarrier &b)
+{
+    if (b.trace) {
+        if (threadIdx.x == 0 && b.n_ev < kTraceEvents) b.trace[b.n_ev] = wall_clock64();
+        b.n_ev += 1;
+    }
+}
+
+// One thread per block calls it once every store of the phase that other blocks will read has
+// been acknowledged (wait_stores() in the storing waves).  Counts arrival number b.done + 1.
+__device__ __forceinline__ void bar_signal(const GridBarrier &b)
+{
+    uint32_t old = __hip_atomic_fetch_add(b.ctr + kBarStride * (1 + b.grp), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old == (b.done + 1u) * (uint32_t)b.gsize - 1u)
+        __hip_atomic_fetch_add(b.ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// All threads call it after their last store of the phase (phases without per-tile accounting).
+__device__ __forceinline__ void bar_arrive(GridBarrier &b)
+{
+    bar_stamp(b);
+    wait_stores();
+    block_sync_lds();
+    if (threadIdx.x == 0) bar_signal(b);
+    b.done += 1;
+}
+
+// All threads call it before their first load of data produced in the previous phase.  Does not
+// wait for this wave's outstanding loads (the weight prefetch stays in flight).
+__device__ __forceinline__ void bar_wait(GridBarrier &b)
+{
+    if (threadIdx.x == 0) {
+        const uint32_t target = b.done * (uint32_t)b.ngroups;
+        int spins = 0;
+        while ((int32_t)(ld_agent(b.ctr) - target) < 0) {
+            __builtin_amdgcn_s_sleep(4);
+            if (++spins > (1 << 21)) {  // about a second: something is wrong, do not hang the GPU
+                st_agent(b.error, 1);
+                break;
+            }
+        }
+    }
+    block_sync_lds();
+    bar_stamp(b);
+}
+
+struct WSrc {
+    const uint4 *Wp;
+    int nks, n_tiles;
+};
+
+constexpr int kChunk = 8;   // k-steps per wave per pipeline item (half a tile when K = 4096)
+
+// k-steps wave + 8 * (8 c + u), u = 0..7, of tile `tile`.  Buffer loads: the descriptor covers exactly
+// the tile's nks blocks, so k-steps past the end (and tiles that do not exist) read as zeros
+// without a branch, and one offset register per thread serves every load.
+__device__ __forceinline__ void load_wchunk(uint4 (&w)[kChunk], const WSrc &s, int tile, int c, int wave, int lane)
+{
+    const bool have = tile < s.n_tiles;
+    const uint4 *base = s.Wp + (size_t)(have ? tile : 0) * s.nks * 64;
+    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(base), 0, have ? s.nks * 1024 : 0, 0x00020000);
+    const int voff = (wave * 64 + lane) * 16;
+#pragma unroll
+    for (int u = 0; u < kChunk; ++u) {
+        u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, (kChunk * c + u) * kFastWaves * 1024, 0);
+        w[u] = make_uint4(v.x, v.y, v.z, v.w);
+    }
+}
+
+__device__ __forceinline__ void load_xchunk(uint4 (&x)[kChunk], const uint4 *Xp, int nks, int c, int wave, int lane)
+{
+    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(Xp), 0, nks * 1024, 0x00020000);
+    const int voff = (wave * 64 + lane) * 16;
+#pragma unroll
+    for (int u = 0; u < kChunk; ++u) {
+        u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, (kChunk * c + u) * kFastWaves * 1024, kAuxCoherent);
+        x[u] = make_uint4(v.x, v.y, v.z, v.w);
+    }
+}
+
+struct MegaShared {
+    union {
+        float red[2][kFastWaves][256];
+        AttnShared<128> attn128;
+        AttnShared<64> attn64;
+    };
+    float rinv[32];
+    int tiles_done;   // epilogues finished by this block since the kernel started
+};
+
+template <int DH>
+__device__ __forceinline__ AttnShared<DH> &attn_shared(MegaShared &sh);
+template <>
+__device__ __forceinline__ AttnShared<128> &attn_shared<128>(MegaShared &sh) { return sh.attn128; }
+template <>
+__device__ __forceinline__ AttnShared<64> &attn_shared<64>(MegaShared &sh) { return sh.attn64; }
+
+// One GEMM phase.  On entry pf holds (or has in flight) the weights of this block's first work
+// item, loaded by the previous phase; on exit those of the next phase's first item are in flight
+// (issued after this block has arrived at the phase barrier, so the arrival does not wait for them).
+// A work item is a chunk of kChunk k-steps per wave of one tile.
+// STATIONARY: K needs at most two chunks; the activation operand stays in registers for all tiles.
+template <int EPI, bool STATIONARY>
+__device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, uint4 (&pf)[kChunk], MegaShared &sh,
+                                           GridBarrier &bar, int &tiles_before)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, grid = gridDim.x;
+    const WSrc cur = {a.Wp, a.nks, a.n_tiles};
+    const int n_chunks = (((a.nks + kFastWaves - 1) / kFastWaves) + kChunk - 1) / kChunk;
+    const int my_tiles = (int)blockIdx.x < cur.n_tiles ? (cur.n_tiles - 1 - (int)blockIdx.x) / grid + 1 : 0;
+    const int tiles_after = tiles_before + my_tiles;
+    // Waves that finish tiles in this phase have stores to wait for at its end; they fetch their share
+    // of the next phase's first weights only after that wait, so the wait stays short.
+    const bool reducer = wave < my_tiles;
+    uint4 wb[kChunk], wc[kChunk], x0[kChunk], x1[kChunk];
+
+    // work items of this block: (tile, chunk) in order; pf holds item 0, wb and wc the two after it
+    int tile = blockIdx.x, c = 0;     // item being computed
+    int lt = blockIdx.x, lc = 0;      // last item whose weights have been requested
+    bool next_issued = false;         // the next phase's first chunk has been requested
+    auto fetch = [&](uint4 (&dst)[kChunk]) {
+        if (++lc == n_chunks) { lc = 0; lt += grid; }
+        if (lt < cur.n_tiles) {
+            load_wchunk(dst, cur, lt, lc, wave, lane);
+        } else if (!next_issued && !reducer) {
+            load_wchunk(dst, next, blockIdx.x, 0, wave, lane);
+            next_issued = true;
+        }
+    };
+    fetch(wb);
+    fetch(wc);
+
+    bar_wait(bar);
+    if (my_tiles == 0 && threadIdx.x == 0) bar_signal(bar);
+    load_xchunk(x0, a.Xp, a.nks, 0, wave, lane);
+    if (STATIONARY) load_xchunk(x1, a.Xp, a.nks, 1, wave, lane);   // else: one chunk ahead, alternating x0 / x1
+    if (EPI == EPI_QKV || EPI == EPI_GATE_UP || EPI == EPI_LOGITS || EPI == EPI_LM_ARGMAX)
+        compute_rinv<true>(a, sh.rinv, &sh.red[1][0][0]);
+
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    int it = 0, par = 0;
+    while (tile < cur.n_tiles) {
+        if (!STATIONARY) {
+            int pc = c + 1, pt = tile;
+            if (pc == n_chunks) { pc = 0; pt += grid; }
+            if (pt < cur.n_tiles) {
+                if (par == 0) load_xchunk(x1, a.Xp, a.nks, pc, wave, lane);
+                else load_xchunk(x0, a.Xp, a.nks, pc, wave, lane);
+            }
+        }
+        if (STATIONARY ? c == 1 : par == 1) {
+#pragma unroll
+            for (int u = 0; u < kChunk; ++u)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pf[u]),
+                                                              __builtin_bit_cast(bf16x8, x1[u]), acc, 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int u = 0; u < kChunk; ++u)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pf[u]),
+                                                              __builtin_bit_cast(bf16x8, x0[u]), acc, 0, 0, 0);
+        }
+        par ^= 1;
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u) { pf[u] = wb[u]; wb[u] = wc[u]; }
+        fetch(wc);
+        const bool tile_done = (c == n_chunks - 1);
+        const int finished = tile;
+        if (++c == n_chunks) { c = 0; tile += grid; }
+        if (tile_done) {
+            float *r = &sh.red[it & 1][0][0];
+            *reinterpret_cast<f32x4 *>(r + ((size_t)wave * 64 + lane) * 4) = acc;
+            block_sync_lds();
+            if (wave == (it & (kFastWaves - 1))) reduce_and_finish<1, EPI, true>(a, finished, r, kFastWaves, lane, sh.rinv);
+            acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+            ++it;
+        }
+    }
+    if (my_tiles == 0) {
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u) pf[u] = wb[u];
+    }
+    if (reducer) {
+        // this wave's epilogue stores must be out before the block counts its tiles as done; the wave
+        // that completes the block's count signals the grid barrier
+        wait_stores();
+        const int mine = (my_tiles - 1 - wave) / kFastWaves + 1;
+        if (lane == 0 && atomicAdd(&sh.tiles_done, mine) + mine == tiles_after) bar_signal(bar);
+        load_wchunk(pf, next, blockIdx.x, 0, wave, lane);
+    }
+    tiles_before = tiles_after;
+    bar.done += 1;
+    bar_stamp(bar);
+}
+
+template <int DH>
+__global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs g)
+{
+    __shared__ MegaShared sh;
+    __shared__ float bval[kFastWaves];
+    __shared__ int bidx[kFastWaves];
+    __shared__ bool last_row;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, grid = gridDim.x;
+    GridBarrier bar;
+    bar_init(bar, g);
+    bar_stamp(bar);
+    if (threadIdx.x == 0) sh.tiles_done = 0;   // ordered by the first block barrier below
+    int tiles_before = 0;
+    const int L = *g.len_ptr;
+    const int d = g.d, F = g.F;
+    const int nks_d = (d + 31) / 32, nks_f = (F + 31) / 32;
+
+    FastArgs base = {};
+    base.M = g.M;
+    base.cls = 8;
+    base.inv_d = g.inv_d;
+    base.eps = g.eps;
+    base.n_ss = d / 16;
+    base.d = d;
+    base.x = g.x;
+    base.pool = g.pool;
+    base.page_table = g.page_table;
+    base.len_ptr = g.len_ptr;
+    base.rope = g.rope;
+    base.n_layers = g.n_layers;
+    base.n_heads = g.n_heads;
+    base.head_dim = g.head_dim;
+    base.qp = g.qp;
+    base.ap = g.xp_f;
+
+    uint4 pf[kChunk];
+    {   // weights of the first QKV tile go out before anything else
+        WSrc first = {g.layers[0].qkv, nks_d, 3 * d / 16};
+        load_wchunk(pf, first, blockIdx.x, 0, wave, lane);
+    }
+    // ---- embed (+ operand and sums of squares for the first norm)
+    {
+        FastArgs a = base;
+        a.gain = g.layers[0].attn_gain;
+        a.xp_next = g.xp_d;
+        a.ssp_next = g.ssp_a;
+        if (wave == 0)
+            for (int t = blockIdx.x; t < d / 16; t += grid) embed_tile<true>(g.embed, g.tok, a, t, lane);
+        bar_arrive(bar);
+    }
+    const int n_splits = (L + g.M + kFastSplit - 1) / kFastSplit;
+    for (int l = 0; l < g.n_layers; ++l) {
+        const LayerW w = g.layers[l];
+        {   // QKV (+ norm, RoPE, cache write); then the O tile is put in flight
+            FastArgs a = base;
+            a.Wp = w.qkv; a.Xp = (const uint4 *)g.xp_d; a.nks = nks_d; a.n_tiles = 3 * d / 16;
+            a.ssp = g.ssp_a; a.layer = l;
+            WSrc none = {w.o, nks_d, 0};   // the O tile is fetched from inside the attention phase
+            gemm_phase<EPI_QKV, true>(a, none, pf, sh, bar, tiles_before);
+        }
+        {   // attention: (head, split) tasks; the O weights stream in meanwhile
+            bar_wait(bar);
+            const WSrc o_src = {w.o, nks_d, d / 16};
+            bool fetched = false;
+            auto prefetch_o = [&]() {
+                if (!fetched) load_wchunk(pf, o_src, blockIdx.x, 0, wave, lane);
+                fetched = true;
+            };
+            for (int t = blockIdx.x; t < g.n_heads * n_splits; t += grid) {
+                const int head = t % g.n_heads, split = t / g.n_heads;
+                attn_task<DH, true>(attn_shared<DH>(sh), head, split, L, (const uint4 *)g.qp, g.pool, g.page_table, g.M, l,
+                                    g.n_layers, g.n_heads, g.max_splits, g.scale, g.part, g.head_counter, g.xp_att, 8,
+                                    prefetch_o);
+                block_sync_lds();
+            }
+            prefetch_o();
+            bar_arrive(bar);
+        }
+        {   // O (+ residual, operand and sums for the FFN norm)
+            FastArgs a = base;
+            a.Wp = w.o; a.Xp = (const uint4 *)g.xp_att; a.nks = nks_d; a.n_tiles = d / 16;
+            a.gain = w.ffn_gain; a.xp_next = g.xp_d; a.ssp_next = g.ssp_b;
+            WSrc next = {w.gu, nks_d, F / 8};
+            gemm_phase<EPI_RESIDUAL, true>(a, next, pf, sh, bar, tiles_before);
+        }
+        {   // gate / up (+ norm, SwiGLU)
+            FastArgs a = base;
+            a.Wp = w.gu; a.Xp = (const uint4 *)g.xp_d; a.nks = nks_d; a.n_tiles = F / 8;
+            a.ssp = g.ssp_b;
+            WSrc next = {w.down, nks_f, d / 16};
+            gemm_phase<EPI_GATE_UP, true>(a, next, pf, sh, bar, tiles_before);
+        }
+        {   // down (+ residual, operand and sums for the next norm)
+            FastArgs a = base;
+            a.Wp = w.down; a.Xp = (const uint4 *)g.xp_f; a.nks = nks_f; a.n_tiles = d / 16;
+            const bool more = l + 1 < g.n_layers;
+            a.gain = more ? g.layers[l + 1].attn_gain : g.final_gain;
+            a.xp_next = g.xp_d; a.ssp_next = g.ssp_a;
+            WSrc next = {more ? g.layers[l + 1].qkv : g.wp_lm, nks_d, more ? 3 * d / 16 : g.V / 16};
+            gemm_phase<EPI_RESIDUAL, false>(a, next, pf, sh, bar, tiles_before);
+        }
+    }
+    {   // LM head (+ final norm) with per-tile argmax
+        FastArgs a = base;
+        a.Wp = g.wp_lm; a.Xp = (const uint4 *)g.xp_d; a.nks = nks_d; a.n_tiles = g.V / 16;
+        a.ssp = g.ssp_a; a.Y = g.logits; a.ldy = g.V; a.amax = g.amax;
+        WSrc none = {g.wp_lm, nks_d, 0};
+        gemm_phase<EPI_LM_ARGMAX, true>(a, none, pf, sh, bar, tiles_before);
+    }
+    // ---- argmax over the tile winners, acceptance, commit (blocks 0..M-1, one row each)
+    bar_wait(bar);
+    if ((int)blockIdx.x < g.M) {
+        const int r = blockIdx.x, n_tiles = g.V / 16;
+        float best = -INFINITY;
+        int besti = 0x7fffffff;
+        for (int t = threadIdx.x; t < n_tiles; t += kFastThreads) {
+            uint2 pk = ld8_at<true>(reinterpret_cast<const uint2 *>(g.amax), (uint32_t)(t * 32 + r));
+            float v = __uint_as_float(pk.y);
+            int i = (int)pk.x;
+            if (v > best || besti == 0x7fffffff || (v == best && i < besti)) { best = v; besti = i; }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            float ov = __shfl_xor(best, off, kWave);
+            int oi = __shfl_xor(besti, off, kWave);
+            if (ov > best || (ov == best && oi < besti)) { best = ov; besti = oi; }
+        }
+        if (lane == 0) { bval[wave] = best; bidx[wave] = besti; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int w2 = 1; w2 < kFastWaves; ++w2)
+                if (bval[w2] > best || (bval[w2] == best && bidx[w2] < besti)) { best = bval[w2]; besti = bidx[w2]; }
+            st_agent(g.result + 2 + r, (int32_t)besti);
+            wait_stores();
+            last_row = __hip_atomic_fetch_add(g.row_counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)(g.M - 1);
+        }
+        __syncthreads();
+        if (last_row && threadIdx.x == 0) {
+            const int32_t *pred = g.result + 2;
+            int acc_n = 0;
+            if (g.mode == 0) {
+                while (acc_n < g.M - 1 && g.tok[acc_n + 1] == ld_agent(pred + acc_n)) ++acc_n;
+            } else {
+                acc_n = g.M - 1;
+            }
+            g.result[0] = acc_n;
+            g.result[1] = ld_agent(pred + acc_n);
+            *g.len_ptr = L + 1 + acc_n;
+            st_agent(g.row_counter, 0u);
+        }
+    }
+}
+
+}  // namespace anpd
