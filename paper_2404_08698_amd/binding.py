@@ -129,6 +129,12 @@ def lib():
     return L
 
 
+def _alive() -> bool:
+    """False once the interpreter is shutting down (module globals are being cleared)."""
+    import sys
+    return _lib is not None and lib is not None and not sys.is_finalizing()
+
+
 def _check(rc: int) -> int:
     if rc < 0:
         raise AnpdError(rc, lib().anpd_last_error().decode("utf-8", "replace"))
@@ -150,11 +156,15 @@ class NgramTable:
         self._h = h
 
     def close(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _alive():
             lib().anpd_ngram_destroy(self._h)
-            self._h = None
+        self._h = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
     def reset(self) -> None:
         _check(lib().anpd_ngram_reset(self._h))
@@ -224,9 +234,15 @@ class Model:
         self.max_window = max_window
 
     def close(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _alive():
             lib().anpd_model_destroy(self._h)
-            self._h = None
+        self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
     def trace(self, enable: bool):
         """Barrier timestamps of the one-kernel step: returns an int64 CUDA tensor [grid][1024] (or None)."""
@@ -271,11 +287,15 @@ class KVCache:
         self.max_tokens = max_tokens
 
     def close(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _alive():
             lib().anpd_kv_destroy(self._h)
-            self._h = None
+        self._h = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
     @property
     def length(self) -> int:
@@ -384,10 +404,19 @@ def greedy_generate(model: Model, kv: KVCache, prompt: Sequence[int], n_tokens: 
     return out
 
 
+def adaptive_draft_length(levels: Sequence[int], k_max: int) -> int:
+    """Draft length chosen from the level that answered the first draft: 2^(level - 2), capped
+    (level 2 -> 1 draft, 3 -> 2, 4 -> 4, 5 -> 8, 6 -> 16); no answer -> no drafts."""
+    if not levels:
+        return 0
+    return max(1, min(k_max, 1 << (levels[0] - 2)))
+
+
 def anpd_generate(model: Model, kv: KVCache, table: NgramTable, prompt: Sequence[int], K: int, n_tokens: int,
-                  stream=None, drafter=None) -> Dict[str, object]:
+                  stream=None, drafter=None, adaptive: bool = False) -> Dict[str, object]:
     """Algorithm 1: commit, draft K tokens from the table, verify, accept the
-    matching prefix, continue from the LLM's own token."""
+    matching prefix, continue from the LLM's own token.  ``adaptive`` cuts the
+    drafts of a step to adaptive_draft_length()."""
     table.reset()
     table.update(prompt)
     c = prefill(model, kv, prompt, stream)
@@ -396,7 +425,12 @@ def anpd_generate(model: Model, kv: KVCache, table: NgramTable, prompt: Sequence
     while len(out) < n_tokens:
         table.update([c])
         out.append(c)
-        drafts = drafter(len(out), K) if drafter is not None else table.propose(K)[0]
+        if drafter is not None:
+            drafts = drafter(len(out), K)
+        else:
+            drafts, levels = table.propose(K)
+            if adaptive:
+                drafts = drafts[:adaptive_draft_length(levels, K)]
         a, nxt = verify(model, kv, [c] + drafts, VERIFY, stream=stream)
         if a:
             table.update(drafts[:a])

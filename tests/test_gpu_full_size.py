@@ -1,0 +1,138 @@
+"""Parity at the benchmark's own sizes and launch configuration, and at the other
+workloads' distinguishing shapes (13B widths, long paged context)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import anpd as oanpd
+from oracle import decoder as od
+from paper_2404_08698_amd import binding as B
+from paper_2404_08698_amd import synth
+from helpers import TOL, top2_gap
+
+pytestmark = pytest.mark.gpu
+
+
+def _seed_both(shape, dec, kvs, n_tokens, seed):
+    for layer in range(shape.n_layers):
+        k, v = synth.kv_fill(shape, seed, layer, n_tokens, device="cuda")
+        kf, vf = k.float().contiguous(), v.float().contiguous()
+        dec.kv_load(layer, 0, kf.cpu().numpy(), vf.cpu().numpy())
+        for kv in kvs:
+            kv.write(layer, 0, kf, vf)
+    dec.set_length(n_tokens)
+    for kv in kvs:
+        kv.truncate(n_tokens)
+
+
+def _step_logits(model, kv, window):
+    buf = torch.empty(len(window), model.vocab, dtype=torch.float32, device="cuda")
+    a, nxt, preds = B.verify(model, kv, window, B.VERIFY, want_predicts=True, out_logits=buf)
+    return a, nxt, preds, buf
+
+
+def test_llama7b_step_in_the_bench_configuration():
+    """One verification step of the 7B shape, window 6, 512 cached tokens: the persistent kernel
+    (what bench.py times) against the fp64 oracle on all 6 x 32000 logits, and against the
+    one-launch-per-operation path bit for bit."""
+    shape = synth.LLAMA_7B
+    L, K = 512, 5
+    w = synth.make_weights(shape, 2, device="cuda")
+    model = B.Model(shape, w, max_window=32, max_positions=L + 64)
+    model_l = B.Model(shape, w, max_window=32, max_positions=L + 64, gemm_path=B.GEMM_MFMA_LAUNCHES)
+    kv, kv_l = B.KVCache(model, L + 64), B.KVCache(model_l, L + 64)
+    w_host = {k_: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k_, v in w.items()}
+    dec = od.Decoder(shape, w_host, L + 64)
+    _seed_both(shape, dec, [kv, kv_l], L, seed=7)
+    window = synth.random_tokens(shape.vocab, K + 1, 5)
+
+    ref = dec.forward(window)
+    a, nxt, preds, got = _step_logits(model, kv, window)
+    a2, nxt2, preds2, got2 = _step_logits(model_l, kv_l, window)
+    assert torch.equal(got, got2) and (a, nxt, preds) == (a2, nxt2, preds2)
+    g = got.cpu().numpy().astype(np.float64)
+    err = float(np.max(np.abs(g - ref)))
+    print("7B step: max |logit error| = %.2e, logit std %.3f" % (err, float(np.std(ref))))
+    assert err < TOL["bf16"]
+    assert np.std(ref) > 0.3
+    ref_preds = [od.argmax(ref[r]) for r in range(K + 1)]
+    for r in range(K + 1):
+        if top2_gap(ref[r]) > TOL["bf16"]:
+            assert preds[r] == ref_preds[r]
+    a_ref = oanpd.accept_length(window[1:], ref_preds)
+    if all(top2_gap(ref[r]) > TOL["bf16"] for r in range(a_ref + 1)):
+        assert (a, nxt) == (a_ref, ref_preds[a_ref])
+    assert kv.length == L + 1 + a
+
+    # row 0 of the window == the plain greedy step at the same position, bit for bit
+    kv.truncate(L)
+    _, _, _, one = _step_logits(model, kv, window[:1])
+    assert torch.equal(one[0], got[0])
+    # the K and V rows the step wrote match the oracle's cache (bf16 storage, rounding ties aside)
+    k_gpu, v_gpu = kv.read(shape.n_layers - 1, L, 1)
+    k_ref, v_ref = dec.kv_read(shape.n_layers - 1, L, 1)
+    assert np.max(np.abs(k_gpu.cpu().numpy() - k_ref)) < 0.05 and np.max(np.abs(v_gpu.cpu().numpy() - v_ref)) < 0.05
+
+
+def test_13b_widths_two_layers():
+    """d_model 5120, 40 heads, FFN 13824: the register-resident GEMM form with 20 k-steps per wave
+    and the streaming form at K = 13824, windows of 9 (the 13B workload's k + 1) and fewer rows."""
+    shape = dataclasses.replace(synth.LLAMA_13B, n_layers=2)
+    L = 300
+    w = synth.make_weights(shape, 4, device="cuda")
+    model = B.Model(shape, w, max_window=16, max_positions=L + 32)
+    kv = B.KVCache(model, L + 32)
+    w_host = {k_: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k_, v in w.items()}
+    dec = od.Decoder(shape, w_host, L + 32)
+    _seed_both(shape, dec, [kv], L, seed=8)
+    full = None
+    for M in (9, 1, 6):
+        kv.truncate(L)
+        window = synth.random_tokens(shape.vocab, 9, 11)[:M]
+        ref = dec.forward(window)
+        _, _, preds, got = _step_logits(model, kv, window)
+        err = float(np.max(np.abs(got.cpu().numpy().astype(np.float64) - ref)))
+        assert err < TOL["bf16"], (M, err)
+        for r in range(M):
+            if top2_gap(ref[r]) > TOL["bf16"]:
+                assert preds[r] == od.argmax(ref[r])
+        if full is None:
+            full = got
+        else:
+            assert torch.equal(got, full[:M])
+
+
+def test_long_paged_context_and_adaptive_draft_length():
+    """3584 cached tokens in 16-token pages handed out in a scrambled order; windows up to 17 rows."""
+    shape = synth.MID_BF16
+    L = 3584
+    w = synth.make_weights(shape, 5)
+    wc = {k_: ([t.cuda() for t in v] if isinstance(v, list) else v.cuda()) for k_, v in w.items()}
+    model = B.Model(shape, wc, max_window=32, max_positions=L + 600)
+    kv = B.KVCache(model, L + 600)
+    n = kv.num_pages
+    kv.set_page_order([(37 * i + 11) % n for i in range(n)])
+    dec = od.Decoder(shape, w, L + 600)
+    _seed_both(shape, dec, [kv], L, seed=9)
+    full = None
+    for M in (17, 1, 9, 6):
+        kv.truncate(L)
+        window = synth.random_tokens(shape.vocab, 17, 13)[:M]
+        ref = dec.forward(window)
+        _, _, _, got = _step_logits(model, kv, window)
+        assert float(np.max(np.abs(got.cpu().numpy().astype(np.float64) - ref))) < TOL["bf16"]
+        if full is None:
+            full = got
+        else:
+            assert torch.equal(got, full[:M])
+    # adaptive draft length from the level that answered the first draft: k = 2^(level - 2), 1..16
+    kv.truncate(0)
+    prompt = synth.markov_stream(shape.vocab, 400, 0.2, 4, 16, 5)
+    ref_tokens = B.greedy_generate(model, kv, prompt, 96)
+    kv.truncate(0)
+    table = B.NgramTable(2, 6, shape.vocab)
+    res = B.anpd_generate(model, kv, table, prompt, 16, 96, adaptive=True)
+    assert res["tokens"] == ref_tokens
+    assert res["n_steps"] <= 96
