@@ -160,9 +160,22 @@ template <bool COH = false>
 __device__ __forceinline__ void compute_rinv(const FastArgs &a, float *rinv /* LDS [32] */, float *scratch /* LDS [kFastThreads] */)
 {
     const int m = threadIdx.x & 31, g = threadIdx.x >> 5;
+    // 16 loads in flight per thread: one memory round trip for d_model <= 4096 instead of one per
+    // term (the terms are still added in increasing tile order)
+    constexpr int G = kFastThreads / 32, B = 16;
     float s = 0.f;
-    if (m < a.M)
-        for (int t = g; t < a.n_ss; t += kFastThreads / 32) s += ldf_at<COH>(a.ssp, (uint32_t)(t * 32 + m));
+    if (m < a.M) {
+        for (int t0 = g; t0 < a.n_ss; t0 += B * G) {
+            float v[B];
+#pragma unroll
+            for (int u = 0; u < B; ++u) {
+                const int t = t0 + u * G;
+                v[u] = ldf_at<COH>(a.ssp, (uint32_t)((t < a.n_ss ? t : t0) * 32 + m));
+            }
+#pragma unroll
+            for (int u = 0; u < B; ++u) s += (t0 + u * G < a.n_ss) ? v[u] : 0.f;
+        }
+    }
     scratch[g * 32 + m] = s;
     block_sync_lds();
     if (threadIdx.x < 32) {
