@@ -153,36 +153,41 @@ struct FastArgs {
 };
 
 // rinv[m] = 1 / sqrt(mean(x[m]^2) + eps) for the window rows, from the producer's per-tile partial
-// sums.  All threads of the block take part: thread (m = tid % 32, g = tid / 32) adds the
-// partials of tiles g, g + G, ... (G = kFastThreads / 32) in increasing order, then row m adds
-// the G group sums in increasing g.  The order depends on the tile count only.  Ends with a block barrier.
+// sums.  The order of the additions is the same for every window class: the partials of tiles
+// g, g + 64, g + 128, ... are added in increasing order for each of 64 groups g, then the 64 group
+// sums in increasing g.  Class 8 gives each thread one (row, group) pair, the other classes four
+// groups of one of 32 rows; all of a thread's loads are in flight together.  Ends with a block
+// barrier.  scratch: 64 * 32 floats of LDS.
 template <bool COH = false>
-__device__ __forceinline__ void compute_rinv(const FastArgs &a, float *rinv /* LDS [32] */, float *scratch /* LDS [kFastThreads] */)
+__device__ __forceinline__ void compute_rinv(const FastArgs &a, float *rinv /* LDS [32] */, float *scratch /* LDS [2048] */)
 {
-    const int m = threadIdx.x & 31, g = threadIdx.x >> 5;
-    // 16 loads in flight per thread: one memory round trip for d_model <= 4096 instead of one per
-    // term (the terms are still added in increasing tile order)
-    constexpr int G = kFastThreads / 32, B = 16;
-    float s = 0.f;
-    if (m < a.M) {
-        for (int t0 = g; t0 < a.n_ss; t0 += B * G) {
-            float v[B];
+    constexpr int NG = 64, B = 4;
+    const int tid = fresh_tid();
+    const int rows = a.cls == 8 ? 8 : 32;
+    const int slots = kFastThreads / rows;            // 64 or 16 threads per row
+    const int m = tid % rows, g0 = tid / rows;
+    for (int g = g0; g < NG; g += slots) {
+        float s = 0.f;
+        if (m < a.M) {
+            for (int t0 = g; t0 < a.n_ss; t0 += B * NG) {
+                float v[B];
 #pragma unroll
-            for (int u = 0; u < B; ++u) {
-                const int t = t0 + u * G;
-                v[u] = ldf_at<COH>(a.ssp, (uint32_t)((t < a.n_ss ? t : t0) * 32 + m));
+                for (int u = 0; u < B; ++u) {
+                    const int t = t0 + u * NG;
+                    v[u] = ldf_at<COH>(a.ssp, (uint32_t)((t < a.n_ss ? t : t0) * 32 + m));
+                }
+#pragma unroll
+                for (int u = 0; u < B; ++u) s += (t0 + u * NG < a.n_ss) ? v[u] : 0.f;
             }
-#pragma unroll
-            for (int u = 0; u < B; ++u) s += (t0 + u * G < a.n_ss) ? v[u] : 0.f;
         }
+        scratch[g * 32 + m] = s;
     }
-    scratch[g * 32 + m] = s;
     block_sync_lds();
-    if (threadIdx.x < 32) {
+    if (tid < rows) {
         float tot = 0.f;
-#pragma unroll
-        for (int gg = 0; gg < kFastThreads / 32; ++gg) tot += scratch[gg * 32 + threadIdx.x];
-        rinv[threadIdx.x] = 1.0f / sqrtf(tot * a.inv_d + a.eps);
+#pragma unroll 8
+        for (int g = 0; g < NG; ++g) tot += scratch[g * 32 + tid];
+        rinv[tid] = 1.0f / sqrtf(tot * a.inv_d + a.eps);
     }
     block_sync_lds();
 }
@@ -505,7 +510,6 @@ template <int DH>
 struct AttnShared {
     float red[kFastWaves / 2][DH / 16][32][4];
     float wmax[kFastWaves][8], wden[kFastWaves][8];
-    float gm[32], gden[32];
     bool last;
 };
 
@@ -513,49 +517,93 @@ struct NoPrefetch {
     __device__ __forceinline__ void operator()() const {}
 };
 
-// One (head, split) task; every thread of the block calls it.  `after_loads` runs right after the
-// task's own K / V loads have been issued (the persistent kernel puts its weight prefetch there, so
-// that the prefetch queues behind the loads attention is waiting for, not in front of them).
-template <int DH, bool COH = false, typename AfterLoads = NoPrefetch>
-__device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int split, int L, const uint4 *__restrict__ qp,
-                                          const bf16_t *__restrict__ pool, const int32_t *__restrict__ page_table, int M,
-                                          int layer, int n_layers, int n_heads, int max_splits, float scale,
-                                          float *__restrict__ part, uint32_t *__restrict__ head_counter,
-                                          bf16_t *__restrict__ xp_att, int cls, AfterLoads after_loads = AfterLoads())
-{
-    constexpr int NKS = DH / 32, NDT = DH / 16;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, slot = lane & 15, kg = lane >> 4;
-    const int key0 = split * kFastSplit + wave * 16;
-    const bool active = key0 < L + M;
-    ANPD_STAMP(0);
+// This wave's page of a (head, split) task: K and V fragments in registers.
+template <int DH>
+struct AttnKV {
+    uint4 kf[DH / 32];
+    uint2 vf[DH / 16];
+    bool loaded;
+};
 
-    uint4 kf[NKS];
-    uint2 vf[NDT];
+// Requests the wave's K / V page.  With only_old, only a page that lies wholly below position L:
+// such a page was written by earlier steps, so the persistent kernel can request it before the
+// barrier that ends the QKV phase (the window's own rows are written in that phase).
+template <int DH, bool COH>
+__device__ __forceinline__ void attn_load_kv(AttnKV<DH> &kv, int head, int split, int L, int M,
+                                             const bf16_t *__restrict__ pool, const int32_t *__restrict__ page_table,
+                                             int layer, int n_layers, int n_heads, bool only_old)
+{
+    const int tid = fresh_tid();
+    constexpr int NKS = DH / 32, NDT = DH / 16;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int key0 = split * kFastSplit + wave * 16;
 #pragma unroll
-    for (int i = 0; i < NKS; ++i) kf[i] = make_uint4(0, 0, 0, 0);
+    for (int i = 0; i < NKS; ++i) kv.kf[i] = make_uint4(0, 0, 0, 0);
 #pragma unroll
-    for (int i = 0; i < NDT; ++i) vf[i] = make_uint2(0, 0);
-    if (active) {
+    for (int i = 0; i < NDT; ++i) kv.vf[i] = make_uint2(0, 0);
+    kv.loaded = false;
+    if (key0 < L + M && (!only_old || key0 + 15 < L)) {
         const int page = __builtin_amdgcn_readfirstlane(page_table[key0 >> 4]);
         const uint4 *kp = reinterpret_cast<const uint4 *>(pool + kvf_base(page, layer, n_layers, 0, head, n_heads, DH));
         const uint2 *vp = reinterpret_cast<const uint2 *>(pool + kvf_base(page, layer, n_layers, 1, head, n_heads, DH));
 #pragma unroll
-        for (int i = 0; i < NKS; ++i) kf[i] = ld16_at<COH>(kp, (uint32_t)(i * 64 + lane));
+        for (int i = 0; i < NKS; ++i) kv.kf[i] = ld16_at<COH>(kp, (uint32_t)(i * 64 + lane));
 #pragma unroll
-        for (int i = 0; i < NDT; ++i) vf[i] = ld8_at<COH>(vp, (uint32_t)(i * 64 + lane));
+        for (int i = 0; i < NDT; ++i) kv.vf[i] = ld8_at<COH>(vp, (uint32_t)(i * 64 + lane));
+        kv.loaded = true;
+    }
+}
+
+// Partial results of the splits: outputs [head][split][32 rows][DH], then (maximum, denominator)
+// pairs [head][split][32 rows][2].
+__device__ __forceinline__ size_t part_o_index(int head, int split, int max_splits, int row, int DH)
+{
+    return (((size_t)head * max_splits + split) * 32 + row) * DH;
+}
+__device__ __forceinline__ size_t part_s_index(int n_heads, int head, int split, int max_splits, int row, int DH)
+{
+    return (size_t)n_heads * max_splits * 32 * DH + (((size_t)head * max_splits + split) * 32 + row) * 2;
+}
+
+// One (head, split) task; every thread of the block calls it.  kv holds the wave's page if
+// kv.loaded, else it is requested here.  `after_loads` runs right after the task's own loads have
+// been issued (the persistent kernel puts its weight prefetch there, so that the prefetch queues
+// behind the loads attention is waiting for, not in front of them).
+template <int DH, bool COH = false, typename AfterLoads = NoPrefetch>
+__device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, int head, int split, int L,
+                                          const uint4 *__restrict__ qp, const bf16_t *__restrict__ pool,
+                                          const int32_t *__restrict__ page_table, int M, int layer, int n_layers, int n_heads,
+                                          int max_splits, float scale, float *__restrict__ part,
+                                          uint32_t *__restrict__ head_counter, bf16_t *__restrict__ xp_att, int cls,
+                                          AfterLoads after_loads = AfterLoads())
+{
+    const int tid = fresh_tid();
+    constexpr int NKS = DH / 32, NDT = DH / 16;
+    const int lane = tid & 63, wave = tid >> 6, slot = lane & 15, kg = lane >> 4;
+    const int key0 = split * kFastSplit + wave * 16;
+    const bool active = key0 < L + M;
+    ANPD_STAMP(0);
+
+    if (!kv.loaded) attn_load_kv<DH, COH>(kv, head, split, L, M, pool, page_table, layer, n_layers, n_heads, false);
+    uint4 qf[NKS];
+    {
+        const uint4 *q = qp + ((size_t)(head * 4) * NKS) * 64;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) qf[ks] = ld16_at<COH>(q, (uint32_t)(ks * 64 + lane));
     }
     after_loads();
 
     for (int rg = 0; rg * 8 < M; ++rg) {
         // ---- scores S[key][row]
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        const uint4 *q = qp + ((size_t)(head * 4 + rg) * NKS) * 64;
-        uint4 qf[NKS];
+        if (rg > 0) {
+            const uint4 *q = qp + ((size_t)(head * 4 + rg) * NKS) * 64;
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) qf[ks] = ld16_at<COH>(q, (uint32_t)(ks * 64 + lane));
+            for (int ks = 0; ks < NKS; ++ks) qf[ks] = ld16_at<COH>(q, (uint32_t)(ks * 64 + lane));
+        }
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[ks]),
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kv.kf[ks]),
                                                           __builtin_bit_cast(bf16x8, qf[ks]), acc, 0, 0, 0);
         const int m = rg * 8 + (slot & 7);
         float sc[4], mx = kMasked;
@@ -600,7 +648,7 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
 #pragma unroll
         for (int dt = 0; dt < NDT; ++dt) {
             f32x4 o = {0.f, 0.f, 0.f, 0.f};
-            o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4s, vf[dt]), pb, o, 0, 0, 0);
+            o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4s, kv.vf[dt]), pb, o, 0, 0, 0);
             f32x4 lo;
 #pragma unroll
             for (int i = 0; i < 4; ++i) lo[i] = row_down8(o[i]);
@@ -630,21 +678,16 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
                 f32x4 tot = *reinterpret_cast<const f32x4 *>(&sh.red[0][dt][cl][0]);
 #pragma unroll
                 for (int w = 1; w < HW; ++w) tot += *reinterpret_cast<const f32x4 *>(&sh.red[w][dt][cl][0]);
-                if (row < M) {
-                    float *dst = part + (((size_t)head * max_splits + split) * 32 + row) * (DH + 2) + 16 * dt + 4 * kg;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) st_agent(dst + i, tot[i]);
-                }
+                if (row < M) stc16<true>(part + part_o_index(head, split, max_splits, row, DH) + 16 * dt + 4 * kg, tot);
             }
         }
-        if (threadIdx.x < 8 && rg * 8 + threadIdx.x < M) {
-            const int mm = threadIdx.x;
-            size_t b2 = (((size_t)head * max_splits + split) * 32 + rg * 8 + mm) * (DH + 2) + DH;
+        if (tid < 8 && rg * 8 + tid < M) {
+            const int mm = tid;
             float bmx = sh.wmax[0][mm], dsum = sh.wden[0][mm];
 #pragma unroll
             for (int w = 1; w < kFastWaves; ++w) { bmx = fmaxf(bmx, sh.wmax[w][mm]); dsum += sh.wden[w][mm]; }
-            st_agent(part + b2, bmx);
-            st_agent(part + b2 + 1, dsum);
+            stc8<true>(part + part_s_index(n_heads, head, split, max_splits, rg * 8 + mm, DH),
+                       make_uint2(__float_as_uint(bmx), __float_as_uint(dsum)));
         }
         ANPD_STAMP(10);
         block_sync_lds();
@@ -657,53 +700,56 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, int head, int spli
     block_sync_lds();
     ANPD_STAMP(3);
     const int n_blocks = (L + M + kFastSplit - 1) / kFastSplit;
-    if (threadIdx.x == 0)
+    if (tid == 0)
         sh.last = __hip_atomic_fetch_add(&head_counter[head], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
                   (uint32_t)(n_blocks - 1);
     block_sync_lds();
     ANPD_STAMP(4);
     if (!sh.last) return;
-    if (threadIdx.x == 0) st_agent(&head_counter[head], 0u);
-    const float *ph = part + ((size_t)head * max_splits) * 32 * (DH + 2);
-    const size_t stride = (size_t)32 * (DH + 2);
-    // global maximum and denominator of every row: wave w takes rows w, w + 8, ...; lanes stride over the splits
-    for (int row = wave; row < M; row += kFastWaves) {
+    if (tid == 0) st_agent(&head_counter[head], 0u);
+    // Every thread merges four adjacent output elements of a row on its own: it reads the
+    // (maximum, denominator) pair of each split of the row together with the split's outputs,
+    // eight splits per round trip, and forms the row's global maximum and denominator itself.
+    // Fixed order: splits ascending.
+    constexpr int SB = 8, DQ = DH / 4;
+    const uint4 *po = reinterpret_cast<const uint4 *>(part + part_o_index(head, 0, max_splits, 0, DH));
+    const uint2 *ps = reinterpret_cast<const uint2 *>(part + part_s_index(n_heads, head, 0, max_splits, 0, DH));
+    for (int idx = tid; idx < M * DQ; idx += kFastThreads) {
+        const int row = idx / DQ, e4 = idx - row * DQ;
         const int ns = (L + row) / kFastSplit + 1;
-        const uint32_t ro = (uint32_t)row * (DH + 2);
         float g = kMasked;
-        for (int s2 = lane; s2 < ns; s2 += 64) g = fmaxf(g, ldf_at<true>(ph, ro + (uint32_t)(s2 * stride + DH)));
-        g = wave_max(g);
-        float dsum = 0.f;
-        for (int s2 = lane; s2 < ns; s2 += 64)
-            dsum += expf(ldf_at<true>(ph, ro + (uint32_t)(s2 * stride + DH)) - g) *
-                    ldf_at<true>(ph, ro + (uint32_t)(s2 * stride + DH + 1));
-        dsum = wave_sum(dsum);
-        if (lane == 0) { sh.gm[row] = g; sh.gden[row] = dsum; }
-    }
-    block_sync_lds();
-    ANPD_STAMP(5);
-    for (int idx = threadIdx.x; idx < M * DH; idx += kFastThreads) {
-        const int row = idx / DH, e = idx - row * DH;
-        const int ns = (L + row) / kFastSplit + 1;
-        const uint32_t ro = (uint32_t)row * (DH + 2);
-        const float g = sh.gm[row];
-        float o = 0.f;
-        for (int s0 = 0; s0 < ns; s0 += 4) {
-            float ov[4], bv[4];
+        if (ns > SB)   // long contexts: the maximum needs a pass of its own
+            for (int s2 = 0; s2 < ns; ++s2) g = fmaxf(g, __uint_as_float(ld8_at<true>(ps, (uint32_t)(s2 * 32 + row)).x));
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
+        float den = 0.f;
+        for (int s0 = 0; s0 < ns; s0 += SB) {
+            uint4 ov[SB];
+            uint2 st[SB];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const bool okj = s0 + j < ns;
-                ov[j] = okj ? ldf_at<true>(ph, ro + (uint32_t)((s0 + j) * stride + e)) : 0.f;
-                bv[j] = okj ? ldf_at<true>(ph, ro + (uint32_t)((s0 + j) * stride + DH)) : kMasked;
+            for (int j = 0; j < SB; ++j) {
+                const int s2 = s0 + j < ns ? s0 + j : s0;
+                ov[j] = ld16_at<true>(po, (uint32_t)((s2 * 32 + row) * DQ + e4));
+                st[j] = ld8_at<true>(ps, (uint32_t)(s2 * 32 + row));
+            }
+            if (ns <= SB) {
+#pragma unroll
+                for (int j = 0; j < SB; ++j)
+                    if (j < ns) g = fmaxf(g, __uint_as_float(st[j].x));
             }
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (s0 + j < ns) o = fmaf(expf(bv[j] - g), ov[j], o);
+            for (int j = 0; j < SB; ++j) {
+                if (s0 + j < ns) {
+                    const float wgt = expf(__uint_as_float(st[j].x) - g);
+                    den = fmaf(wgt, __uint_as_float(st[j].y), den);
+                    o[0] = fmaf(wgt, __uint_as_float(ov[j].x), o[0]);
+                    o[1] = fmaf(wgt, __uint_as_float(ov[j].y), o[1]);
+                    o[2] = fmaf(wgt, __uint_as_float(ov[j].z), o[2]);
+                    o[3] = fmaf(wgt, __uint_as_float(ov[j].w), o[3]);
+                }
+            }
         }
-        const float v = o / sh.gden[row];
-        const bf16_t hi = f32_to_bf16(v);
-        stc2<COH>(xp_att + xp_offset(cls, row, head * DH + e, 0), hi);
-        stc2<COH>(xp_att + xp_offset(cls, row, head * DH + e, 1), f32_to_bf16(v - bf16_to_f32(hi)));
+        o[0] /= den; o[1] /= den; o[2] /= den; o[3] /= den;
+        xp_store4<COH>(xp_att, cls, row, head * DH + 4 * e4, o);
     }
     ANPD_STAMP(6);
 }
@@ -720,7 +766,9 @@ __global__ __launch_bounds__(kFastThreads) void attn_fast_kernel(const uint4 *__
     __shared__ AttnShared<DH> sh;
     const int L = *len_ptr;
     if ((int)blockIdx.y * kFastSplit >= L + M) return;
-    attn_task<DH>(sh, blockIdx.x, blockIdx.y, L, qp, pool, page_table, M, layer, n_layers, n_heads, max_splits, scale, part,
+    AttnKV<DH> kv;
+    kv.loaded = false;
+    attn_task<DH>(sh, kv, blockIdx.x, blockIdx.y, L, qp, pool, page_table, M, layer, n_layers, n_heads, max_splits, scale, part,
                   head_counter, xp_att, cls);
 }
 

@@ -146,6 +146,16 @@ __device__ __forceinline__ float ldf_at(const float *base, uint32_t idx)
     return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(wave_buffer(base), (int)(idx * 4u), 0, kAuxCoherent));
 }
 
+// threadIdx.x as a value the optimiser treats as new at every call.  In the persistent kernel,
+// lane-dependent offsets derived from the plain threadIdx.x are loop invariant over the layers: they
+// get computed once up front, by the dozen, and then live in scratch memory.
+__device__ __forceinline__ int fresh_tid()
+{
+    int t = threadIdx.x;
+    asm volatile("" : "+v"(t));
+    return t;
+}
+
 // Block barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding
 // global load of the wave, which would drain the weight prefetch at each tile boundary.
 __device__ __forceinline__ void block_sync_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }

@@ -71,15 +71,16 @@ struct GridBarrier {
     int n_ev;
 };
 
-__device__ __forceinline__ void bar_init(GridBarrier &b, const MegaArgs &a)
+template <typename ArgsPtr>
+__device__ __forceinline__ void bar_init(GridBarrier &b, ArgsPtr a)
 {
-    b.ctr = a.bar;
-    b.done = a.bar_epoch;
-    b.error = a.error;
+    b.ctr = a->bar;
+    b.done = a->bar_epoch;
+    b.error = a->error;
     b.ngroups = (gridDim.x % 8 == 0) ? 8 : 1;
     b.gsize = gridDim.x / b.ngroups;
     b.grp = blockIdx.x % b.ngroups;
-    b.trace = a.trace ? a.trace + (size_t)blockIdx.x * kTraceEvents : nullptr;
+    b.trace = a->trace ? a->trace + (size_t)blockIdx.x * kTraceEvents : nullptr;
     b.n_ev = 0;
 }
 
@@ -189,7 +190,8 @@ template <int EPI, bool STATIONARY>
 __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, uint4 (&pf)[kChunk], MegaShared &sh,
                                            GridBarrier &bar, int &tiles_before)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, grid = gridDim.x;
+    const int tid = fresh_tid();
+    const int lane = tid & 63, wave = tid >> 6, grid = gridDim.x;
     const WSrc cur = {a.Wp, a.nks, a.n_tiles};
     const int n_chunks = (((a.nks + kFastWaves - 1) / kFastWaves) + kChunk - 1) / kChunk;
     const int my_tiles = (int)blockIdx.x < cur.n_tiles ? (cur.n_tiles - 1 - (int)blockIdx.x) / grid + 1 : 0;
@@ -216,7 +218,7 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     fetch(wc);
 
     bar_wait(bar);
-    if (my_tiles == 0 && threadIdx.x == 0) bar_signal(bar);
+    if (my_tiles == 0 && tid == 0) bar_signal(bar);
     load_xchunk(x0, a.Xp, a.nks, 0, wave, lane);
     if (STATIONARY) load_xchunk(x1, a.Xp, a.nks, 1, wave, lane);   // else: one chunk ahead, alternating x0 / x1
     if (EPI == EPI_QKV || EPI == EPI_GATE_UP || EPI == EPI_LOGITS || EPI == EPI_LM_ARGMAX)
@@ -277,78 +279,120 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     bar_stamp(bar);
 }
 
+// The kernel's arguments stay in the kernarg segment.  Every phase reads the fields it needs
+// through a pointer the optimiser cannot see through, so nothing read for one phase stays in
+// registers across the others (kept live, these values push the weight pipeline into scratch
+// memory, and a scratch reload queues behind the weight loads in flight).
+typedef const MegaArgs __attribute__((address_space(4))) *MegaArgsK;
+typedef const LayerW __attribute__((address_space(4))) *LayerWK;
+__device__ __forceinline__ MegaArgsK phase_args()
+{
+    MegaArgsK p = (MegaArgsK)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(p));
+    return p;
+}
+__device__ __forceinline__ LayerW layer_weights(MegaArgsK g, int l)
+{
+    LayerWK t = (LayerWK)g->layers + l;   // the table is not written while the kernel runs
+    LayerW w;
+    w.qkv = t->qkv; w.o = t->o; w.gu = t->gu; w.down = t->down;
+    w.attn_gain = t->attn_gain; w.ffn_gain = t->ffn_gain;
+    return w;
+}
+__device__ __forceinline__ FastArgs base_args(MegaArgsK g)
+{
+    FastArgs a = {};
+    a.M = g->M;
+    a.cls = 8;
+    a.inv_d = g->inv_d;
+    a.eps = g->eps;
+    a.n_ss = g->d / 16;
+    a.d = g->d;
+    a.x = g->x;
+    a.pool = g->pool;
+    a.page_table = g->page_table;
+    a.len_ptr = g->len_ptr;
+    a.rope = g->rope;
+    a.n_layers = g->n_layers;
+    a.n_heads = g->n_heads;
+    a.head_dim = g->head_dim;
+    a.qp = g->qp;
+    a.ap = g->xp_f;
+    return a;
+}
+
 template <int DH>
-__global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs g)
+__global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* read through phase_args() */)
 {
     __shared__ MegaShared sh;
     __shared__ float bval[kFastWaves];
     __shared__ int bidx[kFastWaves];
     __shared__ bool last_row;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, grid = gridDim.x;
+    const int grid = gridDim.x;
     GridBarrier bar;
-    bar_init(bar, g);
-    bar_stamp(bar);
-    if (threadIdx.x == 0) sh.tiles_done = 0;   // ordered by the first block barrier below
-    int tiles_before = 0;
-    const int L = *g.len_ptr;
-    const int d = g.d, F = g.F;
-    const int nks_d = (d + 31) / 32, nks_f = (F + 31) / 32;
-
-    FastArgs base = {};
-    base.M = g.M;
-    base.cls = 8;
-    base.inv_d = g.inv_d;
-    base.eps = g.eps;
-    base.n_ss = d / 16;
-    base.d = d;
-    base.x = g.x;
-    base.pool = g.pool;
-    base.page_table = g.page_table;
-    base.len_ptr = g.len_ptr;
-    base.rope = g.rope;
-    base.n_layers = g.n_layers;
-    base.n_heads = g.n_heads;
-    base.head_dim = g.head_dim;
-    base.qp = g.qp;
-    base.ap = g.xp_f;
-
+    int tiles_before = 0, L, n_layers;
     uint4 pf[kChunk];
-    {   // weights of the first QKV tile go out before anything else
-        WSrc first = {g.layers[0].qkv, nks_d, 3 * d / 16};
-        load_wchunk(pf, first, blockIdx.x, 0, wave, lane);
-    }
-    // ---- embed (+ operand and sums of squares for the first norm)
     {
-        FastArgs a = base;
-        a.gain = g.layers[0].attn_gain;
-        a.xp_next = g.xp_d;
-        a.ssp_next = g.ssp_a;
+        MegaArgsK g = phase_args();
+        bar_init(bar, g);
+        bar_stamp(bar);
+        if (threadIdx.x == 0) sh.tiles_done = 0;   // ordered by the first block barrier below
+        L = *g->len_ptr;
+        n_layers = g->n_layers;
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const int d = g->d;
+        const LayerW w0 = layer_weights(g, 0);
+        {   // weights of the first QKV tile go out before anything else
+            WSrc first = {w0.qkv, (d + 31) / 32, 3 * d / 16};
+            load_wchunk(pf, first, blockIdx.x, 0, wave, lane);
+        }
+        // ---- embed (+ operand and sums of squares for the first norm)
+        FastArgs a = base_args(g);
+        a.gain = w0.attn_gain;
+        a.xp_next = g->xp_d;
+        a.ssp_next = g->ssp_a;
         if (wave == 0)
-            for (int t = blockIdx.x; t < d / 16; t += grid) embed_tile<true>(g.embed, g.tok, a, t, lane);
+            for (int t = blockIdx.x; t < d / 16; t += grid) embed_tile<true>(g->embed, g->tok, a, t, lane);
         bar_arrive(bar);
     }
-    const int n_splits = (L + g.M + kFastSplit - 1) / kFastSplit;
-    for (int l = 0; l < g.n_layers; ++l) {
-        const LayerW w = g.layers[l];
+    for (int l = 0; l < n_layers; ++l) {
         {   // QKV (+ norm, RoPE, cache write); then the O tile is put in flight
-            FastArgs a = base;
-            a.Wp = w.qkv; a.Xp = (const uint4 *)g.xp_d; a.nks = nks_d; a.n_tiles = 3 * d / 16;
-            a.ssp = g.ssp_a; a.layer = l;
+            MegaArgsK g = phase_args();
+            const LayerW w = layer_weights(g, l);
+            FastArgs a = base_args(g);
+            const int nks_d = (g->d + 31) / 32;
+            a.Wp = w.qkv; a.Xp = (const uint4 *)g->xp_d; a.nks = nks_d; a.n_tiles = 3 * g->d / 16;
+            a.ssp = g->ssp_a; a.layer = l;
             WSrc none = {w.o, nks_d, 0};   // the O tile is fetched from inside the attention phase
             gemm_phase<EPI_QKV, true>(a, none, pf, sh, bar, tiles_before);
         }
-        {   // attention: (head, split) tasks; the O weights stream in meanwhile
+        {   // attention: (head, split) tasks; the O weights stream in meanwhile.  Cache pages wholly
+            // below the committed length do not depend on this step: the first task's page is
+            // requested before the barrier.
+            MegaArgsK g = phase_args();
+            const LayerW w = layer_weights(g, l);
+            const int tid = fresh_tid();
+            const int lane = tid & 63, wave = tid >> 6;
+            const int M = g->M, n_heads = g->n_heads;
+            const int n_splits = (L + M + kFastSplit - 1) / kFastSplit;
+            const int n_tasks = n_heads * n_splits;
+            AttnKV<DH> kv;
+            kv.loaded = false;
+            if ((int)blockIdx.x < n_tasks)
+                attn_load_kv<DH, true>(kv, blockIdx.x % n_heads, blockIdx.x / n_heads, L, M, g->pool, g->page_table, l,
+                                       n_layers, n_heads, true);
             bar_wait(bar);
-            const WSrc o_src = {w.o, nks_d, d / 16};
+            const WSrc o_src = {w.o, (g->d + 31) / 32, g->d / 16};
             bool fetched = false;
             auto prefetch_o = [&]() {
                 if (!fetched) load_wchunk(pf, o_src, blockIdx.x, 0, wave, lane);
                 fetched = true;
             };
-            for (int t = blockIdx.x; t < g.n_heads * n_splits; t += grid) {
-                const int head = t % g.n_heads, split = t / g.n_heads;
-                attn_task<DH, true>(attn_shared<DH>(sh), head, split, L, (const uint4 *)g.qp, g.pool, g.page_table, g.M, l,
-                                    g.n_layers, g.n_heads, g.max_splits, g.scale, g.part, g.head_counter, g.xp_att, 8,
+            for (int t = blockIdx.x; t < n_tasks; t += grid) {
+                const int head = t % n_heads, split = t / n_heads;
+                if (t != (int)blockIdx.x) kv.loaded = false;
+                attn_task<DH, true>(attn_shared<DH>(sh), kv, head, split, L, (const uint4 *)g->qp, g->pool, g->page_table, M, l,
+                                    n_layers, n_heads, g->max_splits, g->scale, g->part, g->head_counter, g->xp_att, 8,
                                     prefetch_o);
                 block_sync_lds();
             }
@@ -356,44 +400,55 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs g)
             bar_arrive(bar);
         }
         {   // O (+ residual, operand and sums for the FFN norm)
-            FastArgs a = base;
-            a.Wp = w.o; a.Xp = (const uint4 *)g.xp_att; a.nks = nks_d; a.n_tiles = d / 16;
-            a.gain = w.ffn_gain; a.xp_next = g.xp_d; a.ssp_next = g.ssp_b;
-            WSrc next = {w.gu, nks_d, F / 8};
+            MegaArgsK g = phase_args();
+            const LayerW w = layer_weights(g, l);
+            FastArgs a = base_args(g);
+            const int nks_d = (g->d + 31) / 32;
+            a.Wp = w.o; a.Xp = (const uint4 *)g->xp_att; a.nks = nks_d; a.n_tiles = g->d / 16;
+            a.gain = w.ffn_gain; a.xp_next = g->xp_d; a.ssp_next = g->ssp_b;
+            WSrc next = {w.gu, nks_d, g->F / 8};
             gemm_phase<EPI_RESIDUAL, true>(a, next, pf, sh, bar, tiles_before);
         }
         {   // gate / up (+ norm, SwiGLU)
-            FastArgs a = base;
-            a.Wp = w.gu; a.Xp = (const uint4 *)g.xp_d; a.nks = nks_d; a.n_tiles = F / 8;
-            a.ssp = g.ssp_b;
-            WSrc next = {w.down, nks_f, d / 16};
+            MegaArgsK g = phase_args();
+            const LayerW w = layer_weights(g, l);
+            FastArgs a = base_args(g);
+            a.Wp = w.gu; a.Xp = (const uint4 *)g->xp_d; a.nks = (g->d + 31) / 32; a.n_tiles = g->F / 8;
+            a.ssp = g->ssp_b;
+            WSrc next = {w.down, (g->F + 31) / 32, g->d / 16};
             gemm_phase<EPI_GATE_UP, true>(a, next, pf, sh, bar, tiles_before);
         }
         {   // down (+ residual, operand and sums for the next norm)
-            FastArgs a = base;
-            a.Wp = w.down; a.Xp = (const uint4 *)g.xp_f; a.nks = nks_f; a.n_tiles = d / 16;
-            const bool more = l + 1 < g.n_layers;
-            a.gain = more ? g.layers[l + 1].attn_gain : g.final_gain;
-            a.xp_next = g.xp_d; a.ssp_next = g.ssp_a;
-            WSrc next = {more ? g.layers[l + 1].qkv : g.wp_lm, nks_d, more ? 3 * d / 16 : g.V / 16};
+            MegaArgsK g = phase_args();
+            const LayerW w = layer_weights(g, l);
+            FastArgs a = base_args(g);
+            a.Wp = w.down; a.Xp = (const uint4 *)g->xp_f; a.nks = (g->F + 31) / 32; a.n_tiles = g->d / 16;
+            const bool more = l + 1 < n_layers;
+            a.gain = more ? layer_weights(g, l + 1).attn_gain : g->final_gain;
+            a.xp_next = g->xp_d; a.ssp_next = g->ssp_a;
+            WSrc next = {more ? layer_weights(g, l + 1).qkv : g->wp_lm, (g->d + 31) / 32, more ? 3 * g->d / 16 : g->V / 16};
             gemm_phase<EPI_RESIDUAL, false>(a, next, pf, sh, bar, tiles_before);
         }
     }
     {   // LM head (+ final norm) with per-tile argmax
-        FastArgs a = base;
-        a.Wp = g.wp_lm; a.Xp = (const uint4 *)g.xp_d; a.nks = nks_d; a.n_tiles = g.V / 16;
-        a.ssp = g.ssp_a; a.Y = g.logits; a.ldy = g.V; a.amax = g.amax;
-        WSrc none = {g.wp_lm, nks_d, 0};
+        MegaArgsK g = phase_args();
+        FastArgs a = base_args(g);
+        const int nks_d = (g->d + 31) / 32;
+        a.Wp = g->wp_lm; a.Xp = (const uint4 *)g->xp_d; a.nks = nks_d; a.n_tiles = g->V / 16;
+        a.ssp = g->ssp_a; a.Y = g->logits; a.ldy = g->V; a.amax = g->amax;
+        WSrc none = {g->wp_lm, nks_d, 0};
         gemm_phase<EPI_LM_ARGMAX, true>(a, none, pf, sh, bar, tiles_before);
     }
+    MegaArgsK g = phase_args();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // ---- argmax over the tile winners, acceptance, commit (blocks 0..M-1, one row each)
     bar_wait(bar);
-    if ((int)blockIdx.x < g.M) {
-        const int r = blockIdx.x, n_tiles = g.V / 16;
+    if ((int)blockIdx.x < g->M) {
+        const int r = blockIdx.x, n_tiles = g->V / 16;
         float best = -INFINITY;
         int besti = 0x7fffffff;
         for (int t = threadIdx.x; t < n_tiles; t += kFastThreads) {
-            uint2 pk = ld8_at<true>(reinterpret_cast<const uint2 *>(g.amax), (uint32_t)(t * 32 + r));
+            uint2 pk = ld8_at<true>(reinterpret_cast<const uint2 *>(g->amax), (uint32_t)(t * 32 + r));
             float v = __uint_as_float(pk.y);
             int i = (int)pk.x;
             if (v > best || besti == 0x7fffffff || (v == best && i < besti)) { best = v; besti = i; }
@@ -409,23 +464,23 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs g)
         if (threadIdx.x == 0) {
             for (int w2 = 1; w2 < kFastWaves; ++w2)
                 if (bval[w2] > best || (bval[w2] == best && bidx[w2] < besti)) { best = bval[w2]; besti = bidx[w2]; }
-            st_agent(g.result + 2 + r, (int32_t)besti);
+            st_agent(g->result + 2 + r, (int32_t)besti);
             wait_stores();
-            last_row = __hip_atomic_fetch_add(g.row_counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)(g.M - 1);
+            last_row = __hip_atomic_fetch_add(g->row_counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)(g->M - 1);
         }
         __syncthreads();
         if (last_row && threadIdx.x == 0) {
-            const int32_t *pred = g.result + 2;
+            const int32_t *pred = g->result + 2;
             int acc_n = 0;
-            if (g.mode == 0) {
-                while (acc_n < g.M - 1 && g.tok[acc_n + 1] == ld_agent(pred + acc_n)) ++acc_n;
+            if (g->mode == 0) {
+                while (acc_n < g->M - 1 && g->tok[acc_n + 1] == ld_agent(pred + acc_n)) ++acc_n;
             } else {
-                acc_n = g.M - 1;
+                acc_n = g->M - 1;
             }
-            g.result[0] = acc_n;
-            g.result[1] = ld_agent(pred + acc_n);
-            *g.len_ptr = L + 1 + acc_n;
-            st_agent(g.row_counter, 0u);
+            g->result[0] = acc_n;
+            g->result[1] = ld_agent(pred + acc_n);
+            *g->len_ptr = L + 1 + acc_n;
+            st_agent(g->row_counter, 0u);
         }
     }
 }
