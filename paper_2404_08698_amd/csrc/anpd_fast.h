@@ -192,11 +192,55 @@ __device__ __forceinline__ void compute_rinv(const FastArgs &a, float *rinv /* L
     block_sync_lds();
 }
 
+// Operands an epilogue reads from memory.  The persistent kernel requests them when the tile starts:
+// a wave's loads return in order, so a load issued at the epilogue would wait for the weight chunks
+// requested before it, and the gain vector is a first touch that comes from HBM.
+struct EpiPre {
+    f32x4 x, g;       // RESIDUAL: residual row piece and gain
+    float2 cs[4];     // QKV: cos / sin of the four rotary pairs
+    int page;         // QKV: physical page of the row's position
+};
+
+template <int EPI>
+__device__ __forceinline__ void epilogue_preload(const FastArgs &a, int tile, int lane, EpiPre &pre)
+{
+    const int m = lane & 15, kg = lane >> 4;
+    const bool valid = m < 8 && m < a.M;
+    if (EPI == EPI_RESIDUAL) {
+        const int n = tile * 16 + 4 * kg;
+        pre.x = (f32x4){0.f, 0.f, 0.f, 0.f};
+        pre.g = pre.x;
+        if (valid) {
+            pre.x = *reinterpret_cast<const f32x4 *>(a.x + (size_t)m * a.d + n);
+            uint2 gb = *reinterpret_cast<const uint2 *>(a.gain + n);
+            pre.g = (f32x4){__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xffff0000u), __uint_as_float(gb.y << 16),
+                            __uint_as_float(gb.y & 0xffff0000u)};
+        }
+    } else if (EPI == EPI_QKV) {
+        const int T = a.n_heads * a.head_dim / 16;
+        const int which = tile / T, t = tile - which * T;
+        const int pos = *a.len_ptr + m;
+        pre.page = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pre.cs[i] = make_float2(1.f, 0.f);
+        if (valid) {
+            pre.page = a.page_table[pos >> 4];
+            if (which < 2) {
+                const int tph = a.head_dim / 16, half = a.head_dim / 2;
+                const int j = t % tph;
+                const int i0 = 8 * j + 4 * (kg & 1);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pre.cs[i] = a.rope[(size_t)pos * half + i0 + i];
+            }
+        }
+    }
+}
+
 // y: this lane's four outputs D[4 kg + i][m] of tile `tile` for window row m (valid says whether the row exists).
 // Every lane of the wave must call this (the fused forms exchange values with lane ^ 32).
 template <int EPI, bool COH = false>
 __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int kg, f32x4 y, bool valid,
-                                         const float *rinv)
+                                         const float *rinv, const EpiPre *pre = nullptr)
 {
     if (EPI == EPI_PLAIN) {
         if (valid) stc16<COH>(a.Y + (size_t)m * a.ldy + tile * 16 + 4 * kg, y);
@@ -226,11 +270,17 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
         f32x4 v = {0.f, 0.f, 0.f, 0.f};
         if (valid) {
             float *xr = a.x + (size_t)m * a.d + n;
-            v = *reinterpret_cast<const f32x4 *>(xr) + y;
+            f32x4 g;
+            if (pre) {
+                v = pre->x + y;
+                g = pre->g;
+            } else {
+                v = *reinterpret_cast<const f32x4 *>(xr) + y;
+                uint2 gb = *reinterpret_cast<const uint2 *>(a.gain + n);
+                g = (f32x4){__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xffff0000u), __uint_as_float(gb.y << 16),
+                            __uint_as_float(gb.y & 0xffff0000u)};
+            }
             *reinterpret_cast<f32x4 *>(xr) = v;
-            uint2 gb = *reinterpret_cast<const uint2 *>(a.gain + n);
-            f32x4 g = {__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xffff0000u), __uint_as_float(gb.y << 16),
-                       __uint_as_float(gb.y & 0xffff0000u)};
             xp_store4<COH>(a.xp_next, a.cls, m, n, v * g);
         }
         float s = fmaf(v[3], v[3], fmaf(v[2], v[2], fmaf(v[1], v[1], v[0] * v[0])));
@@ -247,7 +297,7 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
 #pragma unroll
         for (int i = 0; i < 4; ++i) other[i] = __shfl_xor(y[i], 32, kWave);
         if (!valid) return;
-        const int page = a.page_table[pos >> 4], tok = pos & 15;
+        const int page = pre ? pre->page : a.page_table[pos >> 4], tok = pos & 15;
         if (which < 2) {
             const int tph = a.head_dim / 16, half = a.head_dim / 2;
             const int h = t / tph, j = t - h * tph;
@@ -255,7 +305,7 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
             f32x4 o;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                float2 cs = a.rope[(size_t)pos * half + i0 + i];
+                float2 cs = pre ? pre->cs[i] : a.rope[(size_t)pos * half + i0 + i];
                 o[i] = kg < 2 ? y[i] * cs.x - other[i] * cs.y : y[i] * cs.x + other[i] * cs.y;
             }
             const int dim = i0 + (kg < 2 ? 0 : half);
@@ -299,7 +349,7 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
 // Sum the per-wave partial tiles (wave order), add hi + lo, run the epilogue.  One wave calls this.
 template <int NT, int EPI, bool COH = false>
 __device__ __forceinline__ void reduce_and_finish(const FastArgs &a, int tile, const float *red /* [nw][NT][256] */,
-                                                  int nw, int lane, const float *rinv)
+                                                  int nw, int lane, const float *rinv, const EpiPre *pre = nullptr)
 {
     const int slot = lane & 15, kg = lane >> 4;
     f32x4 tot[NT];
@@ -313,7 +363,7 @@ __device__ __forceinline__ void reduce_and_finish(const FastArgs &a, int tile, c
         f32x4 lo;
 #pragma unroll
         for (int i = 0; i < 4; ++i) lo[i] = row_down8(tot[0][i]);
-        epilogue<EPI, COH>(a, tile, slot, kg, tot[0] + lo, slot < 8 && slot < a.M, rinv);
+        epilogue<EPI, COH>(a, tile, slot, kg, tot[0] + lo, slot < 8 && slot < a.M, rinv, pre);
     } else {
 #pragma unroll
         for (int p = 0; p < NT / 2; ++p) {

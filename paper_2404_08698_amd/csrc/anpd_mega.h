@@ -164,6 +164,42 @@ __device__ __forceinline__ void load_xchunk(uint4 (&x)[kChunk], const uint4 *Xp,
     }
 }
 
+// Epilogue operands of a block's first tiles, staged in LDS by the wave that will finish the
+// tile.  They do not depend on the previous phase (a weight vector, tables of the step, and the
+// residual rows this same block wrote), so they are requested before the phase barrier and are
+// there when the epilogue runs: a load issued at the epilogue would queue behind the weight
+// loads in flight, and the gain vector comes from HBM.
+constexpr int kPreTiles = 3;
+struct EpiPreLds {
+    f32x4 x[64], g[64];
+    float2 cs[4][64];
+    int page[64];
+};
+template <int EPI>
+__device__ __forceinline__ void pre_to_lds(EpiPreLds &d, const EpiPre &p, int lane)
+{
+    if (EPI == EPI_RESIDUAL) {
+        d.x[lane] = p.x;
+        d.g[lane] = p.g;
+    } else if (EPI == EPI_QKV) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) d.cs[i][lane] = p.cs[i];
+        d.page[lane] = p.page;
+    }
+}
+template <int EPI>
+__device__ __forceinline__ void pre_from_lds(EpiPre &p, const EpiPreLds &d, int lane)
+{
+    if (EPI == EPI_RESIDUAL) {
+        p.x = d.x[lane];
+        p.g = d.g[lane];
+    } else if (EPI == EPI_QKV) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) p.cs[i] = d.cs[i][lane];
+        p.page = d.page[lane];
+    }
+}
+
 struct MegaShared {
     union {
         float red[2][kFastWaves][256];
@@ -172,6 +208,7 @@ struct MegaShared {
     };
     float rinv[32];
     int tiles_done;   // epilogues finished by this block since the kernel started
+    EpiPreLds pre[kPreTiles];
 };
 
 template <int DH>
@@ -214,8 +251,13 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
             next_issued = true;
         }
     };
+    constexpr bool kHasPre = (EPI == EPI_RESIDUAL || EPI == EPI_QKV);
+    const bool stages = kHasPre && wave < kPreTiles && wave < my_tiles;   // this wave finishes tile number `wave`
+    EpiPre pre0;
+    if (stages) epilogue_preload<EPI>(a, blockIdx.x + wave * grid, lane, pre0);
     fetch(wb);
     fetch(wc);
+    if (stages) pre_to_lds<EPI>(sh.pre[wave], pre0, lane);
 
     bar_wait(bar);
     if (my_tiles == 0 && tid == 0) bar_signal(bar);
@@ -257,7 +299,15 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
             float *r = &sh.red[it & 1][0][0];
             *reinterpret_cast<f32x4 *>(r + ((size_t)wave * 64 + lane) * 4) = acc;
             block_sync_lds();
-            if (wave == (it & (kFastWaves - 1))) reduce_and_finish<1, EPI, true>(a, finished, r, kFastWaves, lane, sh.rinv);
+            if (wave == (it & (kFastWaves - 1))) {
+                if (kHasPre && it < kPreTiles) {
+                    EpiPre pre;
+                    pre_from_lds<EPI>(pre, sh.pre[it], lane);
+                    reduce_and_finish<1, EPI, true>(a, finished, r, kFastWaves, lane, sh.rinv, &pre);
+                } else {
+                    reduce_and_finish<1, EPI, true>(a, finished, r, kFastWaves, lane, sh.rinv);
+                }
+            }
             acc = (f32x4){0.f, 0.f, 0.f, 0.f};
             ++it;
         }
