@@ -202,9 +202,9 @@ def main() -> int:
         dom_bytes = weight_bytes
         dom_name = "small-M weight-streaming GEMM (all %d launches of a step)" % round(dom_launches)
     dom_gbs = dom_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
-    # HBM bytes per step from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/verify_step_llama7b_hbm_traffic.md):
-    # measured on the one-launch-per-operation path, which issues the same loads and stores
-    traffic = {"llama7b": 13.778e9 + 0.037e9}.get(args.workload) if shape.dtype == "bf16" else None
+    # HBM bytes per launch of the persistent kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    # (profiles/verify_step_llama7b_hbm_traffic.md): 13 772 MB read + 25 MB written
+    traffic = {"llama7b": 13.772e9 + 0.025e9}.get(args.workload) if shape.dtype == "bf16" else None
 
     # ---- ANPD driven by the N-gram table alone (Algorithm 1 as printed), reported beside it
     ms_ = {"c": c0, "proposed": 0, "accepted": 0, "tokens": 0, "since": 0}

@@ -8,6 +8,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -127,6 +128,7 @@ struct anpd_model {
     bool mega;            // the one-kernel step is available
     long long *trace;     // optional device buffer for barrier timestamps
     int mega_grid;
+    bool plain_launch;    // launch the one-kernel step without the cooperative-launch API (profiling aid)
     uint32_t bar_epoch;
     const void *embed, *final_norm, *lm_head;
     std::vector<const void *> attn_norm, wq, wk, wv, wo, ffn_norm, w_gate, w_up, w_down;
@@ -499,10 +501,18 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, int M, int mode, bool want_log
     m->ev_used = 0;
     mark(m, -1, st);
     void *args[] = {&g};
-    if (c.head_dim == 128)
+    if (m->plain_launch) {
+        // profiling aid (see anpd_model_create): an ordinary launch of the same grid
+        if (c.head_dim == 128)
+            hipLaunchKernelGGL((verify_mega_kernel<128>), dim3((unsigned)m->mega_grid), dim3(kFastThreads), 0, st, g);
+        else
+            hipLaunchKernelGGL((verify_mega_kernel<64>), dim3((unsigned)m->mega_grid), dim3(kFastThreads), 0, st, g);
+        HIP_TRY(hipGetLastError());
+    } else if (c.head_dim == 128) {
         HIP_TRY(hipLaunchCooperativeKernel((const void *)verify_mega_kernel<128>, dim3((unsigned)m->mega_grid), dim3(kFastThreads), args, 0, st));
-    else
+    } else {
         HIP_TRY(hipLaunchCooperativeKernel((const void *)verify_mega_kernel<64>, dim3((unsigned)m->mega_grid), dim3(kFastThreads), args, 0, st));
+    }
     m->bar_epoch += (uint32_t)kMegaBarriers(c.n_layers);
     mark(m, ANPD_PROF_STEP, st);
     return ANPD_OK;
@@ -591,6 +601,13 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
     m->trace = nullptr;
     m->mega_grid = 0;
     m->bar_epoch = 0;
+    // ANPD_MEGA_PLAIN_LAUNCH=1: an ordinary launch of the same grid.  Only for profilers that cannot
+    // cope with the cooperative queue; all blocks are resident only if nothing else runs on the device
+    // (otherwise a barrier wait times out and anpd_verify reports it).
+    {
+        const char *pl = std::getenv("ANPD_MEGA_PLAIN_LAUNCH");
+        m->plain_launch = pl && pl[0] == '1';
+    }
     if (e == hipSuccess && m->mfma && cfg->gemm_path != ANPD_GEMM_MFMA_LAUNCHES && (cfg->d_model + 31) / 32 <= 2 * kChunk * kFastWaves) {
         // the persistent step needs every block resident at once: one block per compute unit
         int per_cu = 0;

@@ -69,6 +69,7 @@ struct GridBarrier {
     int grp, gsize, ngroups;
     long long *trace;
     int n_ev;
+    bool failed;     // (thread 0) a wait of this block gave up, or it saw the error flag: later waits do not spin
 };
 
 template <typename ArgsPtr>
@@ -82,6 +83,7 @@ __device__ __forceinline__ void bar_init(GridBarrier &b, ArgsPtr a)
     b.grp = blockIdx.x % b.ngroups;
     b.trace = a->trace ? a->trace + (size_t)blockIdx.x * kTraceEvents : nullptr;
     b.n_ev = 0;
+    b.failed = false;
 }
 
 __device__ __forceinline__ void bar_stamp(GridBarrier &b)
@@ -115,13 +117,19 @@ __device__ __forceinline__ void bar_arrive(GridBarrier &b)
 // wait for this wave's outstanding loads (the weight prefetch stays in flight).
 __device__ __forceinline__ void bar_wait(GridBarrier &b)
 {
-    if (threadIdx.x == 0) {
+    if (threadIdx.x == 0 && !b.failed) {
         const uint32_t target = b.done * (uint32_t)b.ngroups;
         int spins = 0;
         while ((int32_t)(ld_agent(b.ctr) - target) < 0) {
             __builtin_amdgcn_s_sleep(4);
-            if (++spins > (1 << 21)) {  // about a second: something is wrong, do not hang the GPU
+            ++spins;
+            if ((spins & 4095) == 0 && ld_agent(b.error) != 0) {   // some block has given up: stop waiting everywhere
+                b.failed = true;
+                break;
+            }
+            if (spins > (1 << 21)) {  // seconds: something is wrong, do not hang the GPU
                 st_agent(b.error, 1);
+                b.failed = true;
                 break;
             }
         }
