@@ -33,7 +33,7 @@ size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 struct Layout {  // byte offsets into the model workspace
     size_t rope_tab, tok, result, counter, x, h, y, qkv, att, gu, a, logits, part;
     // fast path: packed operands, partial sums of squares, packed weights
-    size_t xp_d, xp_att, xp_f, ssp_a, ssp_b, qp, head_ctr, layer_tab, amax, row_ctr, bar, err, wp_lm, total;
+    size_t xp_d, xp_att, xp_f, ssp_a, ssp_b, qp, head_ctr, layer_tab, amax, row_ctr, bar, wp_lm, total;
     std::vector<size_t> wp_qkv, wp_o, wp_gu, wp_down;
     int max_splits;
 };
@@ -91,7 +91,7 @@ Layout make_layout(const anpd_model_cfg *c)
     L.logits = take(MW * V * 4);
     L.part = take((size_t)c->n_heads * L.max_splits * (wants_mfma(c) ? 32 : MW) * (c->head_dim + 2) * 4);
     L.xp_d = L.xp_att = L.xp_f = L.ssp_a = L.ssp_b = L.qp = L.head_ctr = L.wp_lm = 0;
-    L.layer_tab = L.amax = L.row_ctr = L.bar = L.err = 0;
+    L.layer_tab = L.amax = L.row_ctr = L.bar = 0;
     if (wants_mfma(c)) {
         L.xp_d = take(((d + 31) / 32) * 4 * 1024);
         L.xp_att = take(((d + 31) / 32) * 4 * 1024);
@@ -104,7 +104,6 @@ Layout make_layout(const anpd_model_cfg *c)
         L.amax = take((V / 16) * 32 * sizeof(unsigned long long));
         L.row_ctr = take(sizeof(uint32_t));
         L.bar = take(kBarStride * 9 * sizeof(uint32_t));
-        L.err = take(sizeof(int32_t));
         L.wp_lm = take(packed_bytes(V / 16, (int)d));
         for (int l = 0; l < c->n_layers; ++l) {
             L.wp_qkv.push_back(take(packed_bytes(3 * d / 16, (int)d)));
@@ -132,7 +131,8 @@ struct anpd_model {
     uint32_t bar_epoch;
     const void *embed, *final_norm, *lm_head;
     std::vector<const void *> attn_norm, wq, wk, wv, wo, ffn_norm, w_gate, w_up, w_down;
-    int32_t *pin;  // pinned host staging: [0..32) window, [32..66) result
+    int32_t *pin;  // pinned host staging: [0..32) window, [32..66) result, [100] error flag of the persistent kernel
+    int32_t *pin_dev;  // the same memory as the device addresses it
     // optional per-kernel timing with events on the launch stream
     bool prof;
     std::vector<hipEvent_t> ev;
@@ -466,7 +466,7 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
 }
 
 // The step as one persistent kernel (window class 8).
-int32_t run_step_mega(anpd_model *m, anpd_kv *kv, int M, int mode, bool want_logits, hipStream_t st)
+int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, int mode, bool want_logits, hipStream_t st)
 {
     const anpd_model_cfg &c = m->cfg;
     const Layout &L = m->lay;
@@ -491,12 +491,13 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, int M, int mode, bool want_log
     g.max_splits = L.max_splits;
     g.logits = want_logits ? (float *)(ws + L.logits) : nullptr;
     g.amax = (unsigned long long *)(ws + L.amax);
-    g.tok = (const int32_t *)(ws + L.tok);
+    for (int i = 0; i < 8; ++i) g.tok[i] = i < M ? window[i] : 0;
     g.result = (int32_t *)(ws + L.result);
+    g.host_result = m->pin_dev + 32;
     g.row_counter = (uint32_t *)(ws + L.row_ctr);
     g.bar = (uint32_t *)(ws + L.bar);
     g.bar_epoch = m->bar_epoch;
-    g.error = (int32_t *)(ws + L.err);
+    g.error = m->pin_dev + 100;
     g.trace = m->trace;
     m->ev_used = 0;
     mark(m, -1, st);
@@ -594,6 +595,9 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
     }
     hipError_t e = hipHostMalloc((void **)&m->pin, 128 * sizeof(int32_t), hipHostMallocDefault);
     if (e != hipSuccess) { delete m; return fail(ANPD_E_HIP, "hipHostMalloc: %s", hipGetErrorString(e)); }
+    std::memset(m->pin, 0, 128 * sizeof(int32_t));
+    e = hipHostGetDevicePointer((void **)&m->pin_dev, m->pin, 0);
+    if (e != hipSuccess) { (void)hipHostFree(m->pin); delete m; return fail(ANPD_E_HIP, "hipHostGetDevicePointer: %s", hipGetErrorString(e)); }
     e = hipMemsetAsync(m->ws, 0, m->mfma ? lay.wp_lm : lay.total, st);
     if (e == hipSuccess) e = hipMemcpyAsync(m->ws + lay.rope_tab, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice, st);
     int32_t prc = ANPD_OK;
@@ -845,24 +849,30 @@ int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32
     hipStream_t st = (hipStream_t)stream;
     int32_t rc = ensure_pages(kv, kv->len + n_window, st);
     if (rc != ANPD_OK) return rc;
-    std::memcpy(m->pin, window, sizeof(int32_t) * (size_t)n_window);
-    HIP_TRY(hipMemcpyAsync(m->ws + m->lay.tok, m->pin, sizeof(int32_t) * (size_t)n_window, hipMemcpyHostToDevice, st));
-    if (m->mega && n_window <= 8) rc = run_step_mega(m, kv, n_window, mode, out_logits != nullptr, st);
-    else if (m->mfma) rc = run_step_fast(m, kv, n_window, mode, st);
-    else if (m->cfg.dtype == ANPD_BF16) rc = run_step_generic<bf16_t>(m, kv, n_window, mode, st);
-    else rc = run_step_generic<float>(m, kv, n_window, mode, st);
-    if (rc != ANPD_OK) return rc;
+    // The persistent kernel takes the window by value and writes its result and error flag into the
+    // pinned buffer itself; the other paths go through copies.
+    const bool one_kernel = m->mega && n_window <= 8;
     int32_t *res = m->pin + 32;
-    HIP_TRY(hipMemcpyAsync(res, m->ws + m->lay.result, sizeof(int32_t) * (size_t)(2 + n_window), hipMemcpyDeviceToHost, st));
+    if (one_kernel) {
+        rc = run_step_mega(m, kv, window, n_window, mode, out_logits != nullptr, st);
+        if (rc != ANPD_OK) return rc;
+    } else {
+        std::memcpy(m->pin, window, sizeof(int32_t) * (size_t)n_window);
+        HIP_TRY(hipMemcpyAsync(m->ws + m->lay.tok, m->pin, sizeof(int32_t) * (size_t)n_window, hipMemcpyHostToDevice, st));
+        if (m->mfma) rc = run_step_fast(m, kv, n_window, mode, st);
+        else if (m->cfg.dtype == ANPD_BF16) rc = run_step_generic<bf16_t>(m, kv, n_window, mode, st);
+        else rc = run_step_generic<float>(m, kv, n_window, mode, st);
+        if (rc != ANPD_OK) return rc;
+        HIP_TRY(hipMemcpyAsync(res, m->ws + m->lay.result, sizeof(int32_t) * (size_t)(2 + n_window), hipMemcpyDeviceToHost, st));
+    }
     if (out_logits)
         HIP_TRY(hipMemcpyAsync(out_logits, m->ws + m->lay.logits, sizeof(float) * (size_t)n_window * m->cfg.vocab,
                                hipMemcpyDeviceToDevice, st));
-    if (m->mega) HIP_TRY(hipMemcpyAsync(m->pin + 100, m->ws + m->lay.err, sizeof(int32_t), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
-    if (m->mega && m->pin[100] != 0) {
+    if (one_kernel && m->pin[100] != 0) {
         // a grid barrier gave up: the counters are no longer in step, start them over
+        m->pin[100] = 0;
         (void)hipMemsetAsync(m->ws + m->lay.bar, 0, kBarStride * 9 * sizeof(uint32_t), st);
-        (void)hipMemsetAsync(m->ws + m->lay.err, 0, sizeof(int32_t), st);
         (void)hipStreamSynchronize(st);
         m->bar_epoch = 0;
         return fail(ANPD_E_HIP, "anpd_verify: the persistent kernel timed out at a grid barrier");

@@ -48,12 +48,13 @@ struct MegaArgs {
     int max_splits;
     float *logits;          // nullable: all logits [M][V]
     unsigned long long *amax;  // [V / 16][32] per-tile (value bits << 32 | index) of the best logit
-    const int32_t *tok;
-    int32_t *result;
+    int32_t tok[8];         // the window's tokens, by value (no upload before the launch)
+    int32_t *result;        // device: [0] accepted, [1] next, [2 + r] prediction of row r
+    int32_t *host_result;   // pinned host memory, same layout: written at the end, read by the host after the launch
     uint32_t *row_counter;  // argmax phase hand-off
     uint32_t *bar;          // [0] = top counter, [kBarStride * (1 + g)] = group g
     uint32_t bar_epoch;     // barriers completed by earlier launches
-    int32_t *error;         // set to 1 if a barrier wait gave up
+    int32_t *error;         // pinned host memory: set to 1 if a barrier wait gave up
     long long *trace;       // nullable: [grid][kTraceEvents] timestamps (100 MHz) at barrier arrive / wait-done
 };
 
@@ -123,12 +124,12 @@ __device__ __forceinline__ void bar_wait(GridBarrier &b)
         while ((int32_t)(ld_agent(b.ctr) - target) < 0) {
             __builtin_amdgcn_s_sleep(4);
             ++spins;
-            if ((spins & 4095) == 0 && ld_agent(b.error) != 0) {   // some block has given up: stop waiting everywhere
+            if ((spins & 4095) == 0 && ld_system(b.error) != 0) {   // some block has given up: stop waiting everywhere
                 b.failed = true;
                 break;
             }
             if (spins > (1 << 21)) {  // seconds: something is wrong, do not hang the GPU
-                st_agent(b.error, 1);
+                st_system(b.error, 1);
                 b.failed = true;
                 break;
             }
@@ -410,7 +411,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
         a.xp_next = g->xp_d;
         a.ssp_next = g->ssp_a;
         if (wave == 0)
-            for (int t = blockIdx.x; t < d / 16; t += grid) embed_tile<true>(g->embed, g->tok, a, t, lane);
+            for (int t = blockIdx.x; t < d / 16; t += grid) embed_tile<true>(g->embed, (const int32_t *)g->tok, a, t, lane);
         bar_arrive(bar);
     }
     for (int l = 0; l < n_layers; ++l) {
@@ -535,8 +536,13 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             } else {
                 acc_n = g->M - 1;
             }
+            const int32_t next = ld_agent(pred + acc_n);
             g->result[0] = acc_n;
-            g->result[1] = ld_agent(pred + acc_n);
+            g->result[1] = next;
+            int32_t *hr = g->host_result;
+            st_system(hr, (int32_t)acc_n);
+            st_system(hr + 1, next);
+            for (int i = 0; i < g->M; ++i) st_system(hr + 2 + i, ld_agent(pred + i));
             *g->len_ptr = L + 1 + acc_n;
             st_agent(g->row_counter, 0u);
         }
