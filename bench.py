@@ -40,6 +40,58 @@ def timed_steps(fn, n, torch):
     return time.perf_counter() - t0
 
 
+def sweep(args, torch, B, synth) -> int:
+    """Step time over L x M (seeded N(0,1) cache, random window ids): the question whether a window of
+    k + 1 rows costs what one row costs (paper, Section 3.1, "Parallel Decoding"), and whether paging costs
+    bandwidth.  One JSON line per (L, page order) on stdout, a table on stderr."""
+    wl = synth.WORKLOADS[args.workload]
+    shape = wl["shape"]
+    path = {"auto": B.GEMM_AUTO, "dot": B.GEMM_DOT, "mfma": B.GEMM_MFMA, "launches": B.GEMM_MFMA_LAUNCHES}[args.gemm_path]
+    lengths = [128] if args.workload == "tiny" else [512, 1024, 2048, 4096]
+    rows = [1, 2, 4, 6, 8, 9, 16, 17]
+    cap = max(lengths) + 64
+    weights = synth.make_weights(shape, wl["seed"], device="cuda")
+    model = B.Model(shape, weights, max_window=32, max_positions=cap, gemm_path=path)
+    kv = B.KVCache(model, cap)
+    for layer in range(shape.n_layers):
+        k, v = synth.kv_fill(shape, 7, layer, max(lengths), device="cuda")
+        kv.write(layer, 0, k.float().contiguous(), v.float().contiguous())
+    torch.cuda.synchronize()
+    weight_bytes = 2 * shape.n_params_streamed if shape.dtype == "bf16" else 4 * shape.n_params_streamed
+    n_pages = kv.num_pages
+    perm = sorted(range(n_pages), key=lambda i: synth.splitmix64(0xABCD + i))
+    log("%-9s %-6s" % ("pages", "L") + "".join("  M=%-2d ms (GB/s)" % m for m in rows))
+    for order_name, order in (("identity", list(range(n_pages))), ("permuted", perm)):
+        kv.truncate(0)
+        kv.set_page_order(order)
+        for layer in range(shape.n_layers):
+            k, v = synth.kv_fill(shape, 7, layer, max(lengths), device="cuda")
+            kv.write(layer, 0, k.float().contiguous(), v.float().contiguous())
+        for L in lengths:
+            line, rec = "%-9s %-6d" % (order_name, L), {}
+            for M in rows:
+                win = synth.random_tokens(shape.vocab, M, 11 + M)
+
+                def step():
+                    kv.truncate(L)
+                    B.verify(model, kv, win, B.APPEND)
+
+                for _ in range(max(3, args.warmup // 4)):
+                    step()
+                n = max(10, args.steps // 4)
+                dt = timed_steps(step, n, torch)
+                ms = 1e3 * dt / n
+                gbs = (weight_bytes + shape.kv_bytes_per_token * L) / (ms * 1e-3) / 1e9
+                line += "  %6.3f (%4.0f)" % (ms, gbs)
+                rec[str(M)] = round(ms, 4)
+            log(line)
+            print(json.dumps({"sweep": args.workload, "pages": order_name, "L": L, "ms_per_step_by_rows": rec,
+                              "gemm_path": args.gemm_path}))
+    kv.close()
+    model.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -51,6 +103,9 @@ def main() -> int:
     ap.add_argument("--cpu-steps", type=int, default=2)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB elementwise copy five times (reference for HBM traffic counters)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="kernel sweep instead of the headline run: step time over cache length x window rows on a "
+                         "seeded cache, with the identity page table and a seeded permutation; prints a table")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
@@ -74,6 +129,9 @@ def main() -> int:
             torch.mul(cx, 1.0, out=cy)
         torch.cuda.synchronize()
         del cx, cy
+
+    if args.sweep:
+        return sweep(args, torch, B, synth)
 
     wl = synth.WORKLOADS[args.workload]
     shape = wl["shape"]

@@ -194,13 +194,37 @@ int32_t launch_fast(FastArgs &a, int n_cu, bool force_stream, hipStream_t st)
         else if (kpw <= 8) hipLaunchKernelGGL((gemm_xs_kernel<8, EPI>), grid, block, 0, st, a);
         else if (kpw <= 16) hipLaunchKernelGGL((gemm_xs_kernel<16, EPI>), grid, block, 0, st, a);
         else hipLaunchKernelGGL((gemm_xs_kernel<20, EPI>), grid, block, 0, st, a);
-    } else {
+    } else if (a.cls == 8 || (a.cls == 16 && a.n_tiles <= n_cu)) {
+        // one block per tile; several blocks share a compute unit.  Also the faster form for 9..16 rows when
+        // there is only one tile per compute unit (grouping would leave half of them idle).
         dim3 grid((unsigned)a.n_tiles), block(kFastWaves * 64);
         const int nt = a.cls / 8;
         size_t smem = (size_t)kFastWaves * nt * 256 * sizeof(float);
         if (nt == 1) hipLaunchKernelGGL((gemm_stream_kernel<1, EPI>), grid, block, smem, st, a);
-        else if (nt == 2) hipLaunchKernelGGL((gemm_stream_kernel<2, EPI>), grid, block, smem, st, a);
-        else hipLaunchKernelGGL((gemm_stream_kernel<4, EPI>), grid, block, smem, st, a);
+        else hipLaunchKernelGGL((gemm_stream_kernel<2, EPI>), grid, block, smem, st, a);
+    } else {
+        // windows of 9..32 rows: every block takes a contiguous range of at least two tiles, so that an
+        // activation fragment is loaded once for several weight tiles
+        const int nt = a.cls / 8;
+        int blocks = a.n_tiles / 2 < n_cu ? a.n_tiles / 2 : n_cu;
+        if (blocks < 1) blocks = 1;
+        dim3 grid((unsigned)blocks), block(kFastWaves * 64);
+        const int per_block = (a.n_tiles + blocks - 1) / blocks;
+        if (nt == 2) {
+            size_t smem = (size_t)2 * kFastWaves * 2 * 256 * sizeof(float);
+            hipLaunchKernelGGL((gemm_group_kernel<2, 2, EPI>), grid, block, smem, st, a);
+        } else if (per_block <= 2) {
+            size_t smem = (size_t)2 * kFastWaves * 4 * 256 * sizeof(float);
+            hipLaunchKernelGGL((gemm_group_kernel<4, 2, EPI>), grid, block, smem, st, a);
+        } else {
+            size_t smem = (size_t)4 * kFastWaves * 4 * 256 * sizeof(float);
+            static bool attr_set = false;
+            if (!attr_set) {
+                HIP_TRY(hipFuncSetAttribute((const void *)gemm_group_kernel<4, 4, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+                attr_set = true;
+            }
+            hipLaunchKernelGGL((gemm_group_kernel<4, 4, EPI>), grid, block, smem, st, a);
+        }
     }
     HIP_TRY(hipGetLastError());
     return ANPD_OK;

@@ -487,6 +487,95 @@ __global__ __launch_bounds__(kFastThreads) void gemm_stream_kernel(FastArgs a)
     if (wave == 0) reduce_and_finish<NT, EPI>(a, tile, red_dyn, kFastWaves, lane, rinv);
 }
 
+// ------------------------------------------- GEMM, grouped tiles (windows of 9..32 rows)
+//
+// A window of more than 8 rows has NT = 2 or 4 activation fragments per
+// k-step, too many to keep in registers, and reading them again for every
+// weight tile makes the kernel wait for L2 rather than for HBM (NT times the
+// weight bytes).  Here a block owns a contiguous range of tiles and takes up
+// to TG of them per pass: every activation fragment it loads meets TG weight
+// fragments, so the operand traffic is NT / TG of the weight traffic.  Two
+// register stages of C k-steps keep the loads of the next stage in flight
+// during the MFMAs of this one.  Same k-step assignment (wave, wave + 8, ...)
+// and summation order as the other forms: bit-identical results.
+template <int NT, int TG, int EPI>
+__global__ __launch_bounds__(kFastThreads) void gemm_group_kernel(FastArgs a)
+{
+    extern __shared__ float red_dyn[];  // [TG][kFastWaves][NT][256]
+    __shared__ float rinv[32];
+    constexpr int C = (NT * TG >= 8) ? 2 : 4;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nks = a.nks;
+    if (EPI == EPI_QKV || EPI == EPI_GATE_UP || EPI == EPI_LOGITS) compute_rinv(a, rinv, red_dyn);
+    const int first = (int)(((long long)blockIdx.x * a.n_tiles) / gridDim.x);
+    const int last = (int)(((long long)(blockIdx.x + 1) * a.n_tiles) / gridDim.x);
+    const int n_mine = last - first;
+    const int n_pass = (n_mine + TG - 1) / TG;
+    const int per_pass = n_pass > 0 ? (n_mine + n_pass - 1) / n_pass : 0;
+    const int kpw = (nks + kFastWaves - 1) / kFastWaves;
+    const int n_it = (kpw + C - 1) / C;
+    __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(a.Xp), 0, nks * NT * 1024, 0x00020000);
+
+    for (int t0 = first; t0 < last; t0 += per_pass) {
+        const int ntl = last - t0 < per_pass ? last - t0 : per_pass;
+        __amdgpu_buffer_rsrc_t rw[TG];
+#pragma unroll
+        for (int t = 0; t < TG; ++t) {
+            const bool have = t < ntl;   // absent tiles: an empty buffer, reads zeros and fetches nothing
+            rw[t] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(a.Wp + (size_t)(have ? t0 + t : 0) * nks * 64), 0,
+                                                      have ? nks * 1024 : 0, 0x00020000);
+        }
+        f32x4 acc[TG][NT];
+#pragma unroll
+        for (int t = 0; t < TG; ++t)
+#pragma unroll
+            for (int f = 0; f < NT; ++f) acc[t][f] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        uint4 wA[TG][C], xA[NT][C], wB[TG][C], xB[NT][C];
+        auto load = [&](uint4 (&w)[TG][C], uint4 (&x)[NT][C], int i) {
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const int ks = wave + kFastWaves * (i * C + c);   // past the end: outside every buffer, reads zeros
+#pragma unroll
+                for (int t = 0; t < TG; ++t) {
+                    u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rw[t], (ks * 64 + lane) * 16, 0, 0);
+                    w[t][c] = make_uint4(v.x, v.y, v.z, v.w);
+                }
+#pragma unroll
+                for (int f = 0; f < NT; ++f) {
+                    u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rx, ((ks * NT + f) * 64 + lane) * 16, 0, 0);
+                    x[f][c] = make_uint4(v.x, v.y, v.z, v.w);
+                }
+            }
+        };
+        auto mma = [&](const uint4 (&w)[TG][C], const uint4 (&x)[NT][C]) {
+#pragma unroll
+            for (int c = 0; c < C; ++c)
+#pragma unroll
+                for (int t = 0; t < TG; ++t)
+#pragma unroll
+                    for (int f = 0; f < NT; ++f)
+                        acc[t][f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[t][c]),
+                                                                            __builtin_bit_cast(bf16x8, x[f][c]), acc[t][f], 0, 0, 0);
+        };
+        load(wA, xA, 0);
+        for (int i = 0; i < n_it; i += 2) {
+            if (i + 1 < n_it) load(wB, xB, i + 1);
+            mma(wA, xA);
+            if (i + 2 < n_it) load(wA, xA, i + 2);
+            if (i + 1 < n_it) mma(wB, xB);
+        }
+        __syncthreads();   // the previous pass's partial tiles have been consumed
+#pragma unroll
+        for (int t = 0; t < TG; ++t)
+#pragma unroll
+            for (int f = 0; f < NT; ++f)
+                *reinterpret_cast<f32x4 *>(red_dyn + ((((size_t)t * kFastWaves + wave) * NT + f) * 64 + lane) * 4) = acc[t][f];
+        __syncthreads();
+        if (wave < ntl)
+            reduce_and_finish<NT, EPI>(a, t0 + wave, red_dyn + (size_t)wave * kFastWaves * NT * 256, kFastWaves, lane, rinv);
+    }
+}
+
 // ------------------------------------------------------------------ embed
 //
 // x[m] = E[token[m]] plus what the residual epilogue would leave behind for the
