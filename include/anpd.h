@@ -216,6 +216,13 @@ int32_t anpd_model_profile_read(const anpd_model_t *m, double *out_ms, int64_t *
  * Returns the grid size (0 if this model does not use the one-kernel step). */
 int32_t anpd_model_trace(anpd_model_t *m, void *buffer, size_t bytes);
 
+/* Test hook for the failure path of the one-kernel step.  A block waits at a grid barrier for at
+ * most `spins` polls (0 restores the default, a couple of seconds); a wait that gives up raises
+ * the error flag, every block stops waiting, all phases still run to their end, and that
+ * anpd_verify returns ANPD_E_HIP.  After such an error the cache contents and length are
+ * undefined: truncate and recompute.  The next call starts with fresh barrier counters. */
+int32_t anpd_model_set_barrier_spin_limit(anpd_model_t *m, int32_t spins);
+
 /* The dominant kernel on its own, for per-kernel parity and bandwidth
  * measurement: Y[M][N] = X[M][K] * W[N][K]^T with fp32 accumulation.
  *   X: DEVICE float32 [M][K]; Y: DEVICE float32 [M][N];

@@ -32,7 +32,7 @@ EXPORTS = (
     "anpd_kv_set_page_order", "anpd_kv_num_pages", "anpd_kv_write", "anpd_kv_read",
     "anpd_verify", "anpd_linear_workspace_bytes", "anpd_linear",
     "anpd_model_profile", "anpd_model_profile_read", "anpd_packed_bytes", "anpd_pack_weights",
-    "anpd_model_trace",
+    "anpd_model_trace", "anpd_model_set_barrier_spin_limit",
 )
 PROF_CATEGORIES = ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "attn", "other", "step")
 
@@ -121,6 +121,8 @@ def lib():
     L.anpd_pack_weights.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_size_t, vp]
     L.anpd_model_trace.restype = C.c_int32
     L.anpd_model_trace.argtypes = [vp, vp, C.c_size_t]
+    L.anpd_model_set_barrier_spin_limit.restype = C.c_int32
+    L.anpd_model_set_barrier_spin_limit.argtypes = [vp, C.c_int32]
     L.anpd_model_profile.restype = C.c_int32
     L.anpd_model_profile.argtypes = [vp, C.c_int32]
     L.anpd_model_profile_read.restype = C.c_int32
@@ -257,6 +259,10 @@ class Model:
         self._trace = torch.zeros(grid, 1024, dtype=torch.int64, device=self.device)
         _check(lib().anpd_model_trace(self._h, self._trace.data_ptr(), self._trace.numel() * 8))
         return self._trace
+
+    def set_barrier_spin_limit(self, spins: int) -> None:
+        """Test hook: polls before a grid-barrier wait of the one-kernel step gives up (0 = default)."""
+        _check(lib().anpd_model_set_barrier_spin_limit(self._h, spins))
 
     def profile(self, enable: bool) -> None:
         _check(lib().anpd_model_profile(self._h, 1 if enable else 0))

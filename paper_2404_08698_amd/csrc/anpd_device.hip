@@ -128,6 +128,7 @@ struct anpd_model {
     long long *trace;     // optional device buffer for barrier timestamps
     int mega_grid;
     bool plain_launch;    // launch the one-kernel step without the cooperative-launch API (profiling aid)
+    int32_t spin_limit;   // polls before a grid-barrier wait gives up
     uint32_t bar_epoch;
     const void *embed, *final_norm, *lm_head;
     std::vector<const void *> attn_norm, wq, wk, wv, wo, ffn_norm, w_gate, w_up, w_down;
@@ -522,6 +523,7 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, 
     g.bar = (uint32_t *)(ws + L.bar);
     g.bar_epoch = m->bar_epoch;
     g.error = m->pin_dev + 100;
+    g.spin_limit = m->spin_limit;
     g.trace = m->trace;
     m->ev_used = 0;
     mark(m, -1, st);
@@ -629,6 +631,7 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
     m->trace = nullptr;
     m->mega_grid = 0;
     m->bar_epoch = 0;
+    m->spin_limit = 1 << 21;
     // ANPD_MEGA_PLAIN_LAUNCH=1: an ordinary launch of the same grid.  Only for profilers that cannot
     // cope with the cooperative queue; all blocks are resident only if nothing else runs on the device
     // (otherwise a barrier wait times out and anpd_verify reports it).
@@ -697,6 +700,14 @@ int32_t anpd_model_trace(anpd_model_t *m, void *buffer, size_t bytes)
                     (size_t)m->mega_grid * kTraceEvents * sizeof(long long));
     m->trace = (long long *)buffer;
     return m->mega ? m->mega_grid : 0;
+}
+
+int32_t anpd_model_set_barrier_spin_limit(anpd_model_t *m, int32_t spins)
+{
+    if (!m) return fail(ANPD_E_INVAL, "anpd_model_set_barrier_spin_limit: NULL handle");
+    if (spins < 0) return fail(ANPD_E_INVAL, "anpd_model_set_barrier_spin_limit: spins must be >= 0");
+    m->spin_limit = spins == 0 ? (1 << 21) : spins;
+    return ANPD_OK;
 }
 
 int32_t anpd_model_profile(anpd_model_t *m, int32_t enable)

@@ -55,6 +55,7 @@ struct MegaArgs {
     uint32_t *bar;          // [0] = top counter, [kBarStride * (1 + g)] = group g
     uint32_t bar_epoch;     // barriers completed by earlier launches
     int32_t *error;         // pinned host memory: set to 1 if a barrier wait gave up
+    int32_t spin_limit;     // polls before a barrier wait gives up
     long long *trace;       // nullable: [grid][kTraceEvents] timestamps (100 MHz) at barrier arrive / wait-done
 };
 
@@ -71,6 +72,7 @@ struct GridBarrier {
     long long *trace;
     int n_ev;
     bool failed;     // (thread 0) a wait of this block gave up, or it saw the error flag: later waits do not spin
+    int spin_limit;
 };
 
 template <typename ArgsPtr>
@@ -85,6 +87,7 @@ __device__ __forceinline__ void bar_init(GridBarrier &b, ArgsPtr a)
     b.trace = a->trace ? a->trace + (size_t)blockIdx.x * kTraceEvents : nullptr;
     b.n_ev = 0;
     b.failed = false;
+    b.spin_limit = a->spin_limit;
 }
 
 __device__ __forceinline__ void bar_stamp(GridBarrier &b)
@@ -128,7 +131,7 @@ __device__ __forceinline__ void bar_wait(GridBarrier &b)
                 b.failed = true;
                 break;
             }
-            if (spins > (1 << 21)) {  // seconds: something is wrong, do not hang the GPU
+            if (spins > b.spin_limit) {  // by default seconds: something is wrong, do not hang the GPU
                 st_system(b.error, 1);
                 b.failed = true;
                 break;
