@@ -1,0 +1,45 @@
+"""The host-only ablation driver against the oracle's Algorithm 1 (paper, Algorithm 1, Section 4.3)."""
+from oracle import anpd as oanpd
+from paper_2404_08698_amd import ablation, synth
+
+
+class StreamModel:
+    """A scripted LLM whose greedy output is a fixed stream (oracle/anpd.py's llm interface)."""
+
+    def __init__(self, stream, prompt_len):
+        self.s, self.pos = stream, prompt_len          # cache holds s[:pos]
+
+    def prefill(self, prompt):
+        assert list(prompt) == list(self.s[:self.pos])
+        return self.s[self.pos]
+
+    def predict(self, window):
+        return [self.s[self.pos + 1 + r] if self.pos + 1 + r < len(self.s) else -1 for r in range(len(window))]
+
+    def commit(self, n_rows):
+        self.pos += n_rows
+
+
+def test_driver_counts_match_the_oracle_loop():
+    vocab, P, G = 64, 48, 160
+    stream = synth.markov_stream(vocab, P + G + 40, 0.5, 3, 9, 123)
+    for n_min, n_max, K in ((2, 2, 4), (2, 5, 7), (3, 3, 5), (2, 4, 1)):
+        ref = oanpd.anpd_generate(StreamModel(stream, P), stream[:P], K, G, n_min, n_max)
+        got = ablation.run_stream(stream[:P + G + 40], P, n_min, n_max, K, vocab, max_tokens=None)
+        # same drafts and acceptances step by step: compare over the steps the oracle took
+        n = ref["n_steps"]
+        again = ablation.run_stream(stream, P, n_min, n_max, K, vocab, max_tokens=sum(1 + s["accepted"] for s in ref["steps"]))
+        assert again["steps"] == n
+        assert again["proposed"] == ref["proposed"] and again["accepted"] == ref["accepted"]
+        assert got["alpha"] >= 0.0
+
+
+def test_periodic_stream_is_drafted_perfectly_and_step_times_are_applied():
+    period = [5, 9, 2, 7, 11, 3]
+    stream = period * 40
+    r = ablation.run_stream(stream, 24, 2, 3, 5, 16)
+    assert r["alpha"] > 0.98 and r["tokens_per_step"] > 5.5
+    flat = {1: 3.0, 8: 3.0}
+    assert abs(ablation.speedup_with_times(r, flat) - r["tokens_per_step"]) < 1e-9
+    slow = {1: 3.0, 8: 6.0}
+    assert ablation.speedup_with_times(r, slow) < r["tokens_per_step"]
