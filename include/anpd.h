@@ -212,7 +212,8 @@ int32_t anpd_model_profile_read(const anpd_model_t *m, double *out_ms, int64_t *
 
 /* Barrier-level trace of the one-kernel step.  buffer: DEVICE, grid * 1024 int64 (NULL switches the
  * trace off).  While set, block b stores 100 MHz timestamps at buffer[b * 1024 + e]: e = 0 kernel
- * start, then for every grid barrier the moment the block arrives and the moment its wait ends.
+ * start, then for every phase boundary the moment the block reaches it and the moment its wait
+ * ends (1 + 5 * n_layers + 1 pairs; the pair after a QKV phase is a per-head hand-off, not a grid barrier).
  * Returns the grid size (0 if this model does not use the one-kernel step). */
 int32_t anpd_model_trace(anpd_model_t *m, void *buffer, size_t bytes);
 

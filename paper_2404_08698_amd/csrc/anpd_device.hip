@@ -99,11 +99,11 @@ Layout make_layout(const anpd_model_cfg *c)
         L.ssp_a = take((d / 16) * 32 * 4);
         L.ssp_b = take((d / 16) * 32 * 4);
         L.qp = take((size_t)c->n_heads * 4 * (c->head_dim / 32) * 1024);
-        L.head_ctr = take((size_t)c->n_heads * sizeof(uint32_t));
+        L.head_ctr = take((size_t)c->n_heads * kCounterStride * sizeof(uint32_t));
         L.layer_tab = take((size_t)c->n_layers * sizeof(LayerW));
         L.amax = take((V / 16) * 32 * sizeof(unsigned long long));
         L.row_ctr = take(sizeof(uint32_t));
-        L.bar = take(kBarStride * 9 * sizeof(uint32_t));
+        L.bar = take(kBarStride * 9 * sizeof(uint32_t) + (size_t)c->n_heads * kCounterStride * sizeof(uint32_t));   // barrier words, then per-head QKV counters
         L.wp_lm = take(packed_bytes(V / 16, (int)d));
         for (int l = 0; l < c->n_layers; ++l) {
             L.wp_qkv.push_back(take(packed_bytes(3 * d / 16, (int)d)));
@@ -130,6 +130,7 @@ struct anpd_model {
     bool plain_launch;    // launch the one-kernel step without the cooperative-launch API (profiling aid)
     int32_t spin_limit;   // polls before a grid-barrier wait gives up
     uint32_t bar_epoch;
+    uint32_t ready_epoch;  // QKV phases run by the one-kernel step so far
     const void *embed, *final_norm, *lm_head;
     std::vector<const void *> attn_norm, wq, wk, wv, wo, ffn_norm, w_gate, w_up, w_down;
     int32_t *pin;  // pinned host staging: [0..32) window, [32..66) result, [100] error flag of the persistent kernel
@@ -524,6 +525,8 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, 
     g.bar_epoch = m->bar_epoch;
     g.error = m->pin_dev + 100;
     g.spin_limit = m->spin_limit;
+    g.qkv_ready = (uint32_t *)(ws + L.bar) + kBarStride * 9;
+    g.ready_epoch = m->ready_epoch;
     g.trace = m->trace;
     m->ev_used = 0;
     mark(m, -1, st);
@@ -541,6 +544,7 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, 
         HIP_TRY(hipLaunchCooperativeKernel((const void *)verify_mega_kernel<64>, dim3((unsigned)m->mega_grid), dim3(kFastThreads), args, 0, st));
     }
     m->bar_epoch += (uint32_t)kMegaBarriers(c.n_layers);
+    m->ready_epoch += (uint32_t)c.n_layers;
     mark(m, ANPD_PROF_STEP, st);
     return ANPD_OK;
 }
@@ -631,6 +635,7 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
     m->trace = nullptr;
     m->mega_grid = 0;
     m->bar_epoch = 0;
+    m->ready_epoch = 0;
     m->spin_limit = 1 << 21;
     // ANPD_MEGA_PLAIN_LAUNCH=1: an ordinary launch of the same grid.  Only for profilers that cannot
     // cope with the cooperative queue; all blocks are resident only if nothing else runs on the device
@@ -907,9 +912,10 @@ int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32
     if (one_kernel && m->pin[100] != 0) {
         // a grid barrier gave up: the counters are no longer in step, start them over
         m->pin[100] = 0;
-        (void)hipMemsetAsync(m->ws + m->lay.bar, 0, kBarStride * 9 * sizeof(uint32_t), st);
+        (void)hipMemsetAsync(m->ws + m->lay.bar, 0, kBarStride * 9 * sizeof(uint32_t) + (size_t)m->cfg.n_heads * kCounterStride * sizeof(uint32_t), st);
         (void)hipStreamSynchronize(st);
         m->bar_epoch = 0;
+        m->ready_epoch = 0;
         return fail(ANPD_E_HIP, "anpd_verify: the persistent kernel timed out at a grid barrier");
     }
     if (m->prof) {

@@ -150,6 +150,8 @@ struct FastArgs {
     bf16_t *ap;           // operand of the down projection: split(silu(gate) * up)
     // LM_ARGMAX: Y (nullable) receives the logits; amax the per-tile best (value bits << 32 | index)
     unsigned long long *amax;  // [n_tiles][32]
+    // QKV in the persistent kernel: per-head count of finished q / k / v tiles (nullable)
+    uint32_t *ready;
 };
 
 // rinv[m] = 1 / sqrt(mean(x[m]^2) + eps) for the window rows, from the producer's per-tile partial
@@ -637,6 +639,9 @@ typedef short bf16x4s __attribute__((ext_vector_type(4)));
 // in increasing order and writes the packed operand of the output projection.
 // Row r sees keys 0..len + r; keys it must not see get weight exactly 0.
 constexpr int kFastSplit = kFastWaves * 16;
+// uint32 words between per-head counters: one 256-byte line each.  Atomics of different heads on one
+// line serialise at the memory side (measured with polled counters: +16 % step time when packed).
+constexpr int kCounterStride = 64;
 
 #ifdef ANPD_TIMING
 __device__ long long *g_anpd_dbg = nullptr;
@@ -840,12 +845,12 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
     ANPD_STAMP(3);
     const int n_blocks = (L + M + kFastSplit - 1) / kFastSplit;
     if (tid == 0)
-        sh.last = __hip_atomic_fetch_add(&head_counter[head], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+        sh.last = __hip_atomic_fetch_add(&head_counter[head * kCounterStride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
                   (uint32_t)(n_blocks - 1);
     block_sync_lds();
     ANPD_STAMP(4);
     if (!sh.last) return;
-    if (tid == 0) st_agent(&head_counter[head], 0u);
+    if (tid == 0) st_agent(&head_counter[head * kCounterStride], 0u);
     // Every thread merges four adjacent output elements of a row on its own: it reads the
     // (maximum, denominator) pair of each split of the row together with the split's outputs,
     // eight splits per round trip, and forms the row's global maximum and denominator itself.

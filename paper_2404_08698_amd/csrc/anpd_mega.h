@@ -56,13 +56,17 @@ struct MegaArgs {
     uint32_t bar_epoch;     // barriers completed by earlier launches
     int32_t *error;         // pinned host memory: set to 1 if a barrier wait gave up
     int32_t spin_limit;     // polls before a barrier wait gives up
+    uint32_t *qkv_ready;    // [n_heads] finished q / k / v tiles of the head, counted up over layers and launches
+    uint32_t ready_epoch;   // QKV phases completed by earlier launches
     long long *trace;       // nullable: [grid][kTraceEvents] timestamps (100 MHz) at barrier arrive / wait-done
 };
 
 constexpr int kTraceEvents = 1024;
 
 constexpr int kBarStride = 256;  // uint32 words between barrier counters (1 KiB: separate channels)
-constexpr int kMegaBarriers(int n_layers) { return 1 + 5 * n_layers + 1; }
+// embed, then attention / O / gate-up / down of every layer, then the LM head (the QKV phase hands over
+// per head, not through the grid barrier)
+constexpr int kMegaBarriers(int n_layers) { return 1 + 4 * n_layers + 1; }
 
 struct GridBarrier {
     uint32_t *ctr;
@@ -140,6 +144,21 @@ __device__ __forceinline__ void bar_wait(GridBarrier &b)
     }
     block_sync_lds();
     bar_stamp(b);
+}
+
+// Bounded wait for a counter that only grows (same give-up rules as bar_wait).  Thread 0 only.
+__device__ __forceinline__ void wait_count(GridBarrier &b, const uint32_t *p, uint32_t target)
+{
+    int spins = 0;
+    while (!b.failed && (int32_t)(ld_agent(p) - target) < 0) {
+        __builtin_amdgcn_s_sleep(4);
+        ++spins;
+        if ((spins & 4095) == 0 && ld_system(b.error) != 0) b.failed = true;
+        if (spins > b.spin_limit) {
+            st_system(b.error, 1);
+            b.failed = true;
+        }
+    }
 }
 
 struct WSrc {
@@ -235,7 +254,10 @@ __device__ __forceinline__ AttnShared<64> &attn_shared<64>(MegaShared &sh) { ret
 // (issued after this block has arrived at the phase barrier, so the arrival does not wait for them).
 // A work item is a chunk of kChunk k-steps per wave of one tile.
 // STATIONARY: K needs at most two chunks; the activation operand stays in registers for all tiles.
-template <int EPI, bool STATIONARY>
+// BARRIER = false (QKV): the phase does not end in a grid barrier; its consumers wait for per-head tile
+// counts (a.ready).  The barrier's counters assume that no block is more than one barrier ahead of
+// another, so a barrier that is not waited for must not be signalled either.
+template <int EPI, bool STATIONARY, bool BARRIER = true>
 __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, uint4 (&pf)[kChunk], MegaShared &sh,
                                            GridBarrier &bar, int &tiles_before)
 {
@@ -272,7 +294,7 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     if (stages) pre_to_lds<EPI>(sh.pre[wave], pre0, lane);
 
     bar_wait(bar);
-    if (my_tiles == 0 && tid == 0) bar_signal(bar);
+    if (BARRIER && my_tiles == 0 && tid == 0) bar_signal(bar);
     load_xchunk(x0, a.Xp, a.nks, 0, wave, lane);
     if (STATIONARY) load_xchunk(x1, a.Xp, a.nks, 1, wave, lane);   // else: one chunk ahead, alternating x0 / x1
     if (EPI == EPI_QKV || EPI == EPI_GATE_UP || EPI == EPI_LOGITS || EPI == EPI_LM_ARGMAX)
@@ -332,12 +354,24 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
         // this wave's epilogue stores must be out before the block counts its tiles as done; the wave
         // that completes the block's count signals the grid barrier
         wait_stores();
-        const int mine = (my_tiles - 1 - wave) / kFastWaves + 1;
-        if (lane == 0 && atomicAdd(&sh.tiles_done, mine) + mine == tiles_after) bar_signal(bar);
+        if (BARRIER) {
+            const int mine = (my_tiles - 1 - wave) / kFastWaves + 1;
+            if (lane == 0 && atomicAdd(&sh.tiles_done, mine) + mine == tiles_after) bar_signal(bar);
+        }
+        if (EPI == EPI_QKV && a.ready && lane == 0) {
+            // the attention tasks of a head wait for its 3 * head_dim / 16 tiles only, not for the whole grid
+            const int T = a.n_heads * a.head_dim / 16, tph = a.head_dim / 16;
+            for (int i = wave; i < my_tiles; i += kFastWaves) {
+                const int t = (int)blockIdx.x + i * grid;
+                __hip_atomic_fetch_add(a.ready + kCounterStride * ((t % T) / tph), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
         load_wchunk(pf, next, blockIdx.x, 0, wave, lane);
     }
-    tiles_before = tiles_after;
-    bar.done += 1;
+    if (BARRIER) {
+        tiles_before = tiles_after;
+        bar.done += 1;
+    }
     bar_stamp(bar);
 }
 
@@ -424,9 +458,9 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             FastArgs a = base_args(g);
             const int nks_d = (g->d + 31) / 32;
             a.Wp = w.qkv; a.Xp = (const uint4 *)g->xp_d; a.nks = nks_d; a.n_tiles = 3 * g->d / 16;
-            a.ssp = g->ssp_a; a.layer = l;
+            a.ssp = g->ssp_a; a.layer = l; a.ready = g->qkv_ready;
             WSrc none = {w.o, nks_d, 0};   // the O tile is fetched from inside the attention phase
-            gemm_phase<EPI_QKV, true>(a, none, pf, sh, bar, tiles_before);
+            gemm_phase<EPI_QKV, true, false>(a, none, pf, sh, bar, tiles_before);
         }
         {   // attention: (head, split) tasks; the O weights stream in meanwhile.  Cache pages wholly
             // below the committed length do not depend on this step: the first task's page is
@@ -443,7 +477,15 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             if ((int)blockIdx.x < n_tasks)
                 attn_load_kv<DH, true>(kv, blockIdx.x % n_heads, blockIdx.x / n_heads, L, M, g->pool, g->page_table, l,
                                        n_layers, n_heads, true);
-            bar_wait(bar);
+            // No grid barrier here: a task needs the q / k / v tiles of its own head only, and every
+            // block still arrives at the barrier that ends this phase after its QKV tiles, which is
+            // what the O phase waits for.
+            if (tid == 0) {
+                const uint32_t target = (uint32_t)(3 * g->head_dim / 16) * (g->ready_epoch + (uint32_t)l + 1u);
+                for (int t = blockIdx.x; t < n_tasks; t += grid) wait_count(bar, g->qkv_ready + kCounterStride * (t % n_heads), target);
+            }
+            block_sync_lds();
+            bar_stamp(bar);
             const WSrc o_src = {w.o, (g->d + 31) / 32, g->d / 16};
             bool fetched = false;
             auto prefetch_o = [&]() {

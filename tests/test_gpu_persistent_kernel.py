@@ -34,7 +34,11 @@ def test_barrier_trace_has_one_ordered_stamp_pair_per_barrier():
     assert (t[:, n_events:] == 0).all()
     # a barrier releases nobody before its last arrival: release k of any block >= every arrival k
     # (10 ns clock: allow one tick)
+    # (the barrier that ends a QKV phase is arrived at but not waited for: attention tasks wait for
+    # their own head's tiles instead, so those stamp pairs are exempt)
     for k in range(1 + 5 * shape.n_layers + 1):
+        if k >= 1 and (k - 1) % 5 == 0 and k < 1 + 5 * shape.n_layers:
+            continue
         arrive, release = used[:, 1 + 2 * k], used[:, 2 + 2 * k]
         assert release.min() >= arrive.max() - 1
     assert model.trace(False) is None
