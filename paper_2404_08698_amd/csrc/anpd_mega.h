@@ -280,11 +280,9 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
         if (++lc == n_chunks) { lc = 0; lt += grid; }
         if (lt < cur.n_tiles) {
             load_wchunk(dst, cur, lt, lc, wave, lane);
-        } else if (!next_issued && !reducer) {
-            load_wchunk(dst, next, blockIdx.x, 0, wave, lane);
-            next_issued = true;
         }
     };
+    (void)next_issued;
     constexpr bool kHasPre = (EPI == EPI_RESIDUAL || EPI == EPI_QKV);
     const bool stages = kHasPre && wave < kPreTiles && wave < my_tiles;   // this wave finishes tile number `wave`
     EpiPre pre0;
@@ -346,10 +344,11 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
             ++it;
         }
     }
-    if (my_tiles == 0) {
-#pragma unroll
-        for (int u = 0; u < kChunk; ++u) pf[u] = wb[u];
-    }
+    // Order in this compute unit's memory queue at the end of a phase: the last epilogue's stores,
+    // then the other waves' first chunk of the next phase, then (after the acknowledgement) the
+    // barrier signal, and only then the rest of the next phase's requests.
+    block_sync_lds();                       // the last epilogue's stores have been issued
+    if (!reducer) load_wchunk(pf, next, blockIdx.x, 0, wave, lane);
     if (reducer) {
         // this wave's epilogue stores must be out before the block counts its tiles as done; the wave
         // that completes the block's count signals the grid barrier
@@ -368,6 +367,7 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
         }
         load_wchunk(pf, next, blockIdx.x, 0, wave, lane);
     }
+    block_sync_lds();                       // the block's signal (if it was this block's turn) has been issued
     if (BARRIER) {
         tiles_before = tiles_after;
         bar.done += 1;
