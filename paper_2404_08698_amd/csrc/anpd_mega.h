@@ -276,19 +276,23 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     int tile = blockIdx.x, c = 0;     // item being computed
     int lt = blockIdx.x, lc = 0;      // last item whose weights have been requested
     bool next_issued = false;         // the next phase's first chunk has been requested
-    auto fetch = [&](uint4 (&dst)[kChunk]) {
+    // may_cross: the request may go to the next phase's first chunk when this phase has nothing left
+    // (only on entry: later it would sit in front of the last epilogue's stores)
+    auto fetch = [&](uint4 (&dst)[kChunk], bool may_cross) {
         if (++lc == n_chunks) { lc = 0; lt += grid; }
         if (lt < cur.n_tiles) {
             load_wchunk(dst, cur, lt, lc, wave, lane);
+        } else if (may_cross && !next_issued && !reducer) {
+            load_wchunk(dst, next, blockIdx.x, 0, wave, lane);
+            next_issued = true;
         }
     };
-    (void)next_issued;
     constexpr bool kHasPre = (EPI == EPI_RESIDUAL || EPI == EPI_QKV);
     const bool stages = kHasPre && wave < kPreTiles && wave < my_tiles;   // this wave finishes tile number `wave`
     EpiPre pre0;
     if (stages) epilogue_preload<EPI>(a, blockIdx.x + wave * grid, lane, pre0);
-    fetch(wb);
-    fetch(wc);
+    fetch(wb, true);
+    fetch(wc, true);
     if (stages) pre_to_lds<EPI>(sh.pre[wave], pre0, lane);
 
     bar_wait(bar);
@@ -323,7 +327,7 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
         par ^= 1;
 #pragma unroll
         for (int u = 0; u < kChunk; ++u) { pf[u] = wb[u]; wb[u] = wc[u]; }
-        fetch(wc);
+        fetch(wc, false);
         const bool tile_done = (c == n_chunks - 1);
         const int finished = tile;
         if (++c == n_chunks) { c = 0; tile += grid; }
@@ -347,8 +351,12 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     // Order in this compute unit's memory queue at the end of a phase: the last epilogue's stores,
     // then the other waves' first chunk of the next phase, then (after the acknowledgement) the
     // barrier signal, and only then the rest of the next phase's requests.
+    if (my_tiles == 0 && next_issued) {     // nothing was consumed: the chunk requested on entry sits in wb
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u) pf[u] = wb[u];
+    }
     block_sync_lds();                       // the last epilogue's stores have been issued
-    if (!reducer) load_wchunk(pf, next, blockIdx.x, 0, wave, lane);
+    if (!reducer && !next_issued) load_wchunk(pf, next, blockIdx.x, 0, wave, lane);
     if (reducer) {
         // this wave's epilogue stores must be out before the block counts its tiles as done; the wave
         // that completes the block's count signals the grid barrier
