@@ -194,6 +194,36 @@ __device__ __forceinline__ void compute_rinv(const FastArgs &a, float *rinv /* L
     block_sync_lds();
 }
 
+// compute_rinv in three steps for window class 8 and at most 256 tiles of partial sums, so that the
+// persistent kernel can request the sums when a phase starts and reduce them when the first
+// epilogue needs them, after the first tile's MFMAs.  Same additions in the same order.
+template <bool COH>
+__device__ __forceinline__ void rinv_issue(const FastArgs &a, float (&v)[4], int tid)
+{
+    const int m = tid & 7, g = tid >> 3;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int t = g + 64 * u;
+        v[u] = (m < a.M && t < a.n_ss) ? ldf_at<COH>(a.ssp, (uint32_t)(t * 32 + m)) : 0.f;
+    }
+}
+__device__ __forceinline__ void rinv_partial_to_lds(const float (&v)[4], float *scratch /* LDS [2048] */, int tid)
+{
+    float s = 0.f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) s += v[u];
+    scratch[(tid >> 3) * 32 + (tid & 7)] = s;
+}
+__device__ __forceinline__ void rinv_from_lds(const FastArgs &a, float *rinv, const float *scratch, int tid)
+{
+    if (tid < 8) {
+        float tot = 0.f;
+#pragma unroll 8
+        for (int g = 0; g < 64; ++g) tot += scratch[g * 32 + tid];
+        rinv[tid] = 1.0f / sqrtf(tot * a.inv_d + a.eps);
+    }
+}
+
 // Operands an epilogue reads from memory.  The persistent kernel requests them when the tile starts:
 // a wave's loads return in order, so a load issued at the epilogue would wait for the weight chunks
 // requested before it, and the gain vector is a first touch that comes from HBM.

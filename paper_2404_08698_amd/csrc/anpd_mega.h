@@ -240,6 +240,7 @@ struct MegaShared {
     float rinv[32];
     int tiles_done;   // epilogues finished by this block since the kernel started
     EpiPreLds pre[kPreTiles];
+    float rscratch[2048];   // group sums of the RMSNorm partials (see rinv_partial_to_lds)
 };
 
 template <int DH>
@@ -299,8 +300,13 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     if (BARRIER && my_tiles == 0 && tid == 0) bar_signal(bar);
     load_xchunk(x0, a.Xp, a.nks, 0, wave, lane);
     if (STATIONARY) load_xchunk(x1, a.Xp, a.nks, 1, wave, lane);   // else: one chunk ahead, alternating x0 / x1
-    if (EPI == EPI_QKV || EPI == EPI_GATE_UP || EPI == EPI_LOGITS || EPI == EPI_LM_ARGMAX)
-        compute_rinv<true>(a, sh.rinv, &sh.red[1][0][0]);
+    // the RMSNorm scale is needed by the first epilogue only: its partial sums are requested here and
+    // reduced after the first tile's MFMAs, off the path from the barrier to the first MFMA
+    constexpr bool kNorm = (EPI == EPI_QKV || EPI == EPI_GATE_UP || EPI == EPI_LOGITS || EPI == EPI_LM_ARGMAX);
+    const bool late_norm = kNorm && a.n_ss <= 256 && my_tiles > 0;
+    float nv[4];
+    if (late_norm) rinv_issue<true>(a, nv, tid);
+    else if (kNorm) compute_rinv<true>(a, sh.rinv, &sh.red[1][0][0]);
 
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     int it = 0, par = 0;
@@ -334,7 +340,9 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
         if (tile_done) {
             float *r = &sh.red[it & 1][0][0];
             *reinterpret_cast<f32x4 *>(r + ((size_t)wave * 64 + lane) * 4) = acc;
+            if (late_norm && it == 0) rinv_partial_to_lds(nv, sh.rscratch, tid);
             block_sync_lds();
+            if (late_norm && it == 0) rinv_from_lds(a, sh.rinv, sh.rscratch, tid);   // wave 0, which also finishes tile 0
             if (wave == (it & (kFastWaves - 1))) {
                 if (kHasPre && it < kPreTiles) {
                     EpiPre pre;
