@@ -383,7 +383,7 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
         }
         load_wchunk(pf, next, blockIdx.x, 0, wave, lane);
     }
-    block_sync_lds();                       // the block's signal (if it was this block's turn) has been issued
+    if (BARRIER) block_sync_lds();          // the block's signal (if it was this block's turn) has been issued
     if (BARRIER) {
         tiles_before = tiles_after;
         bar.done += 1;
