@@ -298,8 +298,13 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
 
     bar_wait(bar);
     if (BARRIER && my_tiles == 0 && tid == 0) bar_signal(bar);
+    // STATIONARY: both chunks of the operand stay in x0 / x1.  Otherwise x0 / x1 alternate: a step's MFMAs
+    // free one of them, and the operand chunk of the step after next is requested into it right away,
+    // BEFORE the weights requested at the end of the step, so that no step's operand waits behind
+    // weights of later steps (a wave's loads return in order).
+    const int n_steps = my_tiles * n_chunks;
     load_xchunk(x0, a.Xp, a.nks, 0, wave, lane);
-    if (STATIONARY) load_xchunk(x1, a.Xp, a.nks, 1, wave, lane);   // else: one chunk ahead, alternating x0 / x1
+    if (STATIONARY || 1 < n_steps) load_xchunk(x1, a.Xp, a.nks, STATIONARY ? 1 : 1 % n_chunks, wave, lane);
     // the RMSNorm scale is needed by the first epilogue only: its partial sums are requested here and
     // reduced after the first tile's MFMAs, off the path from the barrier to the first MFMA
     constexpr bool kNorm = (EPI == EPI_QKV || EPI == EPI_GATE_UP || EPI == EPI_LOGITS || EPI == EPI_LM_ARGMAX);
@@ -310,15 +315,8 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
 
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     int it = 0, par = 0;
+    int step = 0;
     while (tile < cur.n_tiles) {
-        if (!STATIONARY) {
-            int pc = c + 1, pt = tile;
-            if (pc == n_chunks) { pc = 0; pt += grid; }
-            if (pt < cur.n_tiles) {
-                if (par == 0) load_xchunk(x1, a.Xp, a.nks, pc, wave, lane);
-                else load_xchunk(x0, a.Xp, a.nks, pc, wave, lane);
-            }
-        }
         if (STATIONARY ? c == 1 : par == 1) {
 #pragma unroll
             for (int u = 0; u < kChunk; ++u)
@@ -330,6 +328,11 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pf[u]),
                                                               __builtin_bit_cast(bf16x8, x0[u]), acc, 0, 0, 0);
         }
+        if (!STATIONARY && step + 2 < n_steps) {
+            if (par == 1) load_xchunk(x1, a.Xp, a.nks, (step + 2) % n_chunks, wave, lane);
+            else load_xchunk(x0, a.Xp, a.nks, (step + 2) % n_chunks, wave, lane);
+        }
+        ++step;
         par ^= 1;
 #pragma unroll
         for (int u = 0; u < kChunk; ++u) { pf[u] = wb[u]; wb[u] = wc[u]; }
