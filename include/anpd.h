@@ -196,7 +196,33 @@ int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32
                     int32_t mode, int32_t *out_accepted, int32_t *out_next, int32_t *out_predicts,
                     float *out_logits, void *stream);
 
-/* Per-kernel timing of anpd_verify with events recorded on the launch stream
+/* Prompt processing.
+ *
+ * Paper, Section 3.1 "Parallel Decoding", step 1, and the opening of Algorithm 1: before any
+ * drafting the LLM reads the whole prompt once; that fills the (k, v) cache and yields the first
+ * generated token.  Same arithmetic as appending the rows with anpd_verify (same layer, same
+ * bf16 storage of K and V, causal attention over everything cached so far), but all n_tokens rows
+ * go through each weight matrix together, on the matrix cores, instead of in windows of at most
+ * ANPD_MAX_WINDOW rows; the sums are formed in a different order, so results agree with the
+ * windowed form to rounding, not bit for bit.
+ *   tokens (host, n_tokens ints) are appended at positions length .. length + n_tokens - 1; the
+ *   cache need not be empty (a prompt may be fed in pieces) and its length need not be a multiple
+ *   of the page size.  All rows are committed: length += n_tokens.
+ *   *out_next = argmax of the last row's logits (lowest index among equal maxima).
+ *   out_logits (nullable, DEVICE, vocab floats): the last row's logits.
+ *   workspace: DEVICE, 256-byte aligned, >= anpd_prefill_workspace_bytes(m, n_tokens) bytes,
+ *   used only during the call (about 110 KB per token at the 7B shape).  Models on the
+ *   dot-product path (f32 weights) process the prompt in windows of max_window rows and need no
+ *   workspace: the size is 0 and workspace may be NULL.
+ * Blocks until the result is on the host.
+ * Errors: ANPD_E_RANGE (bad token), ANPD_E_CAPACITY (length + n_tokens > max_tokens, or the
+ * workspace is too small), ANPD_E_INVAL, ANPD_E_HIP.  Nothing is launched on the first three. */
+size_t anpd_prefill_workspace_bytes(const anpd_model_t *m, int32_t n_tokens);
+int32_t anpd_prefill(anpd_model_t *m, anpd_kv_t *kv, const int32_t *tokens, int32_t n_tokens,
+                     int32_t *out_next, float *out_logits, void *workspace, size_t workspace_bytes,
+                     void *stream);
+
+/* Per-kernel timing of anpd_verify and anpd_prefill with events recorded on the launch stream
  * between kernel groups.  While enabled, every step accumulates the elapsed
  * milliseconds and the number of timed intervals per category; enabling or
  * disabling resets the sums.  out_ms, out_launches: host arrays of

@@ -30,7 +30,7 @@ EXPORTS = (
     "anpd_model_workspace_bytes", "anpd_model_create", "anpd_model_destroy",
     "anpd_kv_pool_bytes", "anpd_kv_create", "anpd_kv_destroy", "anpd_kv_length", "anpd_kv_truncate",
     "anpd_kv_set_page_order", "anpd_kv_num_pages", "anpd_kv_write", "anpd_kv_read",
-    "anpd_verify", "anpd_linear_workspace_bytes", "anpd_linear",
+    "anpd_verify", "anpd_prefill_workspace_bytes", "anpd_prefill", "anpd_linear_workspace_bytes", "anpd_linear",
     "anpd_model_profile", "anpd_model_profile_read", "anpd_packed_bytes", "anpd_pack_weights",
     "anpd_model_trace", "anpd_model_set_barrier_spin_limit",
 )
@@ -111,6 +111,10 @@ def lib():
     L.anpd_kv_read.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp]
     L.anpd_verify.restype = C.c_int32
     L.anpd_verify.argtypes = [vp, vp, i32p, C.c_int32, C.c_int32, i32p, i32p, i32p, vp, vp]
+    L.anpd_prefill_workspace_bytes.restype = C.c_size_t
+    L.anpd_prefill_workspace_bytes.argtypes = [vp, C.c_int32]
+    L.anpd_prefill.restype = C.c_int32
+    L.anpd_prefill.argtypes = [vp, vp, i32p, C.c_int32, i32p, vp, vp, C.c_size_t, vp]
     L.anpd_linear_workspace_bytes.restype = C.c_size_t
     L.anpd_linear_workspace_bytes.argtypes = [C.c_int32, C.c_int32]
     L.anpd_linear.restype = C.c_int32
@@ -391,9 +395,35 @@ def linear(X, W, path: int, stream=None, packed=None, Y=None, workspace=None):
 
 # ------------------------------------------------------------ decode loops
 
-def prefill(model: Model, kv: KVCache, prompt: Sequence[int], stream=None) -> int:
-    """LLM(prompt) of Algorithm 1 through the verification kernels: the prompt is
-    appended in chunks of max_window rows; returns the greedy token after it."""
+def prefill_workspace_bytes(model: Model, n_tokens: int) -> int:
+    """anpd_prefill_workspace_bytes (0 for models that process the prompt in windows)."""
+    return int(lib().anpd_prefill_workspace_bytes(model._h, n_tokens))
+
+
+def prefill(model: Model, kv: KVCache, prompt: Sequence[int], stream=None, out_logits=None, workspace=None) -> int:
+    """anpd_prefill: LLM(prompt) of Algorithm 1, all rows in one pass; returns the greedy token
+    after the prompt.  ``out_logits``: CUDA float32 [vocab] for the last row's logits.
+    ``workspace``: a CUDA uint8 tensor to reuse (allocated here if absent)."""
+    import torch
+    n = len(prompt)
+    nb = prefill_workspace_bytes(model, n) if n >= 1 else 0
+    ws = workspace
+    if ws is None or ws.numel() < nb:
+        ws = torch.empty(max(nb, 256), dtype=torch.uint8, device="cuda")
+    lp = 0
+    if out_logits is not None:
+        assert out_logits.is_cuda and out_logits.dtype == torch.float32 and out_logits.is_contiguous()
+        assert out_logits.numel() >= model.vocab
+        lp = out_logits.data_ptr()
+    nxt = C.c_int32(0)
+    _check(lib().anpd_prefill(model._h, kv._h, _ints(prompt), n, C.byref(nxt), lp, ws.data_ptr(), ws.numel(),
+                              _stream_ptr(stream)))
+    return nxt.value
+
+
+def prefill_windows(model: Model, kv: KVCache, prompt: Sequence[int], stream=None) -> int:
+    """The prompt appended through the verification step in windows of max_window rows (what
+    anpd_prefill replaces on the matrix-core path); returns the greedy token after it."""
     nxt = -1
     for lo in range(0, len(prompt), model.max_window):
         _, nxt = verify(model, kv, prompt[lo:lo + model.max_window], APPEND, stream=stream)

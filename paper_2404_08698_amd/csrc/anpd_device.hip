@@ -17,6 +17,7 @@
 #include "anpd_kernels.h"
 #include "anpd_fast.h"
 #include "anpd_mega.h"
+#include "anpd_prefill.h"
 
 using namespace anpd;
 
@@ -112,6 +113,28 @@ Layout make_layout(const anpd_model_cfg *c)
             L.wp_down.push_back(take(packed_bytes(d / 16, (int)F)));
         }
     }
+    L.total = o;
+    return L;
+}
+
+struct PrefillLayout {  // byte offsets into the caller's prefill workspace
+    size_t tok, x, xq, xq_att, xq_f, qp, total;
+};
+
+// Sized for the worst alignment of the first row inside its cache page.
+PrefillLayout make_prefill_layout(const anpd_model_cfg &c, int n_tokens)
+{
+    PrefillLayout L;
+    const size_t G = ((size_t)n_tokens + 30) / 16, d = (size_t)c.d_model, F = (size_t)c.d_ffn;
+    const size_t nks_d = (d + 31) / 32, nks_f = (F + 31) / 32;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+    L.tok = take((size_t)n_tokens * sizeof(int32_t));
+    L.x = take(G * 16 * d * sizeof(float));
+    L.xq = take(G * nks_d * 2048);
+    L.xq_att = take(G * nks_d * 2048);
+    L.xq_f = take(G * nks_f * 2048);
+    L.qp = take((size_t)c.n_heads * G * (size_t)(c.head_dim / 32) * 2048);
     L.total = o;
     return L;
 }
@@ -295,6 +318,20 @@ inline void mark(anpd_model *m, int cat, hipStream_t st)
     m->ev_cat[(size_t)m->ev_used] = cat;
     (void)hipEventRecord(m->ev[(size_t)m->ev_used], st);
     m->ev_used += 1;
+}
+
+// After the stream has been synchronised: add the intervals between this call's marks to the sums.
+void collect_marks(anpd_model *m)
+{
+    if (!m->prof) return;
+    for (int i = 1; i < m->ev_used; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, m->ev[(size_t)i - 1], m->ev[(size_t)i]) == hipSuccess) {
+            m->prof_ms[m->ev_cat[(size_t)i]] += (double)ms;
+            m->prof_launches[m->ev_cat[(size_t)i]] += 1;
+        }
+    }
+    m->prof_steps += 1;
 }
 
 template <typename KT>
@@ -546,6 +583,144 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, 
     m->bar_epoch += (uint32_t)kMegaBarriers(c.n_layers);
     m->ready_epoch += (uint32_t)c.n_layers;
     mark(m, ANPD_PROF_STEP, st);
+    return ANPD_OK;
+}
+
+// ---- prompt processing on the matrix cores ------------------------------------
+
+template <int EPI>
+int32_t launch_prefill_gemm(const PrefillArgs &a, hipStream_t st)
+{
+    const int n_bt = (a.n_tiles + 2 * kPfTN - 1) / (2 * kPfTN), n_br = (a.G + 2 * kPfTM - 1) / (2 * kPfTM);
+    hipLaunchKernelGGL((prefill_gemm_kernel<EPI>), dim3((unsigned)(n_bt * n_br)), dim3(kPfThreads), 0, st, a);
+    HIP_TRY(hipGetLastError());
+    return ANPD_OK;
+}
+
+// All P rows at once; per layer norm -> QKV(+RoPE, cache write) -> attention -> O(+residual) -> norm ->
+// gate/up(+SwiGLU) -> down(+residual); the last row then goes through the step's LM head and argmax.
+int32_t run_prefill_mfma(anpd_model *m, anpd_kv *kv, int P, char *pws, const PrefillLayout &PL, hipStream_t st)
+{
+    const anpd_model_cfg &c = m->cfg;
+    const Layout &L = m->lay;
+    char *ws = m->ws;
+    const int d = c.d_model, F = c.d_ffn, V = c.vocab, H = c.n_heads, dh = c.head_dim;
+    const int len = kv->len, r0 = len & 15;
+    const int G = (r0 + P + 15) / 16;
+    const int nks_d = (d + 31) / 32, nks_f = (F + 31) / 32;
+    const int32_t *tok = (const int32_t *)(pws + PL.tok);
+    float *x = (float *)(pws + PL.x);
+    bf16_t *xq = (bf16_t *)(pws + PL.xq), *xq_att = (bf16_t *)(pws + PL.xq_att), *xq_f = (bf16_t *)(pws + PL.xq_f);
+    bf16_t *qp = (bf16_t *)(pws + PL.qp);
+    const float inv_d = 1.0f / (float)d, scale = 1.0f / sqrtf((float)dh);
+    int32_t rc;
+
+    PrefillArgs base;
+    std::memset(&base, 0, sizeof(base));
+    base.G = G;
+    base.L = len;
+    base.P = P;
+    base.x = x;
+    base.d = d;
+    base.qp = qp;
+    base.pool = (bf16_t *)kv->pool;
+    base.page_table = kv->d_table;
+    base.rope = (const float2 *)(ws + L.rope_tab);
+    base.n_layers = c.n_layers;
+    base.n_heads = H;
+    base.head_dim = dh;
+
+    m->ev_used = 0;
+    mark(m, -1, st);
+    // columns F .. 32 * nks_f of the down projection's operand meet zero weights: they must not hold NaN patterns
+    if (F % 32 != 0) HIP_TRY(hipMemsetAsync(xq_f, 0, (size_t)G * nks_f * 2048, st));
+    hipLaunchKernelGGL((prefill_norm_kernel<true>), dim3((unsigned)(G * 16)), dim3(256), 0, st, (const bf16_t *)m->embed, tok, x,
+                       (const bf16_t *)m->attn_norm[0], xq, nks_d, d, len, P, inv_d, c.rms_eps);
+    mark(m, ANPD_PROF_OTHER, st);
+    for (int l = 0; l < c.n_layers; ++l) {
+        {
+            PrefillArgs a = base;
+            a.Wp = (const uint4 *)(ws + L.wp_qkv[(size_t)l]);
+            a.Xq = (const uint4 *)xq;
+            a.nks = nks_d;
+            a.n_tiles = 3 * d / 16;
+            a.layer = l;
+            if ((rc = launch_prefill_gemm<EPI_QKV>(a, st)) != ANPD_OK) return rc;
+        }
+        mark(m, ANPD_PROF_GEMM_QKV, st);
+        if (dh == 128)
+            hipLaunchKernelGGL((prefill_attn_kernel<128>), dim3((unsigned)H, (unsigned)((G + 3) / 4)), dim3(256), 0, st, (const uint4 *)qp,
+                               (const bf16_t *)kv->pool, kv->d_table, G, len, P, l, c.n_layers, H, scale, xq_att, nks_d);
+        else
+            hipLaunchKernelGGL((prefill_attn_kernel<64>), dim3((unsigned)H, (unsigned)((G + 3) / 4)), dim3(256), 0, st, (const uint4 *)qp,
+                               (const bf16_t *)kv->pool, kv->d_table, G, len, P, l, c.n_layers, H, scale, xq_att, nks_d);
+        mark(m, ANPD_PROF_ATTN, st);
+        {
+            PrefillArgs a = base;
+            a.Wp = (const uint4 *)(ws + L.wp_o[(size_t)l]);
+            a.Xq = (const uint4 *)xq_att;
+            a.nks = nks_d;
+            a.n_tiles = d / 16;
+            if ((rc = launch_prefill_gemm<EPI_RESIDUAL>(a, st)) != ANPD_OK) return rc;
+        }
+        mark(m, ANPD_PROF_GEMM_O, st);
+        hipLaunchKernelGGL((prefill_norm_kernel<false>), dim3((unsigned)(G * 16)), dim3(256), 0, st, (const bf16_t *)nullptr, tok, x,
+                           (const bf16_t *)m->ffn_norm[l], xq, nks_d, d, len, P, inv_d, c.rms_eps);
+        mark(m, ANPD_PROF_OTHER, st);
+        {
+            PrefillArgs a = base;
+            a.Wp = (const uint4 *)(ws + L.wp_gu[(size_t)l]);
+            a.Xq = (const uint4 *)xq;
+            a.nks = nks_d;
+            a.n_tiles = F / 8;
+            a.out = xq_f;
+            a.out_nks = nks_f;
+            if ((rc = launch_prefill_gemm<EPI_GATE_UP>(a, st)) != ANPD_OK) return rc;
+        }
+        mark(m, ANPD_PROF_GEMM_GATE_UP, st);
+        {
+            PrefillArgs a = base;
+            a.Wp = (const uint4 *)(ws + L.wp_down[(size_t)l]);
+            a.Xq = (const uint4 *)xq_f;
+            a.nks = nks_f;
+            a.n_tiles = d / 16;
+            if ((rc = launch_prefill_gemm<EPI_RESIDUAL>(a, st)) != ANPD_OK) return rc;
+        }
+        mark(m, ANPD_PROF_GEMM_DOWN, st);
+        if (l + 1 < c.n_layers) {
+            hipLaunchKernelGGL((prefill_norm_kernel<false>), dim3((unsigned)(G * 16)), dim3(256), 0, st, (const bf16_t *)nullptr, tok,
+                               x, (const bf16_t *)m->attn_norm[(size_t)l + 1], xq, nks_d, d, len, P, inv_d, c.rms_eps);
+            mark(m, ANPD_PROF_OTHER, st);
+        }
+    }
+    // last row -> the step's LM head, argmax and length update (one appended row)
+    hipLaunchKernelGGL(prefill_last_kernel, dim3((unsigned)(d / 16)), dim3(64), 0, st, x + (size_t)(r0 + P - 1) * d,
+                       (const bf16_t *)m->final_norm, (bf16_t *)(ws + L.xp_d), (float *)(ws + L.ssp_a), kv->d_len, len + P - 1);
+    mark(m, ANPD_PROF_OTHER, st);
+    {
+        FastArgs a;
+        std::memset(&a, 0, sizeof(a));
+        a.M = 1;
+        a.cls = 8;
+        a.inv_d = inv_d;
+        a.eps = c.rms_eps;
+        a.n_ss = d / 16;
+        a.d = d;
+        a.Wp = (const uint4 *)(ws + L.wp_lm);
+        a.Xp = (const uint4 *)(ws + L.xp_d);
+        a.nks = nks_d;
+        a.n_tiles = V / 16;
+        a.ssp = (const float *)(ws + L.ssp_a);
+        a.Y = (float *)(ws + L.logits);
+        a.ldy = V;
+        if ((rc = launch_fast<EPI_LOGITS>(a, m->n_cu, false, st)) != ANPD_OK) return rc;
+    }
+    mark(m, ANPD_PROF_GEMM_LM_HEAD, st);
+    hipLaunchKernelGGL(argmax_accept_kernel, dim3(1), dim3(1024), 0, st, (const float *)(ws + L.logits), V, 1,
+                       (const int32_t *)(ws + L.tok), (int)ANPD_APPEND, (int32_t *)(ws + L.result), kv->d_len,
+                       (uint32_t *)(ws + L.counter));
+    mark(m, ANPD_PROF_OTHER, st);
+    HIP_TRY(hipGetLastError());
     return ANPD_OK;
 }
 
@@ -918,21 +1093,72 @@ int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32
         m->ready_epoch = 0;
         return fail(ANPD_E_HIP, "anpd_verify: the persistent kernel timed out at a grid barrier");
     }
-    if (m->prof) {
-        for (int i = 1; i < m->ev_used; ++i) {
-            float ms = 0.f;
-            if (hipEventElapsedTime(&ms, m->ev[(size_t)i - 1], m->ev[(size_t)i]) == hipSuccess) {
-                m->prof_ms[m->ev_cat[(size_t)i]] += (double)ms;
-                m->prof_launches[m->ev_cat[(size_t)i]] += 1;
-            }
-        }
-        m->prof_steps += 1;
-    }
+    collect_marks(m);
     *out_accepted = res[0];
     *out_next = res[1];
     if (out_predicts) std::memcpy(out_predicts, res + 2, sizeof(int32_t) * (size_t)n_window);
     kv->len += 1 + res[0];
     release_pages(kv, kv->len);
+    return ANPD_OK;
+}
+
+size_t anpd_prefill_workspace_bytes(const anpd_model_t *m, int32_t n_tokens)
+{
+    if (!m || n_tokens < 1 || n_tokens > m->cfg.max_positions) {
+        fail(ANPD_E_INVAL, "anpd_prefill_workspace_bytes: bad argument");
+        return 0;
+    }
+    return m->mfma ? make_prefill_layout(m->cfg, n_tokens).total : 0;
+}
+
+int32_t anpd_prefill(anpd_model_t *m, anpd_kv_t *kv, const int32_t *tokens, int32_t n_tokens, int32_t *out_next,
+                     float *out_logits, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!m || !kv || !tokens || !out_next) return fail(ANPD_E_INVAL, "anpd_prefill: NULL argument");
+    if (kv->m != m) return fail(ANPD_E_INVAL, "anpd_prefill: the cache belongs to another model");
+    if (n_tokens < 1) return fail(ANPD_E_INVAL, "anpd_prefill: n_tokens must be >= 1");
+    if (kv->len + n_tokens > kv->max_tokens)
+        return fail(ANPD_E_CAPACITY, "anpd_prefill: length %d + %d tokens exceeds capacity %d", kv->len, n_tokens, kv->max_tokens);
+    for (int i = 0; i < n_tokens; ++i)
+        if (tokens[i] < 0 || tokens[i] >= m->cfg.vocab)
+            return fail(ANPD_E_RANGE, "anpd_prefill: token %d at tokens[%d] outside [0, %d)", tokens[i], i, m->cfg.vocab);
+    hipStream_t st = (hipStream_t)stream;
+    const size_t V = (size_t)m->cfg.vocab;
+
+    if (!m->mfma) {
+        // dot-product models: the prompt goes through the step in windows of max_window appended rows
+        int32_t acc = 0, last_n = 0;
+        for (int i = 0; i < n_tokens; i += last_n) {
+            last_n = n_tokens - i < m->cfg.max_window ? n_tokens - i : m->cfg.max_window;
+            int32_t rc = anpd_verify(m, kv, tokens + i, last_n, ANPD_APPEND, &acc, out_next, nullptr, nullptr, stream);
+            if (rc != ANPD_OK) return rc;
+        }
+        if (out_logits) {
+            HIP_TRY(hipMemcpyAsync(out_logits, m->ws + m->lay.logits + (size_t)(last_n - 1) * V * sizeof(float), V * sizeof(float),
+                                   hipMemcpyDeviceToDevice, st));
+            HIP_TRY(hipStreamSynchronize(st));
+        }
+        return ANPD_OK;
+    }
+
+    const PrefillLayout PL = make_prefill_layout(m->cfg, n_tokens);
+    if (!workspace || ((uintptr_t)workspace & 255) != 0) return fail(ANPD_E_INVAL, "anpd_prefill: workspace must be a 256-byte aligned device buffer");
+    if (workspace_bytes < PL.total)
+        return fail(ANPD_E_CAPACITY, "anpd_prefill: workspace has %zu bytes, %zu needed", workspace_bytes, PL.total);
+    int32_t rc = ensure_pages(kv, kv->len + n_tokens, st);
+    if (rc != ANPD_OK) return rc;
+    char *pws = (char *)workspace;
+    HIP_TRY(hipMemcpyAsync(pws + PL.tok, tokens, sizeof(int32_t) * (size_t)n_tokens, hipMemcpyHostToDevice, st));
+    rc = run_prefill_mfma(m, kv, n_tokens, pws, PL, st);
+    if (rc != ANPD_OK) return rc;
+    int32_t *res = m->pin + 32;
+    HIP_TRY(hipMemcpyAsync(res, m->ws + m->lay.result, sizeof(int32_t) * 3, hipMemcpyDeviceToHost, st));
+    if (out_logits)
+        HIP_TRY(hipMemcpyAsync(out_logits, m->ws + m->lay.logits, V * sizeof(float), hipMemcpyDeviceToDevice, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    collect_marks(m);
+    *out_next = res[1];
+    kv->len += n_tokens;
     return ANPD_OK;
 }
 
