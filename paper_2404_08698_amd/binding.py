@@ -162,8 +162,11 @@ class NgramTable:
         self._h = h
 
     def close(self):
-        if getattr(self, "_h", None) and _alive():
-            lib().anpd_ngram_destroy(self._h)
+        try:
+            if getattr(self, "_h", None) and _alive():
+                lib().anpd_ngram_destroy(self._h)
+        except TypeError:   # interpreter shutdown: this module's globals are already gone
+            pass
         self._h = None
 
     def __del__(self):
@@ -240,8 +243,11 @@ class Model:
         self.max_window = max_window
 
     def close(self):
-        if getattr(self, "_h", None) and _alive():
-            lib().anpd_model_destroy(self._h)
+        try:
+            if getattr(self, "_h", None) and _alive():
+                lib().anpd_model_destroy(self._h)
+        except TypeError:   # interpreter shutdown: this module's globals are already gone
+            pass
         self._h = None
 
     def __del__(self):
@@ -297,8 +303,11 @@ class KVCache:
         self.max_tokens = max_tokens
 
     def close(self):
-        if getattr(self, "_h", None) and _alive():
-            lib().anpd_kv_destroy(self._h)
+        try:
+            if getattr(self, "_h", None) and _alive():
+                lib().anpd_kv_destroy(self._h)
+        except TypeError:   # interpreter shutdown: this module's globals are already gone
+            pass
         self._h = None
 
     def __del__(self):

@@ -118,7 +118,7 @@ Layout make_layout(const anpd_model_cfg *c)
 }
 
 struct PrefillLayout {  // byte offsets into the caller's prefill workspace
-    size_t tok, x, xq, xq_att, xq_f, qp, total;
+    size_t tok, x, part, xq, xq_att, xq_f, qp, total;
 };
 
 // Sized for the worst alignment of the first row inside its cache page.
@@ -131,6 +131,7 @@ PrefillLayout make_prefill_layout(const anpd_model_cfg &c, int n_tokens)
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
     L.tok = take((size_t)n_tokens * sizeof(int32_t));
     L.x = take(G * 16 * d * sizeof(float));
+    L.part = take((size_t)kPgSplit * G * 16 * d * sizeof(float));
     L.xq = take(G * nks_d * 2048);
     L.xq_att = take(G * nks_d * 2048);
     L.xq_f = take(G * nks_f * 2048);
@@ -591,8 +592,13 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, 
 template <int EPI>
 int32_t launch_prefill_gemm(const PrefillArgs &a, hipStream_t st)
 {
-    const int n_bt = (a.n_tiles + 2 * kPfTN - 1) / (2 * kPfTN), n_br = (a.G + 2 * kPfTM - 1) / (2 * kPfTM);
-    hipLaunchKernelGGL((prefill_gemm_kernel<EPI>), dim3((unsigned)(n_bt * n_br)), dim3(kPfThreads), 0, st, a);
+    const int n_bt = (a.n_tiles + 15) / 16, n_br = (a.G + 7) / 8;
+    static bool attr_set = false;   // per epilogue
+    if (!attr_set) {
+        HIP_TRY(hipFuncSetAttribute((const void *)prefill_gemm_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPgLdsBytes));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((prefill_gemm_kernel<EPI>), dim3((unsigned)(n_bt * a.S * n_br)), dim3(kPgThreads), kPgLdsBytes, st, a);
     HIP_TRY(hipGetLastError());
     return ANPD_OK;
 }
@@ -609,7 +615,7 @@ int32_t run_prefill_mfma(anpd_model *m, anpd_kv *kv, int P, char *pws, const Pre
     const int G = (r0 + P + 15) / 16;
     const int nks_d = (d + 31) / 32, nks_f = (F + 31) / 32;
     const int32_t *tok = (const int32_t *)(pws + PL.tok);
-    float *x = (float *)(pws + PL.x);
+    float *x = (float *)(pws + PL.x), *part = (float *)(pws + PL.part);
     bf16_t *xq = (bf16_t *)(pws + PL.xq), *xq_att = (bf16_t *)(pws + PL.xq_att), *xq_f = (bf16_t *)(pws + PL.xq_f);
     bf16_t *qp = (bf16_t *)(pws + PL.qp);
     const float inv_d = 1.0f / (float)d, scale = 1.0f / sqrtf((float)dh);
@@ -620,7 +626,8 @@ int32_t run_prefill_mfma(anpd_model *m, anpd_kv *kv, int P, char *pws, const Pre
     base.G = G;
     base.L = len;
     base.P = P;
-    base.x = x;
+    base.S = 1;
+    base.part = part;
     base.d = d;
     base.qp = qp;
     base.pool = (bf16_t *)kv->pool;
@@ -635,7 +642,7 @@ int32_t run_prefill_mfma(anpd_model *m, anpd_kv *kv, int P, char *pws, const Pre
     // columns F .. 32 * nks_f of the down projection's operand meet zero weights: they must not hold NaN patterns
     if (F % 32 != 0) HIP_TRY(hipMemsetAsync(xq_f, 0, (size_t)G * nks_f * 2048, st));
     hipLaunchKernelGGL((prefill_norm_kernel<true>), dim3((unsigned)(G * 16)), dim3(256), 0, st, (const bf16_t *)m->embed, tok, x,
-                       (const bf16_t *)m->attn_norm[0], xq, nks_d, d, len, P, inv_d, c.rms_eps);
+                       (const float *)nullptr, 0, (const bf16_t *)m->attn_norm[0], xq, nks_d, d, len, P, inv_d, c.rms_eps);
     mark(m, ANPD_PROF_OTHER, st);
     for (int l = 0; l < c.n_layers; ++l) {
         {
@@ -661,11 +668,12 @@ int32_t run_prefill_mfma(anpd_model *m, anpd_kv *kv, int P, char *pws, const Pre
             a.Xq = (const uint4 *)xq_att;
             a.nks = nks_d;
             a.n_tiles = d / 16;
+            a.S = kPgSplit;
             if ((rc = launch_prefill_gemm<EPI_RESIDUAL>(a, st)) != ANPD_OK) return rc;
         }
         mark(m, ANPD_PROF_GEMM_O, st);
         hipLaunchKernelGGL((prefill_norm_kernel<false>), dim3((unsigned)(G * 16)), dim3(256), 0, st, (const bf16_t *)nullptr, tok, x,
-                           (const bf16_t *)m->ffn_norm[l], xq, nks_d, d, len, P, inv_d, c.rms_eps);
+                           (const float *)part, kPgSplit, (const bf16_t *)m->ffn_norm[l], xq, nks_d, d, len, P, inv_d, c.rms_eps);
         mark(m, ANPD_PROF_OTHER, st);
         {
             PrefillArgs a = base;
@@ -684,18 +692,19 @@ int32_t run_prefill_mfma(anpd_model *m, anpd_kv *kv, int P, char *pws, const Pre
             a.Xq = (const uint4 *)xq_f;
             a.nks = nks_f;
             a.n_tiles = d / 16;
+            a.S = kPgSplit;
             if ((rc = launch_prefill_gemm<EPI_RESIDUAL>(a, st)) != ANPD_OK) return rc;
         }
         mark(m, ANPD_PROF_GEMM_DOWN, st);
         if (l + 1 < c.n_layers) {
             hipLaunchKernelGGL((prefill_norm_kernel<false>), dim3((unsigned)(G * 16)), dim3(256), 0, st, (const bf16_t *)nullptr, tok,
-                               x, (const bf16_t *)m->attn_norm[(size_t)l + 1], xq, nks_d, d, len, P, inv_d, c.rms_eps);
+                               x, (const float *)part, kPgSplit, (const bf16_t *)m->attn_norm[(size_t)l + 1], xq, nks_d, d, len, P, inv_d, c.rms_eps);
             mark(m, ANPD_PROF_OTHER, st);
         }
     }
     // last row -> the step's LM head, argmax and length update (one appended row)
     hipLaunchKernelGGL(prefill_last_kernel, dim3((unsigned)(d / 16)), dim3(64), 0, st, x + (size_t)(r0 + P - 1) * d,
-                       (const bf16_t *)m->final_norm, (bf16_t *)(ws + L.xp_d), (float *)(ws + L.ssp_a), kv->d_len, len + P - 1);
+                       (const float *)(part + (size_t)(r0 + P - 1) * d), kPgSplit, (size_t)G * 16 * d, (const bf16_t *)m->final_norm, (bf16_t *)(ws + L.xp_d), (float *)(ws + L.ssp_a), kv->d_len, len + P - 1);
     mark(m, ANPD_PROF_OTHER, st);
     {
         FastArgs a;

@@ -5,8 +5,8 @@
 // the (k, v) cache and yields the first generated token.  With hundreds of
 // rows the GEMMs are bound by the matrix cores, not by weight streaming, so
 // they get a form of their own: every wave owns a 64-feature x 64-row output
-// tile over the whole K, and a weight fragment it loads meets 4 row groups
-// (each as hi and lo term) instead of one.
+// tile, a weight fragment meets 4 row groups (each as hi and lo term) instead
+// of one, and the eight waves of a block share their fragments through LDS.
 //
 // Shared with the verification step: the packed weights (MFMA-fragment order,
 // weights as the A operand, activations as the B operand, so the fused
@@ -28,16 +28,22 @@
 
 namespace anpd {
 
-constexpr int kPfThreads = 256;       // 4 waves: 2 (features) x 2 (rows)
+constexpr int kPgThreads = 512;       // GEMM block: 8 waves, 4 (features) x 2 (rows)
 constexpr int kPfTN = 4, kPfTM = 4;   // wave tile: 4 weight tiles x 4 row groups
+constexpr int kPgStages = 4;          // LDS ring of k-steps
+constexpr int kPgLead = 3;            // k-steps requested ahead of the one being multiplied
+constexpr int kPgUnits = 32;          // 1 KiB fragments per k-step: 16 weight tiles, 8 row groups x (hi, lo)
+constexpr int kPgSplit = 4;           // K splits of the residual GEMMs
+constexpr size_t kPgLdsBytes = (size_t)kPgStages * kPgUnits * 1024;
 
 struct PrefillArgs {
     const uint4 *Wp;      // packed weights [n_tiles][nks][64]
     const uint4 *Xq;      // activation operand [G][nks][2][64]
     int nks, n_tiles, G;
     int L, P;             // cache length before the call, prompt rows
+    int S;                // K splits (1 except RESIDUAL)
     // RESIDUAL
-    float *x;             // residual stream fp32 [16 G][d], updated in place
+    float *part;          // partial products fp32 [S][16 G][d]
     int d;
     // GATE_UP
     bf16_t *out;          // operand of the down projection
@@ -78,19 +84,22 @@ __device__ __forceinline__ f32x4 widen4(uint2 b)
 
 // ------------------------------------------------------------ RMSNorm rows
 //
-// Row m: h = x * g / sqrt(mean(x^2) + eps), stored as the split operand of the
-// GEMM that follows.  EMBED: the row is first fetched from the embedding table
+// Row m: first x += the S partial products of the residual GEMM that ran
+// before (in split order; S = 0: nothing to add), then
+// h = x * g / sqrt(mean(x^2) + eps), stored as the split operand of the GEMM
+// that follows.  EMBED: the row is fetched from the embedding table instead
 // (x[m] = E[token]).  Rows outside the prompt are stored as zeros.
 // grid: 16 G blocks (one per row) of 256 threads.
 template <bool EMBED>
 __global__ __launch_bounds__(256) void prefill_norm_kernel(const bf16_t *__restrict__ E, const int32_t *__restrict__ tok,
-                                                            float *__restrict__ x, const bf16_t *__restrict__ gain,
-                                                            bf16_t *__restrict__ xq, int nks, int d, int L, int P, float inv_d,
-                                                            float eps)
+                                                            float *__restrict__ x, const float *__restrict__ part, int S,
+                                                            const bf16_t *__restrict__ gain, bf16_t *__restrict__ xq, int nks,
+                                                            int d, int L, int P, float inv_d, float eps)
 {
-    __shared__ float part[4];
+    __shared__ float red[4];
     const int m = blockIdx.x, r = m - (L & 15);
     const bool valid = r >= 0 && r < P;
+    const size_t rows = (size_t)gridDim.x;
     float *xr = x + (size_t)m * d;
     float ss = 0.f;
     if (valid) {
@@ -99,17 +108,18 @@ __global__ __launch_bounds__(256) void prefill_norm_kernel(const bf16_t *__restr
             f32x4 v;
             if (EMBED) {
                 v = widen4(*reinterpret_cast<const uint2 *>(er + k));
-                *reinterpret_cast<f32x4 *>(xr + k) = v;
             } else {
                 v = *reinterpret_cast<const f32x4 *>(xr + k);
+                for (int s = 0; s < S; ++s) v += *reinterpret_cast<const f32x4 *>(part + ((size_t)s * rows + m) * d + k);
             }
+            if (EMBED || S > 0) *reinterpret_cast<f32x4 *>(xr + k) = v;
             ss = fmaf(v[3], v[3], fmaf(v[2], v[2], fmaf(v[1], v[1], fmaf(v[0], v[0], ss))));
         }
     }
     ss = wave_sum(ss);
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
-    const float rinv = 1.0f / sqrtf((part[0] + part[1] + part[2] + part[3]) * inv_d + eps);
+    const float rinv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) * inv_d + eps);
     for (int k = 4 * threadIdx.x; k < d; k += 1024) {
         f32x4 h = {0.f, 0.f, 0.f, 0.f};
         if (valid) h = *reinterpret_cast<const f32x4 *>(xr + k) * rinv * widen4(*reinterpret_cast<const uint2 *>(gain + k));
@@ -129,13 +139,10 @@ __host__ __device__ __forceinline__ size_t qpf_offset(int head, int G, int head_
 // y: this lane's four outputs (features 4 kg .. 4 kg + 3 of weight tile `tile`) for row m.
 // Every lane of the wave must call this: the fused forms exchange values with lane ^ 32.
 template <int EPI>
-__device__ __forceinline__ void prefill_epilogue(const PrefillArgs &a, int tile, int m, int kg, f32x4 y, bool valid)
+__device__ __forceinline__ void prefill_epilogue(const PrefillArgs &a, int tile, int m, int kg, f32x4 y, bool valid, int sp)
 {
     if (EPI == EPI_RESIDUAL) {
-        if (valid) {
-            float *xr = a.x + (size_t)m * a.d + tile * 16 + 4 * kg;
-            *reinterpret_cast<f32x4 *>(xr) = *reinterpret_cast<const f32x4 *>(xr) + y;
-        }
+        if (valid) *reinterpret_cast<f32x4 *>(a.part + ((size_t)sp * a.G * 16 + m) * a.d + tile * 16 + 4 * kg) = y;
     } else if (EPI == EPI_GATE_UP) {
         f32x4 up;
 #pragma unroll
@@ -194,76 +201,158 @@ __device__ __forceinline__ void prefill_epilogue(const PrefillArgs &a, int tile,
 // -------------------------------------------------------------------- GEMM
 //
 // Y^T[features][rows] = W X^T with hi and lo terms of X accumulated into the
-// same tile.  Block = 2 x 2 waves, 128 features x 128 rows; consecutive
-// blocks share a weight range (rows run fastest).  A wave streams its 4
-// weight fragments and 8 activation fragments per k-step straight into
-// registers (buffer loads: absent tiles and row groups read zeros and fetch
-// nothing), one k-step ahead of the matrix cores; two blocks per compute unit
-// cover each other's waits.  Each wave owns its tile over the whole K, so
-// there is no cross-wave reduction and every epilogue runs from registers.
-// grid: ceil(n_tiles / 8) * ceil(G / 8) blocks.
-template <int EPI>
-__global__ __launch_bounds__(kPfThreads, 2) void prefill_gemm_kernel(PrefillArgs a)
+// same tile.  Block = 4 x 2 waves, 256 features x 128 rows, each wave a
+// 64 x 64 tile (4 weight fragments x 4 row groups).  Per k-step the block
+// needs 16 weight fragments and 16 activation fragments of 1 KiB; each wave
+// requests four of them straight into LDS (buffer loads with the LDS bit:
+// lane i's 16 bytes land at base + 16 i, the fragment order itself; absent
+// tiles and row groups read zeros and fetch nothing), three k-steps ahead of
+// the matrix cores through a ring of four stages, and every wave then reads
+// its 12 fragments from LDS.  A fragment thus crosses the L2 -> CU path once
+// per block instead of once per wave that uses it.
+// One block barrier per k-step: it publishes the stage whose loads the waves
+// have just waited for, and frees the stage read in the previous iteration
+// for the request that follows it.
+// RESIDUAL GEMMs (few output features) are split S ways along K so that the
+// grid fills the chip; the S partial tiles go to `part` and are added to the
+// residual stream, in split order, by the norm kernel that follows.  S is
+// fixed by the matrix, never by the number of rows: a row's sums are formed
+// in the same order whatever else is in the batch.
+// grid: ceil(n_tiles / 16) * S * ceil(G / 8) blocks; rows run fastest, so
+// consecutive blocks share a weight range.
+template <int OFF>
+__device__ __forceinline__ u32x4_t lds_read16(uint32_t addr)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int n_br = (a.G + 2 * kPfTM - 1) / (2 * kPfTM);
-    const int bt = blockIdx.x / n_br, br = blockIdx.x - bt * n_br;
-    const int f0 = (bt * 2 + (wave & 1)) * kPfTN, g0 = (br * 2 + (wave >> 1)) * kPfTM;
-    if (f0 >= a.n_tiles || g0 >= a.G) return;   // (no block-wide synchronisation below)
-    const int nks = a.nks;
+    u32x4_t v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+    return v;
+}
 
-    __amdgpu_buffer_rsrc_t rw[kPfTN];
-#pragma unroll
-    for (int t = 0; t < kPfTN; ++t) {
-        const bool have = f0 + t < a.n_tiles;
-        rw[t] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(a.Wp + (size_t)(have ? f0 + t : 0) * nks * 64), 0,
-                                                  have ? nks * 1024 : 0, 0x00020000);
+template <int EPI>
+__global__ __launch_bounds__(kPgThreads) void prefill_gemm_kernel(PrefillArgs a)
+{
+    extern __shared__ uint4 ring[];   // [kPgStages][kPgUnits][64]
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wf = wave & 3, wr = wave >> 2;
+    const int n_br = (a.G + 7) / 8;
+    // Blocks are dealt to the 8 XCDs in turn, and each XCD has its own L2.  Give XCD x a contiguous
+    // range of the (weights, rows) order, so that the blocks sharing a weight range, and the row
+    // blocks they all stream in step, meet in one L2 instead of being fetched into several.
+    int id;
+    {
+        const int n = (int)gridDim.x, per = (n + 7) / 8, rem = n % 8;
+        const int xcd = (int)blockIdx.x % 8, j = (int)blockIdx.x / 8;
+        id = (rem == 0 || xcd < rem ? xcd * per : rem * per + (xcd - rem) * (per - 1)) + j;
     }
-    // the wave's row groups as one buffer: groups beyond G lie outside it
-    const int n_g = a.G - g0 < kPfTM ? a.G - g0 : kPfTM;
-    __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(a.Xq + (size_t)g0 * nks * 128), 0,
-                                                                  n_g * nks * 2048, 0x00020000);
+    const int br = id % n_br;
+    id /= n_br;
+    const int sp = id % a.S, bt = id / a.S;
+    const int F0 = bt * 16, G0 = br * 8;
+    const int nks = a.nks;
+    const int ks0 = (int)((long long)sp * nks / a.S), n_it = (int)((long long)(sp + 1) * nks / a.S) - ks0;
+
+    // this wave's share of a stage: units 4 wave .. 4 wave + 3 (waves 0..3 weights, 4..7 activations)
+    __amdgpu_buffer_rsrc_t rs[4];
+    int uoff[4];
+    const int ustride = wave < 4 ? 1024 : 2048;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (wave < 4) {
+            const int tile = F0 + 4 * wave + j;
+            const bool have = tile < a.n_tiles;
+            rs[j] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(a.Wp + (size_t)(have ? tile : 0) * nks * 64), 0,
+                                                      have ? nks * 1024 : 0, 0x00020000);
+            uoff[j] = 0;
+        } else {
+            const int n_g = a.G - G0 < 8 ? a.G - G0 : 8;
+            const int u = 4 * (wave - 4) + j;   // (row group, hi | lo)
+            rs[j] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(a.Xq + (size_t)G0 * nks * 128), 0, n_g * nks * 2048,
+                                                      0x00020000);
+            uoff[j] = ((u >> 1) * nks * 2 + (u & 1)) * 1024;
+        }
+    }
+    auto request = [&](int it) {
+        uint4 *dst = ring + ((size_t)(it & (kPgStages - 1)) * kPgUnits + 4 * wave) * 64;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs[j], (__attribute__((address_space(3))) void *)(dst + j * 64), 16,
+                                                     uoff[j] + (ks0 + it) * ustride + lane * 16, 0, 0, 0);
+    };
+
     f32x4 acc[kPfTN][kPfTM];
 #pragma unroll
     for (int t = 0; t < kPfTN; ++t)
 #pragma unroll
         for (int g = 0; g < kPfTM; ++g) acc[t][g] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)ring;
 
-    uint4 wA[kPfTN], xA[kPfTM][2], wB[kPfTN], xB[kPfTM][2];
-    auto load = [&](uint4 (&w)[kPfTN], uint4 (&x)[kPfTM][2], int ks) {
+    // The fragment reads are written as assembly: reads the compiler can see would make it wait for
+    // every outstanding load into LDS first (it cannot tell the ring's stages apart), and the ring
+    // exists to keep three stages in flight.
+    auto read_stage = [&](u32x4_t (&w)[kPfTN], u32x4_t (&xh)[kPfTM], u32x4_t (&xl)[kPfTM], int it) {
+        const uint32_t sbase = lds_base + (uint32_t)(it & (kPgStages - 1)) * (kPgUnits * 1024) + (uint32_t)lane * 16;
+        const uint32_t aw = sbase + (uint32_t)(4 * wf) * 1024, ax = sbase + (uint32_t)(16 + 8 * wr) * 1024;
+        w[0] = lds_read16<0>(aw); w[1] = lds_read16<1024>(aw); w[2] = lds_read16<2048>(aw); w[3] = lds_read16<3072>(aw);
+        xh[0] = lds_read16<0>(ax); xh[1] = lds_read16<2048>(ax); xh[2] = lds_read16<4096>(ax); xh[3] = lds_read16<6144>(ax);
+        xl[0] = lds_read16<1024>(ax); xl[1] = lds_read16<3072>(ax); xl[2] = lds_read16<5120>(ax); xl[3] = lds_read16<7168>(ax);
+    };
+    auto wait_reads = [&](u32x4_t (&w)[kPfTN], u32x4_t (&xh)[kPfTM], u32x4_t (&xl)[kPfTM]) {
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]), "+v"(xh[0]), "+v"(xh[1]), "+v"(xh[2]), "+v"(xh[3]),
+                       "+v"(xl[0]), "+v"(xl[1]), "+v"(xl[2]), "+v"(xl[3]));
+    };
+    auto mma = [&](const u32x4_t (&w)[kPfTN], const u32x4_t (&xh)[kPfTM], const u32x4_t (&xl)[kPfTM]) {
 #pragma unroll
-        for (int t = 0; t < kPfTN; ++t) {
-            u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rw[t], (ks * 64 + lane) * 16, 0, 0);
-            w[t] = make_uint4(v.x, v.y, v.z, v.w);
+        for (int t = 0; t < kPfTN; ++t)
+#pragma unroll
+            for (int g = 0; g < kPfTM; ++g)
+                acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[t]), __builtin_bit_cast(bf16x8, xh[g]),
+                                                                    acc[t][g], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < kPfTN; ++t)
+#pragma unroll
+            for (int g = 0; g < kPfTM; ++g)
+                acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[t]), __builtin_bit_cast(bf16x8, xl[g]),
+                                                                    acc[t][g], 0, 0, 0);
+    };
+    // Stage s is published by a block barrier that every wave reaches after its own loads of that
+    // stage have landed (at most the two younger stages still outstanding) and its own reads of
+    // stage s - 1 have returned; that barrier also frees the slot of stage s - 1 for stage s + 3.
+    auto publish = [&](int s) {
+        if (s + 2 < n_it) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("s_barrier" ::: "memory");
+        if (s + kPgLead < n_it) request(s + kPgLead);
+    };
+    u32x4_t wA[kPfTN], hA[kPfTM], lA[kPfTM], wB[kPfTN], hB[kPfTM], lB[kPfTM];
+#pragma unroll
+    for (int s = 0; s < kPgLead; ++s)
+        if (s < n_it) request(s);
+    if (n_it > 0) {
+        publish(0);
+        read_stage(wA, hA, lA, 0);
+    }
+    // the reads of the next stage are in flight during the MFMAs of this one
+    for (int it = 0; it < n_it; it += 2) {
+        wait_reads(wA, hA, lA);
+        if (it + 1 < n_it) {
+            publish(it + 1);
+            read_stage(wB, hB, lB, it + 1);
         }
-#pragma unroll
-        for (int g = 0; g < kPfTM; ++g)
-#pragma unroll
-            for (int hl = 0; hl < 2; ++hl) {
-                u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rx, (((g * nks + ks) * 2 + hl) * 64 + lane) * 16, 0, 0);
-                x[g][hl] = make_uint4(v.x, v.y, v.z, v.w);
+        mma(wA, hA, lA);
+        if (it + 1 < n_it) {
+            wait_reads(wB, hB, lB);
+            if (it + 2 < n_it) {
+                publish(it + 2);
+                read_stage(wA, hA, lA, it + 2);
             }
-    };
-    auto mma = [&](const uint4 (&w)[kPfTN], const uint4 (&x)[kPfTM][2]) {
-#pragma unroll
-        for (int hl = 0; hl < 2; ++hl)
-#pragma unroll
-            for (int t = 0; t < kPfTN; ++t)
-#pragma unroll
-                for (int g = 0; g < kPfTM; ++g)
-                    acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[t]),
-                                                                        __builtin_bit_cast(bf16x8, x[g][hl]), acc[t][g], 0, 0, 0);
-    };
-    load(wA, xA, 0);
-    for (int ks = 0; ks < nks; ks += 2) {
-        if (ks + 1 < nks) load(wB, xB, ks + 1);
-        mma(wA, xA);
-        if (ks + 2 < nks) load(wA, xA, ks + 2);
-        if (ks + 1 < nks) mma(wB, xB);
+            mma(wB, hB, lB);
+        }
     }
 
     const int slot = lane & 15, kg = lane >> 4;
     const int r0 = a.L & 15;
+    const int f0 = F0 + 4 * wf, g0 = G0 + 4 * wr;
 #pragma unroll
     for (int t = 0; t < kPfTN; ++t) {
         if (f0 + t >= a.n_tiles) break;   // wave-uniform
@@ -271,7 +360,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_gemm_kernel(PrefillArgs
         for (int g = 0; g < kPfTM; ++g) {
             const int m = (g0 + g) * 16 + slot;
             const bool valid = g0 + g < a.G && m >= r0 && m < r0 + a.P;
-            prefill_epilogue<EPI>(a, f0 + t, m, kg, acc[t][g], valid);
+            prefill_epilogue<EPI>(a, f0 + t, m, kg, acc[t][g], valid, sp);
         }
     }
 }
@@ -381,12 +470,14 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const uint4 *__restri
 
 // ---------------------------------------------------- hand-over to the step
 //
-// The last prompt row is the only one whose logits are needed.  Leaves it
-// where the step's LM-head GEMM expects its input (class-8 packed operand of
-// x * gain in row 0, per-tile sums of squares) and sets the cache length to
-// just below the row, so that the step's own argmax kernel, run for one
-// appended row, finishes the job.   grid: d / 16 blocks of one wave.
-__global__ __launch_bounds__(64) void prefill_last_kernel(const float *__restrict__ x_row, const bf16_t *__restrict__ gain,
+// The last prompt row is the only one whose logits are needed.  Adds the last
+// down projection's partial products to it and leaves it where the step's
+// LM-head GEMM expects its input (class-8 packed operand of x * gain in row 0,
+// per-tile sums of squares); sets the cache length to just below the row, so
+// that the step's own argmax kernel, run for one appended row, finishes the
+// job.   grid: d / 16 blocks of one wave.
+__global__ __launch_bounds__(64) void prefill_last_kernel(const float *__restrict__ x_row, const float *__restrict__ part_row,
+                                                           int S, size_t part_stride, const bf16_t *__restrict__ gain,
                                                            bf16_t *__restrict__ xp, float *__restrict__ ssp,
                                                            int32_t *__restrict__ len_ptr, int len_before_row)
 {
@@ -395,6 +486,7 @@ __global__ __launch_bounds__(64) void prefill_last_kernel(const float *__restric
     f32x4 v = {0.f, 0.f, 0.f, 0.f};
     if (slot == 0) {
         v = *reinterpret_cast<const f32x4 *>(x_row + n);
+        for (int s = 0; s < S; ++s) v += *reinterpret_cast<const f32x4 *>(part_row + (size_t)s * part_stride + n);
         xp_store4<false>(xp, 8, 0, n, v * widen4(*reinterpret_cast<const uint2 *>(gain + n)));
     }
     float s = fmaf(v[3], v[3], fmaf(v[2], v[2], fmaf(v[1], v[1], v[0] * v[0])));

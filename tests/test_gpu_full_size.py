@@ -136,3 +136,57 @@ def test_long_paged_context_and_adaptive_draft_length():
     res = B.anpd_generate(model, kv, table, prompt, 16, 96, adaptive=True)
     assert res["tokens"] == ref_tokens
     assert res["n_steps"] <= 96
+
+
+def test_llama7b_prompt_in_one_pass():
+    """anpd_prefill at the 7B shape.  (a) 48 rows appended behind 500 seeded positions (the piece
+    starts in the middle of a cache page): last-row logits and the K / V rows of the last layer
+    against the oracle.  (b) The benchmark's 512-token prompt in the launch configuration bench.py
+    times: the oracle cannot follow at that size, so the check is agreement with the same prompt
+    appended through the verification step in 32-row windows, a path the oracle covers above."""
+    shape = synth.LLAMA_7B
+    L, P = 500, 48
+    w = synth.make_weights(shape, 2, device="cuda")
+    model = B.Model(shape, w, max_window=32, max_positions=640)
+    kv, kv_w = B.KVCache(model, 640), B.KVCache(model, 640)
+    w_host = {k_: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k_, v in w.items()}
+    dec = od.Decoder(shape, w_host, 640)
+    _seed_both(shape, dec, [kv], L, seed=7)
+    tokens = synth.random_tokens(shape.vocab, P, 17)
+    ref = dec.forward(tokens)
+    buf = torch.empty(shape.vocab, dtype=torch.float32, device="cuda")
+    nxt = B.prefill(model, kv, tokens, out_logits=buf)
+    assert kv.length == L + P
+    err = float(np.max(np.abs(buf.cpu().numpy().astype(np.float64) - ref[-1])))
+    print("7B prompt piece: max |logit error| of the last row = %.2e" % err)
+    assert err < TOL["bf16"]
+    if top2_gap(ref[-1]) > TOL["bf16"]:
+        assert nxt == od.argmax(ref[-1])
+    dec.set_length(L + P)
+    k_gpu, v_gpu = kv.read(shape.n_layers - 1, L, P)
+    k_ref, v_ref = dec.kv_read(shape.n_layers - 1, L, P)
+    for got, want in ((k_gpu.cpu().numpy().astype(np.float64), k_ref), (v_gpu.cpu().numpy().astype(np.float64), v_ref)):
+        assert float(np.max(np.abs(got - want) - 2.0 ** -7 * np.abs(want))) < 5e-3
+        assert np.mean(got == want) > 0.7
+    del dec
+
+    prompt = synth.workload_prompt("llama7b")
+    kv.truncate(0)
+    one = torch.empty(shape.vocab, dtype=torch.float32, device="cuda")
+    n_one = B.prefill(model, kv, prompt, out_logits=one)
+    B.prefill_windows(model, kv_w, prompt[:-1])
+    win = torch.empty(1, shape.vocab, dtype=torch.float32, device="cuda")
+    _, n_win = B.verify(model, kv_w, prompt[-1:], B.APPEND, out_logits=win)
+    assert kv.length == kv_w.length == len(prompt)
+    diff = float((one - win[0]).abs().max())
+    print("7B prompt of %d rows: one pass vs windows, max |logit difference| = %.2e" % (len(prompt), diff))
+    assert diff < TOL["bf16"]
+    srt = torch.sort(win[0], descending=True).values
+    if float(srt[0] - srt[1]) > TOL["bf16"]:
+        assert n_one == n_win
+    for layer in (0, shape.n_layers - 1):
+        ka, va = kv.read(layer, 0, len(prompt))
+        kb, vb = kv_w.read(layer, 0, len(prompt))
+        # two bf16 roundings of values that carry the rounding noise of up to 32 layers
+        assert float((ka - kb).abs().max()) < 0.05 and float((va - vb).abs().max()) < 0.05
+        assert float((ka - kb).abs().mean()) < 2e-3 and float((va - vb).abs().mean()) < 2e-3
