@@ -211,7 +211,7 @@ int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32
  *   *out_next = argmax of the last row's logits (lowest index among equal maxima).
  *   out_logits (nullable, DEVICE, vocab floats): the last row's logits.
  *   workspace: DEVICE, 256-byte aligned, >= anpd_prefill_workspace_bytes(m, n_tokens) bytes,
- *   used only during the call (about 110 KB per token at the 7B shape).  Models on the
+ *   used only during the call (about 175 KB per token at the 7B shape).  Models on the
  *   dot-product path (f32 weights) process the prompt in windows of max_window rows and need no
  *   workspace: the size is 0 and workspace may be NULL.
  * Blocks until the result is on the host.
