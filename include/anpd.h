@@ -100,6 +100,19 @@ int32_t anpd_ngram_query(const anpd_ngram_t *t, const int32_t *tail, int32_t tai
 int32_t anpd_ngram_propose(const anpd_ngram_t *t, int32_t max_k, int32_t *out_tokens,
                            int32_t *out_levels);
 
+/* Drafting for multi-candidate verification (see anpd_verify_tree): up to n_cand candidate
+ * continuations of the committed context, as a tree whose root is the last accepted token.
+ * Candidate first tokens: the levels are walked from n_max downwards; within a level the followers
+ * of the context come most frequent first (most recent first among equally frequent); distinct
+ * tokens only, until n_cand are found.  The first one is therefore the ordinary multi-level answer.
+ * Each candidate is then continued by the drafting loop of Algorithm 1 to at most max_k tokens.
+ * Candidates are written one after the other until max_drafts rows are used up.
+ *   out_tokens, out_parents (host, max_drafts ints): draft i is window row i + 1;
+ *   out_parents[i] = window row it continues (0 = the root).  out_levels: nullable.
+ * Returns the number of drafts written; n_cand = 1 gives exactly anpd_ngram_propose's chain. */
+int32_t anpd_ngram_propose_tree(const anpd_ngram_t *t, int32_t max_k, int32_t n_cand, int32_t max_drafts,
+                                int32_t *out_tokens, int32_t *out_parents, int32_t *out_levels);
+
 /* ------------------------------------------------------------------------
  * Device side: the verification step.
  *
@@ -195,6 +208,28 @@ int32_t anpd_kv_read(const anpd_kv_t *kv, int32_t layer, int32_t pos0, int32_t n
 int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32_t n_window,
                     int32_t mode, int32_t *out_accepted, int32_t *out_next, int32_t *out_predicts,
                     float *out_logits, void *stream);
+
+/* Multi-candidate verification: several candidate drafts scored in ONE forward.
+ *
+ * Paper, Section 5, "Future Works", item 2 (more than one candidate in the LLM's verification
+ * pass); the accept rule is Algorithm 1's, applied along every root-to-leaf path.
+ *   window (host): window[0] = last accepted token; window[r], r >= 1, is a draft that continues
+ *   window row parent[r] (parent[0] = -1, 0 <= parent[r] < r): the window is a tree.
+ *   Row r stands at position length + depth(r) and attends to the cache and to its own ancestors
+ *   only, so its logits are what the linear window [root .. r] would give at its last row.
+ *   Row r >= 1 is accepted iff its parent is accepted and window[r] == argmax(logits[parent[r]]).
+ *   The deepest accepted row wins (lowest index among equally deep): *out_accepted = its depth a,
+ *   *out_next = argmax of its logits, out_path (nullable, host, a + 1 ints) = the window rows
+ *   root .. winner.  Their K and V end up in cache positions length .. length + a, everything else
+ *   is rolled back: length += 1 + a.
+ *   out_predicts / out_logits: as in anpd_verify, by window row.
+ * A chain (parent[r] = r - 1) gives bit for bit the result of anpd_verify.  Other shapes give every
+ * row the same keys in different cache slots: the same sums in another order, equal to rounding.
+ * Runs as one launch per operation (the one-kernel step takes chains only).
+ * Errors: as anpd_verify; ANPD_E_INVAL for a parent that is not an earlier row. */
+int32_t anpd_verify_tree(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, const int32_t *parent,
+                         int32_t n_window, int32_t *out_accepted, int32_t *out_next, int32_t *out_path,
+                         int32_t *out_predicts, float *out_logits, void *stream);
 
 /* Prompt processing.
  *

@@ -1,5 +1,5 @@
 """Ablations of the drafting module on synthetic streams (paper, Section 4.3: draft size K at N = 2,
-the N x K grid, multi-level against single-level N-gram), host only.
+the N x K grid, multi-level against single-level N-gram; Section 5: several candidates per step), host only.
 
 A seeded copy-heavy stream stands for a model whose output re-uses spans of its context: the first
 `prompt` tokens initialise the table, the rest is what the LLM would decode greedily.  Algorithm 1
@@ -51,6 +51,41 @@ def run_stream(stream: Sequence[int], prompt_len: int, n_min: int, n_max: int, K
             "mean_draft": proposed / steps if steps else 0.0,
             "tokens_per_step": tokens / steps if steps else 0.0,
             "windows": windows}
+
+
+def run_stream_multi(stream: Sequence[int], prompt_len: int, n_min: int, n_max: int, K: int, n_cand: int, vocab: int,
+                     max_drafts: int = 31, max_tokens: Optional[int] = None) -> Dict[str, float]:
+    """run_stream with up to n_cand candidate drafts per step (anpd_ngram_propose_tree), verified together:
+    the deepest candidate prefix that follows the stream is kept."""
+    table = B.NgramTable(n_min, n_max, vocab)
+    table.update(list(stream[:prompt_len]))
+    end = len(stream) if max_tokens is None else min(len(stream), prompt_len + max_tokens)
+    pos = prompt_len
+    steps = proposed = accepted = 0
+    windows: Dict[int, int] = {}
+    while pos < end:
+        table.update([stream[pos]])
+        toks, pars, _ = table.propose_tree(K, n_cand, max_drafts)
+        depth, ok, best = [0], [True], 0
+        for i, (tok, par) in enumerate(zip(toks, pars)):
+            d = depth[par] + 1
+            depth.append(d)
+            ok.append(ok[par] and pos + d < end and tok == stream[pos + d])
+            if ok[-1] and d > depth[best]:
+                best = i + 1
+        a = depth[best]
+        if a:
+            table.update(list(stream[pos + 1:pos + 1 + a]))
+        steps += 1
+        proposed += len(toks)
+        accepted += a
+        windows[1 + len(toks)] = windows.get(1 + len(toks), 0) + 1
+        pos += 1 + a
+    table.close()
+    tokens = pos - prompt_len
+    return {"steps": steps, "tokens": tokens, "proposed": proposed, "accepted": accepted,
+            "mean_rows": 1 + proposed / steps if steps else 0.0,
+            "tokens_per_step": tokens / steps if steps else 0.0, "windows": windows}
 
 
 def speedup_with_times(res: Dict[str, float], ms_by_rows: Dict[int, float]) -> float:
@@ -106,6 +141,13 @@ def main(argv: Optional[List[str]] = None) -> int:
     print("-- single level N only (no fallback to shorter contexts), K = 7")
     for N in (2, 3, 4, 5, 6, 7, 8):
         row("single N=%d" % N, N, N, 7)
+    print("-- candidates per step, verified together (Section 5, future work 2), levels 2..5")
+    for K, budget in ((3, 7), (5, 15), (7, 31)):
+        for n_cand in (1, 2, 3, 4):
+            r = run_stream_multi(stream, P, 2, 5, K, n_cand, vocab, budget)
+            extra = "  speed-up at measured step times %.2f" % speedup_with_times(r, times) if times else ""
+            print("K=%d, %d candidate(s), at most %2d drafts: mean rows %.2f  tokens/step %.2f%s" % (
+                K, n_cand, budget, r["mean_rows"], r["tokens_per_step"], extra))
     return 0
 
 

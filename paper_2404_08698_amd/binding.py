@@ -26,11 +26,11 @@ _PER_LAYER = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up",
 EXPORTS = (
     "anpd_last_error",
     "anpd_ngram_create", "anpd_ngram_destroy", "anpd_ngram_reset", "anpd_ngram_update",
-    "anpd_ngram_length", "anpd_ngram_query", "anpd_ngram_propose",
+    "anpd_ngram_length", "anpd_ngram_query", "anpd_ngram_propose", "anpd_ngram_propose_tree",
     "anpd_model_workspace_bytes", "anpd_model_create", "anpd_model_destroy",
     "anpd_kv_pool_bytes", "anpd_kv_create", "anpd_kv_destroy", "anpd_kv_length", "anpd_kv_truncate",
     "anpd_kv_set_page_order", "anpd_kv_num_pages", "anpd_kv_write", "anpd_kv_read",
-    "anpd_verify", "anpd_prefill_workspace_bytes", "anpd_prefill", "anpd_linear_workspace_bytes", "anpd_linear",
+    "anpd_verify", "anpd_verify_tree", "anpd_prefill_workspace_bytes", "anpd_prefill", "anpd_linear_workspace_bytes", "anpd_linear",
     "anpd_model_profile", "anpd_model_profile_read", "anpd_packed_bytes", "anpd_pack_weights",
     "anpd_model_trace", "anpd_model_set_barrier_spin_limit",
 )
@@ -85,6 +85,8 @@ def lib():
     L.anpd_ngram_query.argtypes = [vp, i32p, C.c_int32, i32p, i32p]
     L.anpd_ngram_propose.restype = C.c_int32
     L.anpd_ngram_propose.argtypes = [vp, C.c_int32, i32p, i32p]
+    L.anpd_ngram_propose_tree.restype = C.c_int32
+    L.anpd_ngram_propose_tree.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, i32p, i32p, i32p]
     L.anpd_model_workspace_bytes.restype = C.c_size_t
     L.anpd_model_workspace_bytes.argtypes = [C.POINTER(ModelCfg)]
     L.anpd_model_create.restype = C.c_int32
@@ -111,6 +113,8 @@ def lib():
     L.anpd_kv_read.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp, vp, vp]
     L.anpd_verify.restype = C.c_int32
     L.anpd_verify.argtypes = [vp, vp, i32p, C.c_int32, C.c_int32, i32p, i32p, i32p, vp, vp]
+    L.anpd_verify_tree.restype = C.c_int32
+    L.anpd_verify_tree.argtypes = [vp, vp, i32p, i32p, C.c_int32, i32p, i32p, i32p, i32p, vp, vp]
     L.anpd_prefill_workspace_bytes.restype = C.c_size_t
     L.anpd_prefill_workspace_bytes.argtypes = [vp, C.c_int32]
     L.anpd_prefill.restype = C.c_int32
@@ -196,6 +200,17 @@ class NgramTable:
 
 
 # ------------------------------------------------------------- device side
+
+def _propose_tree(self, max_k: int, n_cand: int, max_drafts: int):
+    """anpd_ngram_propose_tree: (tokens, parents, levels) of the drafts; draft i is window row i + 1."""
+    n = max(1, max_drafts)
+    toks, pars, lvls = (C.c_int32 * n)(), (C.c_int32 * n)(), (C.c_int32 * n)()
+    k = _check(lib().anpd_ngram_propose_tree(self._h, max_k, n_cand, max_drafts, toks, pars, lvls))
+    return list(toks[:k]), list(pars[:k]), list(lvls[:k])
+
+
+NgramTable.propose_tree = _propose_tree
+
 
 def _stream_ptr(stream) -> int:
     import torch
@@ -364,6 +379,27 @@ def verify(model: Model, kv: KVCache, window: Sequence[int], mode: int = VERIFY,
     return acc.value, nxt.value
 
 
+def verify_tree(model: Model, kv: KVCache, window: Sequence[int], parent: Sequence[int], want_predicts: bool = False,
+                out_logits=None, stream=None):
+    """anpd_verify_tree.  Returns (accepted depth, next token, path rows) or with the per-row predictions appended."""
+    n = len(window)
+    assert len(parent) == n
+    acc, nxt = C.c_int32(0), C.c_int32(0)
+    path = (C.c_int32 * (n + 1))()
+    preds = (C.c_int32 * max(1, n))() if want_predicts else None
+    lp = 0
+    if out_logits is not None:
+        import torch
+        assert out_logits.is_cuda and out_logits.dtype == torch.float32 and out_logits.is_contiguous()
+        assert out_logits.numel() >= n * model.vocab
+        lp = out_logits.data_ptr()
+    _check(lib().anpd_verify_tree(model._h, kv._h, _ints(window), _ints(parent), n, C.byref(acc), C.byref(nxt), path, preds, lp,
+                                  _stream_ptr(stream)))
+    if want_predicts:
+        return acc.value, nxt.value, list(path[:acc.value + 1]), list(preds[:n])
+    return acc.value, nxt.value, list(path[:acc.value + 1])
+
+
 def pack_weights(W, stream=None):
     """anpd_pack_weights: bf16 CUDA [N][K] -> fragment-order buffer (uint8 tensor)."""
     import torch
@@ -455,6 +491,33 @@ def adaptive_draft_length(levels: Sequence[int], k_max: int) -> int:
     if not levels:
         return 0
     return max(1, min(k_max, 1 << (levels[0] - 2)))
+
+
+def anpd_generate_multi(model: Model, kv: KVCache, table: NgramTable, prompt: Sequence[int], K: int, n_cand: int,
+                        n_tokens: int, stream=None) -> Dict[str, object]:
+    """Algorithm 1 with multi-candidate verification: every step drafts up to n_cand candidate
+    continuations (NgramTable.propose_tree), scores them in one forward (verify_tree) and keeps the
+    longest accepted one."""
+    table.reset()
+    table.update(prompt)
+    c = prefill(model, kv, prompt, stream)
+    out: List[int] = []
+    steps = proposed = accepted = rows = 0
+    while len(out) < n_tokens:
+        table.update([c])
+        out.append(c)
+        toks, pars, _ = table.propose_tree(K, n_cand, model.max_window - 1)
+        a, nxt, path = verify_tree(model, kv, [c] + toks, [-1] + pars, stream=stream)
+        kept = [toks[r - 1] for r in path[1:]]
+        if kept:
+            table.update(kept)
+            out.extend(kept)
+        steps += 1
+        proposed += len(toks)
+        rows += 1 + len(toks)
+        accepted += a
+        c = nxt
+    return {"tokens": out[:n_tokens], "n_steps": steps, "proposed": proposed, "accepted": accepted, "rows": rows}
 
 
 def anpd_generate(model: Model, kv: KVCache, table: NgramTable, prompt: Sequence[int], K: int, n_tokens: int,

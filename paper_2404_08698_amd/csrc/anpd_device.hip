@@ -32,7 +32,7 @@ namespace {
 size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 struct Layout {  // byte offsets into the model workspace
-    size_t rope_tab, tok, result, counter, x, h, y, qkv, att, gu, a, logits, part;
+    size_t rope_tab, tok, tree, result, counter, x, h, y, qkv, att, gu, a, logits, part;
     // fast path: packed operands, partial sums of squares, packed weights
     size_t xp_d, xp_att, xp_f, ssp_a, ssp_b, qp, head_ctr, layer_tab, amax, row_ctr, bar, wp_lm, total;
     std::vector<size_t> wp_qkv, wp_o, wp_gu, wp_down;
@@ -80,7 +80,8 @@ Layout make_layout(const anpd_model_cfg *c)
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
     L.rope_tab = take((size_t)c->max_positions * (c->head_dim / 2) * sizeof(float2));
     L.tok = take(ANPD_MAX_WINDOW * sizeof(int32_t));
-    L.result = take((2 + ANPD_MAX_WINDOW) * sizeof(int32_t));
+    L.tree = take(3 * ANPD_MAX_WINDOW * sizeof(int32_t));                 // draft tree: parent, depth, visibility mask
+    L.result = take((2 + ANPD_MAX_WINDOW + ANPD_MAX_WINDOW + 1) * sizeof(int32_t));   // accepted, next, predictions, accepted path
     L.counter = take(sizeof(uint32_t));
     L.x = take(MW * d * 4);
     L.h = take(MW * d * 4);
@@ -157,7 +158,8 @@ struct anpd_model {
     uint32_t ready_epoch;  // QKV phases run by the one-kernel step so far
     const void *embed, *final_norm, *lm_head;
     std::vector<const void *> attn_norm, wq, wk, wv, wo, ffn_norm, w_gate, w_up, w_down;
-    int32_t *pin;  // pinned host staging: [0..32) window, [32..66) result, [100] error flag of the persistent kernel
+    int32_t *pin;  // pinned host staging: [0..32) window, [32..99) result and accepted path, [100] error flag of the
+                   // persistent kernel, [128..224) draft tree (parent, depth, mask)
     int32_t *pin_dev;  // the same memory as the device addresses it
     // optional per-kernel timing with events on the launch stream
     bool prof;
@@ -335,8 +337,9 @@ void collect_marks(anpd_model *m)
     m->prof_steps += 1;
 }
 
+// tree: the window is a draft tree whose parent / depth / mask arrays are in the workspace
 template <typename KT>
-int32_t run_step_generic(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t st)
+int32_t run_step_generic(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t st, bool tree = false)
 {
     const anpd_model_cfg &c = m->cfg;
     const Layout &L = m->lay;
@@ -352,6 +355,8 @@ int32_t run_step_generic(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_
     KT *pool = (KT *)kv->pool;
     const float scale = 1.0f / sqrtf((float)dh);
     const int n_splits = (kv->len + M + kAttnSplit - 1) / kAttnSplit;
+    const int32_t *t_parent = (const int32_t *)(ws + L.tree), *t_depth = tree ? t_parent + ANPD_MAX_WINDOW : nullptr;
+    const uint32_t *t_mask = tree ? (const uint32_t *)(t_parent + 2 * ANPD_MAX_WINDOW) : nullptr;
     int32_t rc;
 
     m->ev_used = 0;
@@ -364,16 +369,16 @@ int32_t run_step_generic(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_
         if ((rc = launch_gemm_dot(h, M, d, m->wq[l], m->wk[l], m->wv[l], 3, d, qkv, 3 * d, c.dtype, st)) != ANPD_OK) return rc;
         mark(m, ANPD_PROF_GEMM_QKV, st);
         hipLaunchKernelGGL((rope_kv_kernel<KT>), dim3(M), dim3(256), 0, st, qkv, rope, pool, kv->d_table, kv->d_len, l,
-                           c.n_layers, H, dh, c.page_tokens);
+                           c.n_layers, H, dh, c.page_tokens, t_depth);
         mark(m, ANPD_PROF_OTHER, st);
         if (dh == 128) {
             hipLaunchKernelGGL((attn_kernel<KT, 128>), dim3(H, n_splits), dim3(256), 0, st, qkv, 3 * d, pool, kv->d_table,
-                               kv->d_len, M, l, c.n_layers, H, c.page_tokens, c.max_window, L.max_splits, scale, part);
+                               kv->d_len, M, l, c.n_layers, H, c.page_tokens, c.max_window, L.max_splits, scale, part, t_mask);
             hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(M, H), dim3(128), 0, st, part, kv->d_len, H,
                                c.max_window, L.max_splits, att, (bf16_t *)nullptr, 8);
         } else {
             hipLaunchKernelGGL((attn_kernel<KT, 64>), dim3(H, n_splits), dim3(256), 0, st, qkv, 3 * d, pool, kv->d_table,
-                               kv->d_len, M, l, c.n_layers, H, c.page_tokens, c.max_window, L.max_splits, scale, part);
+                               kv->d_len, M, l, c.n_layers, H, c.page_tokens, c.max_window, L.max_splits, scale, part, t_mask);
             hipLaunchKernelGGL((attn_combine_kernel<64>), dim3(M, H), dim3(64), 0, st, part, kv->d_len, H, c.max_window,
                                L.max_splits, att, (bf16_t *)nullptr, 8);
         }
@@ -397,6 +402,11 @@ int32_t run_step_generic(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_
     mark(m, ANPD_PROF_GEMM_LM_HEAD, st);
     hipLaunchKernelGGL(argmax_accept_kernel, dim3(M), dim3(1024), 0, st, logits, V, M, tok, mode, result, kv->d_len,
                        counter);
+    if (tree) {
+        hipLaunchKernelGGL(accept_tree_kernel, dim3(1), dim3(64), 0, st, tok, t_parent, t_depth, M, result, kv->d_len, kv->len);
+        hipLaunchKernelGGL((kv_compact_kernel<KT>), dim3((unsigned)(c.n_layers * 2 * H)), dim3(128), 0, st, pool, kv->d_table,
+                           (const int32_t *)result, kv->len, c.n_layers, H, dh, c.page_tokens);
+    }
     mark(m, ANPD_PROF_OTHER, st);
     HIP_TRY(hipGetLastError());
     return ANPD_OK;
@@ -404,7 +414,7 @@ int32_t run_step_generic(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_
 
 // The fused bf16 step: per layer QKV(+norm, RoPE, cache write) -> attention -> combine -> O(+residual)
 // -> gate/up(+norm, SwiGLU) -> down(+residual); then LM head(+norm) -> argmax / accept.
-int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t st)
+int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t st, bool tree = false)
 {
     const anpd_model_cfg &c = m->cfg;
     const Layout &L = m->lay;
@@ -423,6 +433,8 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
     const float scale = 1.0f / sqrtf((float)dh);
     const int n_splits = (kv->len + M + kFastSplit - 1) / kFastSplit;
     const int nks_d = (d + 31) / 32, nks_f = (F + 31) / 32;
+    const int32_t *t_parent = (const int32_t *)(ws + L.tree), *t_depth = t_parent + ANPD_MAX_WINDOW;
+    const uint32_t *t_mask = (const uint32_t *)(t_parent + 2 * ANPD_MAX_WINDOW);
     int32_t rc;
 
     FastArgs base;
@@ -462,17 +474,18 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
             a.ssp = ssp_a;
             a.qp = qp;
             a.layer = l;
-            if ((rc = launch_fast<EPI_QKV>(a, m->n_cu, false, st)) != ANPD_OK) return rc;
+            a.depth = t_depth;
+            rc = tree ? launch_fast<EPI_QKV_TREE>(a, m->n_cu, false, st) : launch_fast<EPI_QKV>(a, m->n_cu, false, st);
+            if (rc != ANPD_OK) return rc;
         }
         mark(m, ANPD_PROF_GEMM_QKV, st);
-        if (dh == 128)
-            hipLaunchKernelGGL((attn_fast_kernel<128>), dim3(H, n_splits), dim3(kFastThreads), 0, st, (const uint4 *)qp,
-                               (const bf16_t *)kv->pool, kv->d_table, kv->d_len, M, l, c.n_layers, H, L.max_splits, scale, part,
-                               head_ctr, xp_att, cls);
-        else
-            hipLaunchKernelGGL((attn_fast_kernel<64>), dim3(H, n_splits), dim3(kFastThreads), 0, st, (const uint4 *)qp,
-                               (const bf16_t *)kv->pool, kv->d_table, kv->d_len, M, l, c.n_layers, H, L.max_splits, scale, part,
-                               head_ctr, xp_att, cls);
+#define ANPD_ATTN(DH_, TREE_)                                                                                              \
+    hipLaunchKernelGGL((attn_fast_kernel<DH_, TREE_>), dim3(H, n_splits), dim3(kFastThreads), 0, st, (const uint4 *)qp,  \
+                       (const bf16_t *)kv->pool, kv->d_table, kv->d_len, M, l, c.n_layers, H, L.max_splits, scale, part,   \
+                       head_ctr, xp_att, cls, t_mask)
+        if (dh == 128) { if (tree) ANPD_ATTN(128, true); else ANPD_ATTN(128, false); }
+        else { if (tree) ANPD_ATTN(64, true); else ANPD_ATTN(64, false); }
+#undef ANPD_ATTN
         mark(m, ANPD_PROF_ATTN, st);
         {
             FastArgs a = base;
@@ -524,6 +537,11 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
     mark(m, ANPD_PROF_GEMM_LM_HEAD, st);
     hipLaunchKernelGGL(argmax_accept_kernel, dim3(M), dim3(1024), 0, st, logits, V, M, tok, mode, result, kv->d_len,
                        counter);
+    if (tree) {
+        hipLaunchKernelGGL(accept_tree_kernel, dim3(1), dim3(64), 0, st, tok, t_parent, t_depth, M, result, kv->d_len, kv->len);
+        hipLaunchKernelGGL(kvf_compact_kernel, dim3((unsigned)(c.n_layers * 2 * H)), dim3(128), 0, st, (bf16_t *)kv->pool,
+                           kv->d_table, (const int32_t *)result, kv->len, c.n_layers, H, dh);
+    }
     mark(m, ANPD_PROF_OTHER, st);
     HIP_TRY(hipGetLastError());
     return ANPD_OK;
@@ -807,9 +825,9 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
             tab[(size_t)p * half + i] = make_float2((float)std::cos(ang), (float)std::sin(ang));
         }
     }
-    hipError_t e = hipHostMalloc((void **)&m->pin, 128 * sizeof(int32_t), hipHostMallocDefault);
+    hipError_t e = hipHostMalloc((void **)&m->pin, 256 * sizeof(int32_t), hipHostMallocDefault);
     if (e != hipSuccess) { delete m; return fail(ANPD_E_HIP, "hipHostMalloc: %s", hipGetErrorString(e)); }
-    std::memset(m->pin, 0, 128 * sizeof(int32_t));
+    std::memset(m->pin, 0, 256 * sizeof(int32_t));
     e = hipHostGetDevicePointer((void **)&m->pin_dev, m->pin, 0);
     if (e != hipSuccess) { (void)hipHostFree(m->pin); delete m; return fail(ANPD_E_HIP, "hipHostGetDevicePointer: %s", hipGetErrorString(e)); }
     e = hipMemsetAsync(m->ws, 0, m->mfma ? lay.wp_lm : lay.total, st);
@@ -1106,6 +1124,61 @@ int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32
     *out_accepted = res[0];
     *out_next = res[1];
     if (out_predicts) std::memcpy(out_predicts, res + 2, sizeof(int32_t) * (size_t)n_window);
+    kv->len += 1 + res[0];
+    release_pages(kv, kv->len);
+    return ANPD_OK;
+}
+
+int32_t anpd_verify_tree(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, const int32_t *parent, int32_t n_window,
+                         int32_t *out_accepted, int32_t *out_next, int32_t *out_path, int32_t *out_predicts, float *out_logits,
+                         void *stream)
+{
+    if (!m || !kv || !window || !parent || !out_accepted || !out_next) return fail(ANPD_E_INVAL, "anpd_verify_tree: NULL argument");
+    if (kv->m != m) return fail(ANPD_E_INVAL, "anpd_verify_tree: the cache belongs to another model");
+    if (n_window < 1) return fail(ANPD_E_INVAL, "anpd_verify_tree: n_window must be >= 1");
+    if (n_window > m->cfg.max_window)
+        return fail(ANPD_E_CAPACITY, "anpd_verify_tree: n_window %d exceeds max_window %d", n_window, m->cfg.max_window);
+    if (kv->len + n_window > kv->max_tokens)
+        return fail(ANPD_E_CAPACITY, "anpd_verify_tree: length %d + window %d exceeds capacity %d", kv->len, n_window, kv->max_tokens);
+    if (parent[0] != -1) return fail(ANPD_E_INVAL, "anpd_verify_tree: parent[0] must be -1");
+    for (int i = 0; i < n_window; ++i) {
+        if (window[i] < 0 || window[i] >= m->cfg.vocab)
+            return fail(ANPD_E_RANGE, "anpd_verify_tree: token %d at window[%d] outside [0, %d)", window[i], i, m->cfg.vocab);
+        if (i > 0 && (parent[i] < 0 || parent[i] >= i))
+            return fail(ANPD_E_INVAL, "anpd_verify_tree: parent[%d] = %d is not an earlier row", i, parent[i]);
+    }
+    hipStream_t st = (hipStream_t)stream;
+    int32_t rc = ensure_pages(kv, kv->len + n_window, st);
+    if (rc != ANPD_OK) return rc;
+    // depth and visibility (self + ancestors) of every row
+    int32_t *tp = m->pin + 128, *td = tp + ANPD_MAX_WINDOW;
+    uint32_t *tm = (uint32_t *)(td + ANPD_MAX_WINDOW);
+    for (int i = 0; i < ANPD_MAX_WINDOW; ++i) { tp[i] = 0; td[i] = 0; tm[i] = 0; }
+    tp[0] = -1;
+    tm[0] = 1u;
+    for (int i = 1; i < n_window; ++i) {
+        tp[i] = parent[i];
+        td[i] = td[parent[i]] + 1;
+        tm[i] = tm[parent[i]] | (1u << i);
+    }
+    std::memcpy(m->pin, window, sizeof(int32_t) * (size_t)n_window);
+    HIP_TRY(hipMemcpyAsync(m->ws + m->lay.tok, m->pin, sizeof(int32_t) * (size_t)n_window, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(m->ws + m->lay.tree, tp, sizeof(int32_t) * 3 * ANPD_MAX_WINDOW, hipMemcpyHostToDevice, st));
+    if (m->mfma) rc = run_step_fast(m, kv, n_window, ANPD_APPEND, st, true);
+    else if (m->cfg.dtype == ANPD_BF16) rc = run_step_generic<bf16_t>(m, kv, n_window, ANPD_APPEND, st, true);
+    else rc = run_step_generic<float>(m, kv, n_window, ANPD_APPEND, st, true);
+    if (rc != ANPD_OK) return rc;
+    int32_t *res = m->pin + 32;
+    HIP_TRY(hipMemcpyAsync(res, m->ws + m->lay.result, sizeof(int32_t) * (size_t)(2 + 2 * ANPD_MAX_WINDOW + 1), hipMemcpyDeviceToHost, st));
+    if (out_logits)
+        HIP_TRY(hipMemcpyAsync(out_logits, m->ws + m->lay.logits, sizeof(float) * (size_t)n_window * m->cfg.vocab,
+                               hipMemcpyDeviceToDevice, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    collect_marks(m);
+    *out_accepted = res[0];
+    *out_next = res[1];
+    if (out_predicts) std::memcpy(out_predicts, res + 2, sizeof(int32_t) * (size_t)n_window);
+    if (out_path) std::memcpy(out_path, res + 34, sizeof(int32_t) * (size_t)(res[0] + 1));
     kv->len += 1 + res[0];
     release_pages(kv, kv->len);
     return ANPD_OK;

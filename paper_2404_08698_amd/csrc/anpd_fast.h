@@ -120,7 +120,10 @@ __global__ __launch_bounds__(256) void pack_kernel(const bf16_t *__restrict__ sr
 
 // --------------------------------------------------------------- epilogues
 
-enum { EPI_PLAIN = 0, EPI_QKV = 1, EPI_RESIDUAL = 2, EPI_GATE_UP = 3, EPI_LOGITS = 4, EPI_LM_ARGMAX = 5 };
+enum { EPI_PLAIN = 0, EPI_QKV = 1, EPI_RESIDUAL = 2, EPI_GATE_UP = 3, EPI_LOGITS = 4, EPI_LM_ARGMAX = 5,
+       EPI_QKV_TREE = 6 /* QKV of a draft tree: a row's rotary position is length + its depth, not length + its index */ };
+__host__ __device__ constexpr bool epi_is_qkv(int epi) { return epi == EPI_QKV || epi == EPI_QKV_TREE; }
+__host__ __device__ constexpr bool epi_has_norm(int epi) { return epi_is_qkv(epi) || epi == EPI_GATE_UP || epi == EPI_LOGITS; }
 
 struct FastArgs {
     // GEMM proper
@@ -152,6 +155,8 @@ struct FastArgs {
     unsigned long long *amax;  // [n_tiles][32]
     // QKV in the persistent kernel: per-head count of finished q / k / v tiles (nullable)
     uint32_t *ready;
+    // QKV_TREE: depth of every window row in the draft tree
+    const int32_t *depth;
 };
 
 // rinv[m] = 1 / sqrt(mean(x[m]^2) + eps) for the window rows, from the producer's per-tile partial
@@ -319,12 +324,12 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
         s += __shfl_xor(s, 16, kWave);
         s += __shfl_xor(s, 32, kWave);
         if (valid && kg == 0) stc<COH>(a.ssp_next + (size_t)tile * 32 + m, s);
-    } else if (EPI == EPI_QKV) {
+    } else if (epi_is_qkv(EPI)) {
         const float r = valid ? rinv[m] : 0.f;
         y = y * r;
         const int T = a.n_heads * a.head_dim / 16;
         const int which = tile / T, t = tile - which * T;
-        const int pos = *a.len_ptr + m;
+        const int pos = *a.len_ptr + m;   // the row's cache slot
         f32x4 other;
 #pragma unroll
         for (int i = 0; i < 4; ++i) other[i] = __shfl_xor(y[i], 32, kWave);
@@ -334,10 +339,11 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
             const int tph = a.head_dim / 16, half = a.head_dim / 2;
             const int h = t / tph, j = t - h * tph;
             const int i0 = 8 * j + 4 * (kg & 1);
+            const int rpos = EPI == EPI_QKV_TREE ? *a.len_ptr + a.depth[m] : pos;   // the row's rotary position
             f32x4 o;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                float2 cs = pre ? pre->cs[i] : a.rope[(size_t)pos * half + i0 + i];
+                float2 cs = pre ? pre->cs[i] : a.rope[(size_t)rpos * half + i0 + i];
                 o[i] = kg < 2 ? y[i] * cs.x - other[i] * cs.y : y[i] * cs.x + other[i] * cs.y;
             }
             const int dim = i0 + (kg < 2 ? 0 : half);
@@ -438,7 +444,7 @@ __global__ __launch_bounds__(kFastThreads) void gemm_xs_kernel(FastArgs a)
         int ks = wave + u * kFastWaves;
         x[u] = ks < nks ? a.Xp[(size_t)ks * 64 + lane] : make_uint4(0, 0, 0, 0);
     }
-    if (EPI == EPI_QKV || EPI == EPI_GATE_UP || EPI == EPI_LOGITS) compute_rinv(a, rinv, &red[1][0][0]);
+    if (epi_has_norm(EPI)) compute_rinv(a, rinv, &red[1][0][0]);
 
     for (int it = 0; tile < a.n_tiles; tile += gridDim.x, ++it) {
         const uint4 *W = a.Wp + (size_t)tile * nks * 64 + lane;
@@ -491,7 +497,7 @@ __global__ __launch_bounds__(kFastThreads) void gemm_stream_kernel(FastArgs a)
     const int nks = a.nks, tile = blockIdx.x;
     const uint4 *W = a.Wp + (size_t)tile * nks * 64 + lane;
     const uint4 *X = a.Xp + lane;
-    if (EPI == EPI_QKV || EPI == EPI_GATE_UP || EPI == EPI_LOGITS) compute_rinv(a, rinv, red_dyn);
+    if (epi_has_norm(EPI)) compute_rinv(a, rinv, red_dyn);
     f32x4 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -538,7 +544,7 @@ __global__ __launch_bounds__(kFastThreads) void gemm_group_kernel(FastArgs a)
     constexpr int C = (NT * TG >= 8) ? 2 : 4;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nks = a.nks;
-    if (EPI == EPI_QKV || EPI == EPI_GATE_UP || EPI == EPI_LOGITS) compute_rinv(a, rinv, red_dyn);
+    if (epi_has_norm(EPI)) compute_rinv(a, rinv, red_dyn);
     const int first = (int)(((long long)blockIdx.x * a.n_tiles) / gridDim.x);
     const int last = (int)(((long long)(blockIdx.x + 1) * a.n_tiles) / gridDim.x);
     const int n_mine = last - first;
@@ -743,13 +749,15 @@ __device__ __forceinline__ size_t part_s_index(int n_heads, int head, int split,
 // kv.loaded, else it is requested here.  `after_loads` runs right after the task's own loads have
 // been issued (the persistent kernel puts its weight prefetch there, so that the prefetch queues
 // behind the loads attention is waiting for, not in front of them).
-template <int DH, bool COH = false, typename AfterLoads = NoPrefetch>
+// TREE: the window is a draft tree; row_mask[m] has bit r set if window row r is row m itself or one
+// of its ancestors, and row m sees the cached positions plus exactly those rows.
+template <int DH, bool COH = false, typename AfterLoads = NoPrefetch, bool TREE = false>
 __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, int head, int split, int L,
                                           const uint4 *__restrict__ qp, const bf16_t *__restrict__ pool,
                                           const int32_t *__restrict__ page_table, int M, int layer, int n_layers, int n_heads,
                                           int max_splits, float scale, float *__restrict__ part,
                                           uint32_t *__restrict__ head_counter, bf16_t *__restrict__ xp_att, int cls,
-                                          AfterLoads after_loads = AfterLoads())
+                                          AfterLoads after_loads = AfterLoads(), const uint32_t *__restrict__ row_mask = nullptr)
 {
     const int tid = fresh_tid();
     constexpr int NKS = DH / 32, NDT = DH / 16;
@@ -780,12 +788,15 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kv.kf[ks]),
                                                           __builtin_bit_cast(bf16x8, qf[ks]), acc, 0, 0, 0);
         const int m = rg * 8 + (slot & 7);
+        uint32_t vis = 0;
+        if (TREE) vis = row_mask[m < M ? m : 0];
         float sc[4], mx = kMasked;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             float lo = row_down8(acc[i]);
             const int key = key0 + 4 * kg + i;
-            const bool ok = active && slot < 8 && m < M && key <= L + m;
+            const bool sees = TREE ? (key < L || (key - L < 32 && ((vis >> (key - L)) & 1u))) : key <= L + m;
+            const bool ok = active && slot < 8 && m < M && sees;
             sc[i] = ok ? (acc[i] + lo) * scale : kMasked;
             mx = fmaxf(mx, sc[i]);
         }
@@ -929,21 +940,45 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
 }
 
 // grid: (n_heads, ceil((len + M) / kFastSplit)), kFastWaves waves.
-template <int DH>
+template <int DH, bool TREE = false>
 __global__ __launch_bounds__(kFastThreads) void attn_fast_kernel(const uint4 *__restrict__ qp, const bf16_t *__restrict__ pool,
                                                           const int32_t *__restrict__ page_table,
                                                           const int32_t *__restrict__ len_ptr, int M, int layer, int n_layers,
                                                           int n_heads, int max_splits, float scale, float *__restrict__ part,
                                                           uint32_t *__restrict__ head_counter, bf16_t *__restrict__ xp_att,
-                                                          int cls)
+                                                          int cls, const uint32_t *__restrict__ row_mask)
 {
     __shared__ AttnShared<DH> sh;
     const int L = *len_ptr;
     if ((int)blockIdx.y * kFastSplit >= L + M) return;
     AttnKV<DH> kv;
     kv.loaded = false;
-    attn_task<DH>(sh, kv, blockIdx.x, blockIdx.y, L, qp, pool, page_table, M, layer, n_layers, n_heads, max_splits, scale, part,
-                  head_counter, xp_att, cls);
+    attn_task<DH, false, NoPrefetch, TREE>(sh, kv, blockIdx.x, blockIdx.y, L, qp, pool, page_table, M, layer, n_layers, n_heads,
+                                           max_splits, scale, part, head_counter, xp_att, cls, NoPrefetch(), row_mask);
+}
+
+// After a draft tree has been verified: the accepted path's rows path[1..a] sit in cache slots
+// L + path[j]; move their K and V to slots L + j (path[j] >= j, so in increasing j a source is never
+// overwritten before it is read).  result[0] = a; path = result + 34.  grid: n_layers * 2 * n_heads.
+__global__ __launch_bounds__(128) void kvf_compact_kernel(bf16_t *__restrict__ pool, const int32_t *__restrict__ page_table,
+                                                           const int32_t *__restrict__ result, int L, int n_layers, int n_heads,
+                                                           int head_dim)
+{
+    const int head = blockIdx.x % n_heads, kv = (blockIdx.x / n_heads) & 1, layer = blockIdx.x / (2 * n_heads);
+    const int a = result[0];
+    const int32_t *path = result + 34;
+    for (int j = 1; j <= a; ++j) {
+        const int src = L + path[j], dst = L + j;
+        if (src != dst && (int)threadIdx.x < head_dim) {
+            const int e = threadIdx.x;
+            const size_t so = kvf_base(page_table[src >> 4], layer, n_layers, kv, head, n_heads, head_dim) +
+                              (kv == 0 ? kf_elem(src & 15, e) : vf_elem(src & 15, e));
+            const size_t dofs = kvf_base(page_table[dst >> 4], layer, n_layers, kv, head, n_heads, head_dim) +
+                                (kv == 0 ? kf_elem(dst & 15, e) : vf_elem(dst & 15, e));
+            pool[dofs] = pool[so];
+        }
+        __syncthreads();
+    }
 }
 
 // Copies n positions of one layer between fp32 [n][d] arrays and the fast-path cache layout.

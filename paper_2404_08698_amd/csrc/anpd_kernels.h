@@ -328,15 +328,17 @@ template <typename KT>
 __global__ __launch_bounds__(256) void rope_kv_kernel(float *__restrict__ qkv, const float2 *__restrict__ rope_tab,
                                                        KT *__restrict__ pool, const int32_t *__restrict__ page_table,
                                                        const int32_t *__restrict__ len_ptr, int layer, int n_layers,
-                                                       int n_heads, int head_dim, int page_tokens)
+                                                       int n_heads, int head_dim, int page_tokens,
+                                                       const int32_t *__restrict__ depth /* draft tree: nullable */)
 {
     const int r = blockIdx.x, d = n_heads * head_dim, half = head_dim >> 1;
-    const int pos = *len_ptr + r;
+    const int pos = *len_ptr + r;                              // the row's cache slot
+    const int rpos = depth ? *len_ptr + depth[r] : pos;        // the row's rotary position
     const int page = page_table[pos / page_tokens], tip = pos % page_tokens;
     float *q = qkv + (size_t)r * 3 * d, *k = q + d, *v = q + 2 * d;
     for (int idx = threadIdx.x; idx < n_heads * half; idx += 256) {
         int hd = idx / half, i = idx - hd * half;
-        float2 cs = rope_tab[(size_t)pos * half + i];
+        float2 cs = rope_tab[(size_t)rpos * half + i];
         int e0 = hd * head_dim + i, e1 = e0 + half;
         float qa = q[e0], qb = q[e1];
         q[e0] = qa * cs.x - qb * cs.y;
@@ -368,7 +370,8 @@ __global__ __launch_bounds__(256) void attn_kernel(const float *__restrict__ qkv
                                                     const int32_t *__restrict__ page_table,
                                                     const int32_t *__restrict__ len_ptr, int M, int layer, int n_layers,
                                                     int n_heads, int page_tokens, int max_window, int max_splits,
-                                                    float scale, float *__restrict__ part)
+                                                    float scale, float *__restrict__ part,
+                                                    const uint32_t *__restrict__ row_mask /* draft tree: nullable */)
 {
     constexpr int LPK = DH / 8;        // lanes per key
     constexpr int KPG = 64 / LPK;      // keys per wave group
@@ -414,7 +417,11 @@ __global__ __launch_bounds__(256) void attn_kernel(const float *__restrict__ qkv
                 for (int i = 0; i < 8; ++i) p = fmaf(qv[mm][i], kv[i], p);
 #pragma unroll
                 for (int off = LPK / 2; off >= 1; off >>= 1) p += __shfl_xor(p, off, kWave);
-                if (dg == 0) sc[mm][jl] = (exists && m0 + mm < M && j <= L + m0 + mm) ? p * scale : kMasked;
+                if (dg == 0) {
+                    bool sees = j <= L + m0 + mm;
+                    if (row_mask && m0 + mm < M) sees = j < L || (j - L < 32 && ((row_mask[m0 + mm] >> (j - L)) & 1u));
+                    sc[mm][jl] = (exists && m0 + mm < M && sees) ? p * scale : kMasked;
+                }
             }
         }
         __syncthreads();
@@ -576,6 +583,55 @@ __global__ __launch_bounds__(1024) void argmax_accept_kernel(const float *__rest
         result[1] = ld_agent(pred + a);
         *len_ptr += 1 + a;
         st_agent(counter, 0u);
+    }
+}
+
+// Acceptance over a draft tree, after argmax_accept_kernel has left the per-row predictions in
+// result[2..] (run in APPEND mode on a copy of the length).  Row r > 0 is accepted iff its parent
+// is and window[r] equals the prediction made at the parent; the deepest accepted row wins (lowest
+// index among equally deep).  result[0] = its depth a, result[1] = the prediction at that row,
+// result[34 + j] = the window row at depth j of the accepted path; length += 1 + a.   One thread.
+__global__ void accept_tree_kernel(const int32_t *__restrict__ window, const int32_t *__restrict__ parent,
+                                   const int32_t *__restrict__ depth, int M, int32_t *__restrict__ result,
+                                   int32_t *__restrict__ len_ptr, int len_before)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const int32_t *pred = result + 2;
+    uint32_t acc = 1u;
+    int best = 0;
+    for (int r = 1; r < M; ++r) {
+        const int p = parent[r];
+        if (((acc >> p) & 1u) && window[r] == pred[p]) {
+            acc |= 1u << r;
+            if (depth[r] > depth[best]) best = r;
+        }
+    }
+    const int a = depth[best];
+    for (int r = best, j = a; j >= 0; --j, r = parent[r]) result[34 + j] = r;
+    result[0] = a;
+    result[1] = pred[best];
+    *len_ptr = len_before + 1 + a;
+}
+
+// Generic-layout counterpart of kvf_compact_kernel.   grid: n_layers * 2 * n_heads blocks.
+template <typename KT>
+__global__ __launch_bounds__(128) void kv_compact_kernel(KT *__restrict__ pool, const int32_t *__restrict__ page_table,
+                                                          const int32_t *__restrict__ result, int L, int n_layers, int n_heads,
+                                                          int head_dim, int page_tokens)
+{
+    const int head = blockIdx.x % n_heads, kv = (blockIdx.x / n_heads) & 1, layer = blockIdx.x / (2 * n_heads);
+    const int a = result[0];
+    const int32_t *path = result + 34;
+    for (int j = 1; j <= a; ++j) {
+        const int src = L + path[j], dst = L + j;
+        if (src != dst && (int)threadIdx.x < head_dim) {
+            const size_t so = kv_offset(page_table[src / page_tokens], layer, n_layers, kv, head, n_heads, src % page_tokens,
+                                        page_tokens, head_dim);
+            const size_t dofs = kv_offset(page_table[dst / page_tokens], layer, n_layers, kv, head, n_heads, dst % page_tokens,
+                                          page_tokens, head_dim);
+            pool[dofs + threadIdx.x] = pool[so + threadIdx.x];
+        }
+        __syncthreads();
     }
 }
 

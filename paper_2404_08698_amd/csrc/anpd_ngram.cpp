@@ -209,4 +209,57 @@ int32_t anpd_ngram_propose(const anpd_ngram_t *t, int32_t max_k, int32_t *out_to
     return k;
 }
 
+int32_t anpd_ngram_propose_tree(const anpd_ngram_t *t, int32_t max_k, int32_t n_cand, int32_t max_drafts, int32_t *out_tokens,
+                                int32_t *out_parents, int32_t *out_levels)
+{
+    if (!t || max_k < 0 || n_cand < 1 || max_drafts < 0 || (max_drafts > 0 && max_k > 0 && (!out_tokens || !out_parents)))
+        return fail(ANPD_E_INVAL, "anpd_ngram_propose_tree: bad argument");
+    if (max_k == 0 || max_drafts == 0) return 0;
+    size_t keep = (size_t)(t->n_max - 1);
+    size_t have = t->ids.size() < keep ? t->ids.size() : keep;
+    std::vector<int32_t> base(t->ids.end() - (long)have, t->ids.end());
+    // first tokens of the candidates: walk the levels downwards; inside a level the followers of the
+    // context by (count, latest position) descending; distinct tokens only
+    struct First { int32_t token, level; };
+    std::vector<First> firsts;
+    for (int n = t->n_max; n >= t->n_min && (int)firsts.size() < n_cand; --n) {
+        if ((int64_t)base.size() < n - 1) continue;
+        const Level &level = t->levels[(size_t)(n - t->n_min)];
+        auto it = level.find(make_context(base.data() + base.size(), n - 1));
+        if (it == level.end()) continue;
+        std::vector<Follower> fs = it->second.list;
+        for (size_t i = 1; i < fs.size(); ++i) {   // insertion sort: a context has few followers
+            Follower f = fs[i];
+            size_t j = i;
+            while (j > 0 && (fs[j - 1].count < f.count || (fs[j - 1].count == f.count && fs[j - 1].latest < f.latest))) {
+                fs[j] = fs[j - 1];
+                --j;
+            }
+            fs[j] = f;
+        }
+        for (const Follower &f : fs) {
+            bool seen = false;
+            for (const First &g : firsts) seen = seen || g.token == f.token;
+            if (!seen && (int)firsts.size() < n_cand) firsts.push_back({f.token, n});
+        }
+    }
+    int32_t rows = 0;   // drafts written so far; draft i is window row i + 1
+    std::vector<int32_t> tail;
+    for (const First &f : firsts) {
+        if (rows >= max_drafts) break;
+        tail = base;
+        int32_t parent = 0, tok = f.token, lvl = f.level;
+        for (int32_t k = 0; k < max_k && rows < max_drafts; ++k) {
+            if (k > 0 && !mln_query(t, tail.data() + tail.size(), (int64_t)tail.size(), &tok, &lvl)) break;
+            out_tokens[rows] = tok;
+            out_parents[rows] = parent;
+            if (out_levels) out_levels[rows] = lvl;
+            parent = rows + 1;
+            ++rows;
+            tail.push_back(tok);
+        }
+    }
+    return rows;
+}
+
 }  // extern "C"

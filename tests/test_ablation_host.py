@@ -43,3 +43,17 @@ def test_periodic_stream_is_drafted_perfectly_and_step_times_are_applied():
     assert abs(ablation.speedup_with_times(r, flat) - r["tokens_per_step"]) < 1e-9
     slow = {1: 3.0, 8: 6.0}
     assert ablation.speedup_with_times(r, slow) < r["tokens_per_step"]
+
+
+def test_multi_candidate_driver_counts_match_the_oracle_loop():
+    vocab, P, G = 64, 48, 120
+    stream = synth.markov_stream(vocab, P + G + 40, 0.5, 3, 9, 321)
+    for n_min, n_max, K, n_cand, budget in ((2, 4, 4, 3, 31), (2, 2, 3, 2, 5), (2, 5, 6, 1, 31)):
+        ref = oanpd.anpd_generate_multi(StreamModel(stream, P), stream[:P], K, n_cand, G, budget, n_min, n_max)
+        got = ablation.run_stream_multi(stream, P, n_min, n_max, K, n_cand, vocab, budget,
+                                        max_tokens=sum(1 + s["accepted"] for s in ref["steps"]))
+        assert got["steps"] == ref["n_steps"]
+        assert got["proposed"] == ref["proposed"] and got["accepted"] == ref["accepted"]
+        if n_cand == 1:
+            one = ablation.run_stream(stream, P, n_min, n_max, K, vocab, max_tokens=got["tokens"])
+            assert (one["steps"], one["accepted"]) == (got["steps"], got["accepted"])
