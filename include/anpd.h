@@ -225,7 +225,8 @@ int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32
  *   out_predicts / out_logits: as in anpd_verify, by window row.
  * A chain (parent[r] = r - 1) gives bit for bit the result of anpd_verify.  Other shapes give every
  * row the same keys in different cache slots: the same sums in another order, equal to rounding.
- * Runs as one launch per operation (the one-kernel step takes chains only).
+ * Windows of up to 8 rows run as the one-kernel step (its draft-tree form), larger ones as one launch
+ * per operation; a small kernel then moves the winning path's K and V into place.
  * Errors: as anpd_verify; ANPD_E_INVAL for a parent that is not an earlier row. */
 int32_t anpd_verify_tree(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, const int32_t *parent,
                          int32_t n_window, int32_t *out_accepted, int32_t *out_next, int32_t *out_path,

@@ -150,6 +150,7 @@ struct anpd_model {
     bool mfma;
     int n_cu;
     bool mega;            // the one-kernel step is available
+    bool mega_tree;       // ... and so is its draft-tree form
     long long *trace;     // optional device buffer for barrier timestamps
     int mega_grid;
     bool plain_launch;    // launch the one-kernel step without the cooperative-launch API (profiling aid)
@@ -548,7 +549,9 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
 }
 
 // The step as one persistent kernel (window class 8).
-int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, int mode, bool want_logits, hipStream_t st)
+// tree (nullable): the pinned draft-tree arrays parent[32], depth[32], mask[32] of a window of at most 8 rows.
+int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, int mode, bool want_logits, hipStream_t st,
+                      const int32_t *tree = nullptr)
 {
     const anpd_model_cfg &c = m->cfg;
     const Layout &L = m->lay;
@@ -584,23 +587,31 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, 
     g.qkv_ready = (uint32_t *)(ws + L.bar) + kBarStride * 9;
     g.ready_epoch = m->ready_epoch;
     g.trace = m->trace;
+    if (tree)
+        for (int i = 0; i < 8; ++i) {
+            g.parent[i] = tree[i];
+            g.depth[i] = tree[ANPD_MAX_WINDOW + i];
+            g.mask[i] = (uint32_t)tree[2 * ANPD_MAX_WINDOW + i];
+        }
     m->ev_used = 0;
     mark(m, -1, st);
     void *args[] = {&g};
+    const void *fn = c.head_dim == 128 ? (tree ? (const void *)verify_mega_kernel<128, true> : (const void *)verify_mega_kernel<128, false>)
+                                       : (tree ? (const void *)verify_mega_kernel<64, true> : (const void *)verify_mega_kernel<64, false>);
     if (m->plain_launch) {
         // profiling aid (see anpd_model_create): an ordinary launch of the same grid
-        if (c.head_dim == 128)
-            hipLaunchKernelGGL((verify_mega_kernel<128>), dim3((unsigned)m->mega_grid), dim3(kFastThreads), 0, st, g);
-        else
-            hipLaunchKernelGGL((verify_mega_kernel<64>), dim3((unsigned)m->mega_grid), dim3(kFastThreads), 0, st, g);
-        HIP_TRY(hipGetLastError());
-    } else if (c.head_dim == 128) {
-        HIP_TRY(hipLaunchCooperativeKernel((const void *)verify_mega_kernel<128>, dim3((unsigned)m->mega_grid), dim3(kFastThreads), args, 0, st));
+        HIP_TRY(hipLaunchKernel(fn, dim3((unsigned)m->mega_grid), dim3(kFastThreads), args, 0, st));
     } else {
-        HIP_TRY(hipLaunchCooperativeKernel((const void *)verify_mega_kernel<64>, dim3((unsigned)m->mega_grid), dim3(kFastThreads), args, 0, st));
+        HIP_TRY(hipLaunchCooperativeKernel(fn, dim3((unsigned)m->mega_grid), dim3(kFastThreads), args, 0, st));
     }
     m->bar_epoch += (uint32_t)kMegaBarriers(c.n_layers);
     m->ready_epoch += (uint32_t)c.n_layers;
+    if (tree) {
+        // the winning path's K and V to consecutive positions (a no-op kernel when it is the first candidate)
+        hipLaunchKernelGGL(kvf_compact_kernel, dim3((unsigned)(c.n_layers * 2 * c.n_heads)), dim3(128), 0, st, (bf16_t *)kv->pool,
+                           kv->d_table, (const int32_t *)(ws + L.result), kv->len, c.n_layers, c.n_heads, c.head_dim);
+        HIP_TRY(hipGetLastError());
+    }
     mark(m, ANPD_PROF_STEP, st);
     return ANPD_OK;
 }
@@ -751,6 +762,19 @@ int32_t run_prefill_mfma(anpd_model *m, anpd_kv *kv, int P, char *pws, const Pre
     return ANPD_OK;
 }
 
+// After the stream has been synchronised: did a grid barrier of the one-kernel step give up?  Then the
+// counters are no longer in step: start them over.
+bool barrier_gave_up(anpd_model *m, hipStream_t st)
+{
+    if (m->pin[100] == 0) return false;
+    m->pin[100] = 0;
+    (void)hipMemsetAsync(m->ws + m->lay.bar, 0, kBarStride * 9 * sizeof(uint32_t) + (size_t)m->cfg.n_heads * kCounterStride * sizeof(uint32_t), st);
+    (void)hipStreamSynchronize(st);
+    m->bar_epoch = 0;
+    m->ready_epoch = 0;
+    return true;
+}
+
 }  // namespace
 
 extern "C" {
@@ -834,6 +858,7 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
     if (e == hipSuccess) e = hipMemcpyAsync(m->ws + lay.rope_tab, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice, st);
     int32_t prc = ANPD_OK;
     m->mega = false;
+    m->mega_tree = false;
     m->trace = nullptr;
     m->mega_grid = 0;
     m->bar_epoch = 0;
@@ -866,6 +891,12 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
             if (e == hipSuccess) e = hipStreamSynchronize(st);  // `tab` is about to go out of scope
             m->mega = true;
             m->mega_grid = m->n_cu;
+            int per_cu_t = 0;
+            hipError_t te = cfg->head_dim == 128
+                                ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_t, verify_mega_kernel<128, true>, kFastThreads, 0)
+                                : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_t, verify_mega_kernel<64, true>, kFastThreads, 0);
+            m->mega_tree = te == hipSuccess && per_cu_t >= 1;
+            if (te != hipSuccess) (void)hipGetLastError();
         } else {
             (void)hipGetLastError();
         }
@@ -1111,15 +1142,7 @@ int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32
         HIP_TRY(hipMemcpyAsync(out_logits, m->ws + m->lay.logits, sizeof(float) * (size_t)n_window * m->cfg.vocab,
                                hipMemcpyDeviceToDevice, st));
     HIP_TRY(hipStreamSynchronize(st));
-    if (one_kernel && m->pin[100] != 0) {
-        // a grid barrier gave up: the counters are no longer in step, start them over
-        m->pin[100] = 0;
-        (void)hipMemsetAsync(m->ws + m->lay.bar, 0, kBarStride * 9 * sizeof(uint32_t) + (size_t)m->cfg.n_heads * kCounterStride * sizeof(uint32_t), st);
-        (void)hipStreamSynchronize(st);
-        m->bar_epoch = 0;
-        m->ready_epoch = 0;
-        return fail(ANPD_E_HIP, "anpd_verify: the persistent kernel timed out at a grid barrier");
-    }
+    if (one_kernel && barrier_gave_up(m, st)) return fail(ANPD_E_HIP, "anpd_verify: the persistent kernel timed out at a grid barrier");
     collect_marks(m);
     *out_accepted = res[0];
     *out_next = res[1];
@@ -1161,19 +1184,28 @@ int32_t anpd_verify_tree(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, 
         td[i] = td[parent[i]] + 1;
         tm[i] = tm[parent[i]] | (1u << i);
     }
-    std::memcpy(m->pin, window, sizeof(int32_t) * (size_t)n_window);
-    HIP_TRY(hipMemcpyAsync(m->ws + m->lay.tok, m->pin, sizeof(int32_t) * (size_t)n_window, hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(m->ws + m->lay.tree, tp, sizeof(int32_t) * 3 * ANPD_MAX_WINDOW, hipMemcpyHostToDevice, st));
-    if (m->mfma) rc = run_step_fast(m, kv, n_window, ANPD_APPEND, st, true);
-    else if (m->cfg.dtype == ANPD_BF16) rc = run_step_generic<bf16_t>(m, kv, n_window, ANPD_APPEND, st, true);
-    else rc = run_step_generic<float>(m, kv, n_window, ANPD_APPEND, st, true);
-    if (rc != ANPD_OK) return rc;
     int32_t *res = m->pin + 32;
-    HIP_TRY(hipMemcpyAsync(res, m->ws + m->lay.result, sizeof(int32_t) * (size_t)(2 + 2 * ANPD_MAX_WINDOW + 1), hipMemcpyDeviceToHost, st));
+    // windows of up to 8 rows: the one-kernel step in its draft-tree form (tokens and tree by value, result
+    // written to pinned memory by the kernel); otherwise one launch per operation
+    const bool one_kernel = m->mega && m->mega_tree && n_window <= 8;
+    if (one_kernel) {
+        rc = run_step_mega(m, kv, window, n_window, ANPD_APPEND, out_logits != nullptr, st, tp);
+        if (rc != ANPD_OK) return rc;
+    } else {
+        std::memcpy(m->pin, window, sizeof(int32_t) * (size_t)n_window);
+        HIP_TRY(hipMemcpyAsync(m->ws + m->lay.tok, m->pin, sizeof(int32_t) * (size_t)n_window, hipMemcpyHostToDevice, st));
+        HIP_TRY(hipMemcpyAsync(m->ws + m->lay.tree, tp, sizeof(int32_t) * 3 * ANPD_MAX_WINDOW, hipMemcpyHostToDevice, st));
+        if (m->mfma) rc = run_step_fast(m, kv, n_window, ANPD_APPEND, st, true);
+        else if (m->cfg.dtype == ANPD_BF16) rc = run_step_generic<bf16_t>(m, kv, n_window, ANPD_APPEND, st, true);
+        else rc = run_step_generic<float>(m, kv, n_window, ANPD_APPEND, st, true);
+        if (rc != ANPD_OK) return rc;
+        HIP_TRY(hipMemcpyAsync(res, m->ws + m->lay.result, sizeof(int32_t) * (size_t)(2 + 2 * ANPD_MAX_WINDOW + 1), hipMemcpyDeviceToHost, st));
+    }
     if (out_logits)
         HIP_TRY(hipMemcpyAsync(out_logits, m->ws + m->lay.logits, sizeof(float) * (size_t)n_window * m->cfg.vocab,
                                hipMemcpyDeviceToDevice, st));
     HIP_TRY(hipStreamSynchronize(st));
+    if (one_kernel && barrier_gave_up(m, st)) return fail(ANPD_E_HIP, "anpd_verify_tree: the persistent kernel timed out at a grid barrier");
     collect_marks(m);
     *out_accepted = res[0];
     *out_next = res[1];

@@ -253,7 +253,7 @@ __device__ __forceinline__ void epilogue_preload(const FastArgs &a, int tile, in
             pre.g = (f32x4){__uint_as_float(gb.x << 16), __uint_as_float(gb.x & 0xffff0000u), __uint_as_float(gb.y << 16),
                             __uint_as_float(gb.y & 0xffff0000u)};
         }
-    } else if (EPI == EPI_QKV) {
+    } else if (epi_is_qkv(EPI)) {
         const int T = a.n_heads * a.head_dim / 16;
         const int which = tile / T, t = tile - which * T;
         const int pos = *a.len_ptr + m;
@@ -266,8 +266,9 @@ __device__ __forceinline__ void epilogue_preload(const FastArgs &a, int tile, in
                 const int tph = a.head_dim / 16, half = a.head_dim / 2;
                 const int j = t % tph;
                 const int i0 = 8 * j + 4 * (kg & 1);
+                const int rpos = EPI == EPI_QKV_TREE ? *a.len_ptr + a.depth[m] : pos;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) pre.cs[i] = a.rope[(size_t)pos * half + i0 + i];
+                for (int i = 0; i < 4; ++i) pre.cs[i] = a.rope[(size_t)rpos * half + i0 + i];
             }
         }
     }

@@ -59,6 +59,10 @@ struct MegaArgs {
     uint32_t *qkv_ready;    // [n_heads] finished q / k / v tiles of the head, counted up over layers and launches
     uint32_t ready_epoch;   // QKV phases completed by earlier launches
     long long *trace;       // nullable: [grid][kTraceEvents] timestamps (100 MHz) at barrier arrive / wait-done
+    // draft tree (multi-candidate verification), by value like the tokens: parent row, depth, and the
+    // rows a row sees (itself and its ancestors) as a bit mask
+    int32_t parent[8], depth[8];
+    uint32_t mask[8];
 };
 
 constexpr int kTraceEvents = 1024;
@@ -212,7 +216,7 @@ __device__ __forceinline__ void pre_to_lds(EpiPreLds &d, const EpiPre &p, int la
     if (EPI == EPI_RESIDUAL) {
         d.x[lane] = p.x;
         d.g[lane] = p.g;
-    } else if (EPI == EPI_QKV) {
+    } else if (epi_is_qkv(EPI)) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) d.cs[i][lane] = p.cs[i];
         d.page[lane] = p.page;
@@ -224,7 +228,7 @@ __device__ __forceinline__ void pre_from_lds(EpiPre &p, const EpiPreLds &d, int 
     if (EPI == EPI_RESIDUAL) {
         p.x = d.x[lane];
         p.g = d.g[lane];
-    } else if (EPI == EPI_QKV) {
+    } else if (epi_is_qkv(EPI)) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) p.cs[i] = d.cs[i][lane];
         p.page = d.page[lane];
@@ -288,7 +292,7 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
             next_issued = true;
         }
     };
-    constexpr bool kHasPre = (EPI == EPI_RESIDUAL || EPI == EPI_QKV);
+    constexpr bool kHasPre = (EPI == EPI_RESIDUAL || epi_is_qkv(EPI));
     const bool stages = kHasPre && wave < kPreTiles && wave < my_tiles;   // this wave finishes tile number `wave`
     EpiPre pre0;
     if (stages) epilogue_preload<EPI>(a, blockIdx.x + wave * grid, lane, pre0);
@@ -307,7 +311,7 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     if (STATIONARY || 1 < n_steps) load_xchunk(x1, a.Xp, a.nks, STATIONARY ? 1 : 1 % n_chunks, wave, lane);
     // the RMSNorm scale is needed by the first epilogue only: its partial sums are requested here and
     // reduced after the first tile's MFMAs, off the path from the barrier to the first MFMA
-    constexpr bool kNorm = (EPI == EPI_QKV || EPI == EPI_GATE_UP || EPI == EPI_LOGITS || EPI == EPI_LM_ARGMAX);
+    constexpr bool kNorm = (epi_has_norm(EPI) || EPI == EPI_LM_ARGMAX);
     const bool late_norm = kNorm && a.n_ss <= 256 && my_tiles > 0;
     float nv[4];
     if (late_norm) rinv_issue<true>(a, nv, tid);
@@ -376,7 +380,7 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
             const int mine = (my_tiles - 1 - wave) / kFastWaves + 1;
             if (lane == 0 && atomicAdd(&sh.tiles_done, mine) + mine == tiles_after) bar_signal(bar);
         }
-        if (EPI == EPI_QKV && a.ready && lane == 0) {
+        if (epi_is_qkv(EPI) && a.ready && lane == 0) {
             // the attention tasks of a head wait for its 3 * head_dim / 16 tiles only, not for the whole grid
             const int T = a.n_heads * a.head_dim / 16, tph = a.head_dim / 16;
             for (int i = wave; i < my_tiles; i += kFastWaves) {
@@ -436,7 +440,10 @@ __device__ __forceinline__ FastArgs base_args(MegaArgsK g)
     return a;
 }
 
-template <int DH>
+// TREE: the window is a draft tree (see MegaArgs::parent): rotary positions by depth, attention over
+// ancestors only, acceptance along the paths.  A separate instantiation, so the chain form keeps its
+// registers.
+template <int DH, bool TREE = false>
 __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* read through phase_args() */)
 {
     __shared__ MegaShared sh;
@@ -478,8 +485,9 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             const int nks_d = (g->d + 31) / 32;
             a.Wp = w.qkv; a.Xp = (const uint4 *)g->xp_d; a.nks = nks_d; a.n_tiles = 3 * g->d / 16;
             a.ssp = g->ssp_a; a.layer = l; a.ready = g->qkv_ready;
+            if (TREE) a.depth = (const int32_t *)g->depth;
             WSrc none = {w.o, nks_d, 0};   // the O tile is fetched from inside the attention phase
-            gemm_phase<EPI_QKV, true, false>(a, none, pf, sh, bar, tiles_before);
+            gemm_phase<TREE ? EPI_QKV_TREE : EPI_QKV, true, false>(a, none, pf, sh, bar, tiles_before);
         }
         {   // attention: (head, split) tasks; the O weights stream in meanwhile.  Cache pages wholly
             // below the committed length do not depend on this step: the first task's page is
@@ -514,9 +522,10 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             for (int t = blockIdx.x; t < n_tasks; t += grid) {
                 const int head = t % n_heads, split = t / n_heads;
                 if (t != (int)blockIdx.x) kv.loaded = false;
-                attn_task<DH, true>(attn_shared<DH>(sh), kv, head, split, L, (const uint4 *)g->qp, g->pool, g->page_table, M, l,
-                                    n_layers, n_heads, g->max_splits, g->scale, g->part, g->head_counter, g->xp_att, 8,
-                                    prefetch_o);
+                attn_task<DH, true, decltype(prefetch_o), TREE>(attn_shared<DH>(sh), kv, head, split, L, (const uint4 *)g->qp, g->pool,
+                                                                g->page_table, M, l, n_layers, n_heads, g->max_splits, g->scale,
+                                                                g->part, g->head_counter, g->xp_att, 8, prefetch_o,
+                                                                (const uint32_t *)g->mask);
                 block_sync_lds();
             }
             prefetch_o();
@@ -595,15 +604,36 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
         if (last_row && threadIdx.x == 0) {
             const int32_t *pred = g->result + 2;
             int acc_n = 0;
-            if (g->mode == 0) {
-                while (acc_n < g->M - 1 && g->tok[acc_n + 1] == ld_agent(pred + acc_n)) ++acc_n;
+            int32_t next;
+            int32_t *hr = g->host_result;
+            if (TREE) {
+                // row r > 0 is accepted iff its parent is and its token is the prediction made there; the
+                // deepest accepted row wins, the lowest index among equally deep ones
+                uint32_t ok = 1u;
+                int best = 0;
+                for (int r = 1; r < g->M; ++r) {
+                    const int p = g->parent[r];
+                    if (((ok >> p) & 1u) && g->tok[r] == ld_agent(pred + p)) {
+                        ok |= 1u << r;
+                        if (g->depth[r] > g->depth[best]) best = r;
+                    }
+                }
+                acc_n = g->depth[best];
+                next = ld_agent(pred + best);
+                for (int r = best, j = acc_n; j >= 0; --j, r = g->parent[r]) {
+                    g->result[34 + j] = r;
+                    st_system(hr + 34 + j, (int32_t)r);
+                }
             } else {
-                acc_n = g->M - 1;
+                if (g->mode == 0) {
+                    while (acc_n < g->M - 1 && g->tok[acc_n + 1] == ld_agent(pred + acc_n)) ++acc_n;
+                } else {
+                    acc_n = g->M - 1;
+                }
+                next = ld_agent(pred + acc_n);
             }
-            const int32_t next = ld_agent(pred + acc_n);
             g->result[0] = acc_n;
             g->result[1] = next;
-            int32_t *hr = g->host_result;
             st_system(hr, (int32_t)acc_n);
             st_system(hr + 1, next);
             for (int i = 0; i < g->M; ++i) st_system(hr + 2 + i, ld_agent(pred + i));
