@@ -97,7 +97,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="llama7b", choices=["tiny", "llama7b", "llama13b", "long7b"])
+    ap.add_argument("--workload", default="llama7b", choices=["tiny", "llama7b", "llama13b", "long7b", "glm6b"])
     ap.add_argument("--gemm-path", default="auto", choices=["auto", "dot", "mfma", "launches"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=2)

@@ -135,10 +135,15 @@ typedef struct {
     int32_t max_window;     /* largest n_window, 1..ANPD_MAX_WINDOW */
     int32_t max_positions;  /* largest KV capacity any anpd_kv_t of this model may have */
     int32_t gemm_path;      /* ANPD_GEMM_*: AUTO = MFMA for bf16, dot products for f32 */
+    int32_t n_kv_heads;     /* key / value heads shared by groups of n_heads / n_kv_heads query heads
+                               (grouped-query attention, e.g. the ChatGLM model of the paper's Table 1:
+                               query head h reads key / value head h / (n_heads / n_kv_heads));
+                               0 = n_heads, one per query head.  Must divide n_heads. */
 } anpd_model_cfg;
 
 /* All pointers are DEVICE pointers to [out][in] row-major matrices (gains:
- * [d_model]) in cfg.dtype, borrowed for the model's lifetime.  The per-layer
+ * [d_model]) in cfg.dtype, borrowed for the model's lifetime.  wk and wv have
+ * n_kv_heads * head_dim rows.  The per-layer
  * members are HOST arrays of n_layers device pointers (read at create). */
 typedef struct {
     const void *embed, *final_norm, *lm_head;   /* [vocab][d], [d], [vocab][d] */
@@ -181,7 +186,7 @@ int32_t anpd_kv_truncate(anpd_kv_t *kv, int32_t new_len, void *stream);
 int32_t anpd_kv_set_page_order(anpd_kv_t *kv, const int32_t *perm, int32_t n_pages);
 int32_t anpd_kv_num_pages(const anpd_kv_t *kv);
 /* Copy n positions of one layer between the cache and DEVICE float32 arrays
- * k, v of shape [n][d_model] (values are converted to / from cfg.dtype).
+ * k, v of shape [n][n_kv_heads * head_dim] (values are converted to / from cfg.dtype).
  * Writing allocates pages as needed and does not change the length.
  * Synchronous with respect to the host. */
 int32_t anpd_kv_write(anpd_kv_t *kv, int32_t layer, int32_t pos0, int32_t n, const float *k,

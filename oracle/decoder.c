@@ -12,7 +12,10 @@
  * paper wraps a LLaMA model without describing its layer; the layer below is
  * the public LLaMA architecture: RMSNorm, rotary position embedding in the
  * half-split pairing (i, i + head_dim/2), causal softmax attention with scale
- * 1/sqrt(head_dim), SwiGLU feed-forward, no biases, untied LM head.
+ * 1/sqrt(head_dim), SwiGLU feed-forward, no biases, untied LM head.  Keys and
+ * values may be shared by groups of query heads (grouped-query attention, the
+ * arrangement of the ChatGLM model the paper also evaluates): with n_kv_heads
+ * key/value heads, query head h reads key/value head h / (n_heads / n_kv_heads).
  *
  * Arithmetic is IEEE double throughout.  Storage formats are part of the
  * problem and are modelled: weights arrive either as float32 or as bfloat16
@@ -36,6 +39,7 @@ typedef struct {
     double rms_eps, rope_base;
     int32_t w_dtype; /* ORC_F32 or ORC_BF16: element type behind every weight pointer */
     int32_t kv_bf16; /* round cached K and V to bfloat16 */
+    int32_t n_kv_heads; /* key/value heads; 0 means n_heads (one per query head) */
 } orc_cfg;
 
 typedef struct {
@@ -51,8 +55,8 @@ typedef struct {
 
 typedef struct {
     int32_t max_tokens, len;
-    int32_t n_layers, d_model;
-    double *k, *v; /* [layer][max_tokens][d_model] */
+    int32_t n_layers, d_model; /* d_model here: width of a cached row = n_kv_heads * head_dim */
+    double *k, *v; /* [layer][max_tokens][n_kv_heads * head_dim] */
 } orc_kv;
 
 /* ---- storage formats ---------------------------------------------------- */
@@ -124,19 +128,21 @@ void orc_rope(double *v, int H, int dh, int pos, double base)
     }
 }
 
-/* One query token (H heads) against cached positions 0..n_keys-1.
- * Kc, Vc: [n_keys][H*dh].  out: [H*dh]. */
-void orc_attention(const double *q, const double *Kc, const double *Vc, int n_keys, int H, int dh,
-                   double *out)
+/* One query token (H heads) against cached positions 0..n_keys-1, the keys and values held as Hkv
+ * heads (H a multiple of Hkv): query head h reads key/value head h / (H / Hkv).
+ * Kc, Vc: [n_keys][Hkv*dh].  out: [H*dh]. */
+void orc_attention_grouped(const double *q, const double *Kc, const double *Vc, int n_keys, int H, int Hkv, int dh,
+                           double *out)
 {
-    int d = H * dh;
+    int d = Hkv * dh, group = H / Hkv;
     double scale = 1.0 / sqrt((double)dh);
     double *s = (double *)malloc(sizeof(double) * (size_t)n_keys);
     for (int h = 0; h < H; ++h) {
         const double *qh = q + (size_t)h * dh;
+        const int hk = h / group;
         double mx = -INFINITY;
         for (int j = 0; j < n_keys; ++j) {
-            const double *kj = Kc + (size_t)j * d + (size_t)h * dh;
+            const double *kj = Kc + (size_t)j * d + (size_t)hk * dh;
             double acc = 0.0;
             for (int i = 0; i < dh; ++i) acc += qh[i] * kj[i];
             s[j] = acc * scale;
@@ -149,11 +155,18 @@ void orc_attention(const double *q, const double *Kc, const double *Vc, int n_ke
         }
         for (int i = 0; i < dh; ++i) {
             double acc = 0.0;
-            for (int j = 0; j < n_keys; ++j) acc += s[j] * Vc[(size_t)j * d + (size_t)h * dh + i];
+            for (int j = 0; j < n_keys; ++j) acc += s[j] * Vc[(size_t)j * d + (size_t)hk * dh + i];
             out[(size_t)h * dh + i] = acc / denom;
         }
     }
     free(s);
+}
+
+/* The same with one key/value head per query head. */
+void orc_attention(const double *q, const double *Kc, const double *Vc, int n_keys, int H, int dh,
+                   double *out)
+{
+    orc_attention_grouped(q, Kc, Vc, n_keys, H, H, dh, out);
 }
 
 /* SwiGLU: out_i = silu(gate_i) * up_i, silu(z) = z / (1 + exp(-z)) */
@@ -192,7 +205,7 @@ orc_kv *orc_kv_create(const orc_model *m, int32_t max_tokens)
     orc_kv *kv = (orc_kv *)calloc(1, sizeof(orc_kv));
     kv->max_tokens = max_tokens;
     kv->n_layers = m->cfg.n_layers;
-    kv->d_model = m->cfg.d_model;
+    kv->d_model = (m->cfg.n_kv_heads > 0 ? m->cfg.n_kv_heads : m->cfg.n_heads) * m->cfg.head_dim;
     size_t n = (size_t)kv->n_layers * (size_t)max_tokens * (size_t)kv->d_model;
     kv->k = (double *)calloc(n, sizeof(double));
     kv->v = (double *)calloc(n, sizeof(double));
@@ -259,15 +272,16 @@ int32_t orc_forward(const orc_model *mdl, orc_kv *kv, const int32_t *tokens, int
     const orc_weights *w = &mdl->w;
     const int d = c->d_model, H = c->n_heads, dh = c->head_dim, F = c->d_ffn, V = c->vocab;
     const int L = kv->len, wd = c->w_dtype;
-    if (n < 1 || L + n > kv->max_tokens || H * dh != d) return -1;
+    const int Hkv = c->n_kv_heads > 0 ? c->n_kv_heads : H, dkv = Hkv * dh;
+    if (n < 1 || L + n > kv->max_tokens || H * dh != d || H % Hkv != 0 || kv->d_model != dkv) return -1;
     for (int r = 0; r < n; ++r)
         if (tokens[r] < 0 || tokens[r] >= V) return -1;
 
     double *x = (double *)malloc(sizeof(double) * (size_t)n * d);
     double *h = (double *)malloc(sizeof(double) * (size_t)n * d);
     double *q = (double *)malloc(sizeof(double) * (size_t)n * d);
-    double *kk = (double *)malloc(sizeof(double) * (size_t)n * d);
-    double *vv = (double *)malloc(sizeof(double) * (size_t)n * d);
+    double *kk = (double *)malloc(sizeof(double) * (size_t)n * dkv);
+    double *vv = (double *)malloc(sizeof(double) * (size_t)n * dkv);
     double *att = (double *)malloc(sizeof(double) * (size_t)n * d);
     double *y = (double *)malloc(sizeof(double) * (size_t)n * d);
     double *g = (double *)malloc(sizeof(double) * (size_t)n * F);
@@ -278,27 +292,27 @@ int32_t orc_forward(const orc_model *mdl, orc_kv *kv, const int32_t *tokens, int
         for (int i = 0; i < d; ++i) x[(size_t)r * d + i] = widen(w->embed, wd, (size_t)tokens[r] * d + i);
 
     for (int l = 0; l < c->n_layers; ++l) {
-        double *Kc = kv->k + (size_t)l * kv->max_tokens * d;
-        double *Vc = kv->v + (size_t)l * kv->max_tokens * d;
+        double *Kc = kv->k + (size_t)l * kv->max_tokens * dkv;
+        double *Vc = kv->v + (size_t)l * kv->max_tokens * dkv;
         for (int r = 0; r < n; ++r)
             orc_rmsnorm(x + (size_t)r * d, w->attn_norm[l], wd, d, c->rms_eps, h + (size_t)r * d);
         orc_linear(h, n, d, w->wq[l], wd, d, q);
-        orc_linear(h, n, d, w->wk[l], wd, d, kk);
-        orc_linear(h, n, d, w->wv[l], wd, d, vv);
+        orc_linear(h, n, d, w->wk[l], wd, dkv, kk);
+        orc_linear(h, n, d, w->wv[l], wd, dkv, vv);
         for (int r = 0; r < n; ++r) {
             int pos = L + r;
             orc_rope(q + (size_t)r * d, H, dh, pos, c->rope_base);
-            orc_rope(kk + (size_t)r * d, H, dh, pos, c->rope_base);
-            for (int i = 0; i < d; ++i) {
-                double kval = kk[(size_t)r * d + i], vval = vv[(size_t)r * d + i];
+            orc_rope(kk + (size_t)r * dkv, Hkv, dh, pos, c->rope_base);
+            for (int i = 0; i < dkv; ++i) {
+                double kval = kk[(size_t)r * dkv + i], vval = vv[(size_t)r * dkv + i];
                 if (c->kv_bf16) { kval = orc_round_bf16(kval); vval = orc_round_bf16(vval); }
-                Kc[(size_t)pos * d + i] = kval;
-                Vc[(size_t)pos * d + i] = vval;
+                Kc[(size_t)pos * dkv + i] = kval;
+                Vc[(size_t)pos * dkv + i] = vval;
             }
         }
 #pragma omp parallel for schedule(static)
         for (int r = 0; r < n; ++r)
-            orc_attention(q + (size_t)r * d, Kc, Vc, L + r + 1, H, dh, att + (size_t)r * d);
+            orc_attention_grouped(q + (size_t)r * d, Kc, Vc, L + r + 1, H, Hkv, dh, att + (size_t)r * d);
         orc_linear(att, n, d, w->wo[l], wd, d, y);
         for (size_t i = 0; i < (size_t)n * d; ++i) x[i] += y[i];
         for (int r = 0; r < n; ++r)

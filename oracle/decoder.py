@@ -21,7 +21,7 @@ class _Cfg(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
                 ("rms_eps", C.c_double), ("rope_base", C.c_double),
-                ("w_dtype", C.c_int32), ("kv_bf16", C.c_int32)]
+                ("w_dtype", C.c_int32), ("kv_bf16", C.c_int32), ("n_kv_heads", C.c_int32)]
 
 
 class _Weights(C.Structure):
@@ -47,6 +47,8 @@ def lib():
         L.orc_rope.argtypes = [dp, C.c_int, C.c_int, C.c_int, C.c_double]
         L.orc_attention.restype = None
         L.orc_attention.argtypes = [dp, dp, dp, C.c_int, C.c_int, C.c_int, dp]
+        L.orc_attention_grouped.restype = None
+        L.orc_attention_grouped.argtypes = [dp, dp, dp, C.c_int, C.c_int, C.c_int, C.c_int, dp]
         L.orc_swiglu.restype = None
         L.orc_swiglu.argtypes = [dp, dp, C.c_int, dp]
         L.orc_argmax.restype = C.c_int32
@@ -138,6 +140,17 @@ def attention(q: np.ndarray, Kc: np.ndarray, Vc: np.ndarray, n_heads: int, head_
     return out
 
 
+def attention_grouped(q: np.ndarray, Kc: np.ndarray, Vc: np.ndarray, n_heads: int, n_kv_heads: int,
+                      head_dim: int) -> np.ndarray:
+    """Kc, Vc: [n_keys][n_kv_heads * head_dim]; query head h reads key/value head h // (n_heads // n_kv_heads)."""
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    Kc = np.ascontiguousarray(Kc, dtype=np.float64)
+    Vc = np.ascontiguousarray(Vc, dtype=np.float64)
+    out = np.empty_like(q)
+    lib().orc_attention_grouped(_dp(q), _dp(Kc), _dp(Vc), Kc.shape[0], n_heads, n_kv_heads, head_dim, _dp(out))
+    return out
+
+
 def swiglu(gate: np.ndarray, up: np.ndarray) -> np.ndarray:
     gate = np.ascontiguousarray(gate, dtype=np.float64)
     up = np.ascontiguousarray(up, dtype=np.float64)
@@ -187,7 +200,9 @@ class Decoder:
             self._arrays.append(arr)
             setattr(ws, name, C.cast(arr, C.POINTER(C.c_void_p)))
         cfg = _Cfg(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn,
-                   shape.vocab, shape.rms_eps, shape.rope_base, want, 1 if want == ORC_BF16 else 0)
+                   shape.vocab, shape.rms_eps, shape.rope_base, want, 1 if want == ORC_BF16 else 0,
+                   int(getattr(shape, "n_kv_heads", 0) or 0))
+        self.kv_dim = (cfg.n_kv_heads or shape.n_heads) * shape.head_dim
         self._ws, self._cfg = ws, cfg
         self._model = lib().orc_model_create(C.byref(cfg), C.byref(ws))
         self._kv = lib().orc_kv_create(self._model, max_tokens)
@@ -226,7 +241,7 @@ class Decoder:
             raise ValueError("kv_load out of range")
 
     def kv_read(self, layer: int, pos0: int, n: int):
-        d = self.shape.d_model
+        d = self.kv_dim
         k = np.empty((n, d), dtype=np.float64)
         v = np.empty((n, d), dtype=np.float64)
         if lib().orc_kv_read(self._kv, layer, pos0, n, _dp(k), _dp(v)) != 0:

@@ -48,7 +48,7 @@ class ModelCfg(C.Structure):
                 ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
                 ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32),
                 ("page_tokens", C.c_int32), ("max_window", C.c_int32), ("max_positions", C.c_int32),
-                ("gemm_path", C.c_int32)]
+                ("gemm_path", C.c_int32), ("n_kv_heads", C.c_int32)]
 
 
 class Weights(C.Structure):
@@ -230,7 +230,7 @@ class Model:
         want = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
         cfg = ModelCfg(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, shape.vocab,
                        shape.rms_eps, shape.rope_base, BF16 if shape.dtype == "bf16" else F32, page_tokens,
-                       max_window, max_positions, gemm_path)
+                       max_window, max_positions, gemm_path, int(getattr(shape, "n_kv_heads", 0) or 0))
         self.cfg = cfg
 
         def ptr(t):
@@ -346,14 +346,14 @@ class KVCache:
         _check(lib().anpd_kv_set_page_order(self._h, _ints(perm), len(perm)))
 
     def write(self, layer: int, pos0: int, k, v, stream=None) -> None:
-        """k, v: CUDA float32 [n][d_model]."""
+        """k, v: CUDA float32 [n][n_kv_heads * head_dim]."""
         import torch
         assert k.is_cuda and k.dtype == torch.float32 and k.is_contiguous() and v.is_contiguous()
         _check(lib().anpd_kv_write(self._h, layer, pos0, k.shape[0], k.data_ptr(), v.data_ptr(), _stream_ptr(stream)))
 
     def read(self, layer: int, pos0: int, n: int, stream=None):
         import torch
-        d = self.model.shape.d_model
+        d = (getattr(self.model.shape, "n_kv_heads", 0) or self.model.shape.n_heads) * self.model.shape.head_dim
         k = torch.empty(n, d, dtype=torch.float32, device=self.model.device)
         v = torch.empty(n, d, dtype=torch.float32, device=self.model.device)
         _check(lib().anpd_kv_read(self._h, layer, pos0, n, k.data_ptr(), v.data_ptr(), _stream_ptr(stream)))

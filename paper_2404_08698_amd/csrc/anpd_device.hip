@@ -31,6 +31,9 @@ namespace {
 
 size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+int kv_heads_of(const anpd_model_cfg &c) { return c.n_kv_heads > 0 ? c.n_kv_heads : c.n_heads; }
+int kv_dim_of(const anpd_model_cfg &c) { return kv_heads_of(c) * c.head_dim; }
+
 struct Layout {  // byte offsets into the model workspace
     size_t rope_tab, tok, tree, result, counter, x, h, y, qkv, att, gu, a, logits, part;
     // fast path: packed operands, partial sums of squares, packed weights
@@ -55,6 +58,7 @@ bool cfg_ok(const anpd_model_cfg *c, const char **why)
     REQ(c, "cfg is NULL");
     REQ(c->n_layers >= 1 && c->d_model >= 8 && c->n_heads >= 1 && c->d_ffn >= 8 && c->vocab >= 1, "non-positive dimension");
     REQ(c->n_heads * c->head_dim == c->d_model, "d_model must equal n_heads * head_dim");
+    REQ(c->n_kv_heads >= 0 && (c->n_kv_heads == 0 || c->n_heads % c->n_kv_heads == 0), "n_kv_heads must be 0 or divide n_heads");
     REQ(c->head_dim == 64 || c->head_dim == 128, "head_dim must be 64 or 128");
     REQ(c->d_model % 16 == 0 && c->d_ffn % 16 == 0 && c->vocab % 16 == 0, "d_model, d_ffn and vocab must be multiples of 16");
     REQ(c->dtype == ANPD_F32 || c->dtype == ANPD_BF16, "dtype must be ANPD_F32 or ANPD_BF16");
@@ -75,6 +79,7 @@ Layout make_layout(const anpd_model_cfg *c)
 {
     Layout L;
     const size_t MW = (size_t)c->max_window, d = (size_t)c->d_model, F = (size_t)c->d_ffn, V = (size_t)c->vocab;
+    const size_t kvd = (size_t)kv_dim_of(*c);
     L.max_splits = (c->max_positions + kAttnSplit - 1) / kAttnSplit + 1;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
@@ -86,7 +91,7 @@ Layout make_layout(const anpd_model_cfg *c)
     L.x = take(MW * d * 4);
     L.h = take(MW * d * 4);
     L.y = take(MW * d * 4);
-    L.qkv = take(MW * 3 * d * 4);
+    L.qkv = take(MW * (d + 2 * kvd) * 4);
     L.att = take(MW * d * 4);
     L.gu = take(MW * 2 * F * 4);
     L.a = take(MW * F * 4);
@@ -108,7 +113,7 @@ Layout make_layout(const anpd_model_cfg *c)
         L.bar = take(kBarStride * 9 * sizeof(uint32_t) + (size_t)c->n_heads * kCounterStride * sizeof(uint32_t));   // barrier words, then per-head QKV counters
         L.wp_lm = take(packed_bytes(V / 16, (int)d));
         for (int l = 0; l < c->n_layers; ++l) {
-            L.wp_qkv.push_back(take(packed_bytes(3 * d / 16, (int)d)));
+            L.wp_qkv.push_back(take(packed_bytes((d + 2 * kvd) / 16, (int)d)));
             L.wp_o.push_back(take(packed_bytes(d / 16, (int)d)));
             L.wp_gu.push_back(take(packed_bytes(F / 8, (int)d)));
             L.wp_down.push_back(take(packed_bytes(d / 16, (int)F)));
@@ -189,23 +194,24 @@ namespace {
 
 size_t page_bytes_of(const anpd_model_cfg &c)
 {
-    return (size_t)c.n_layers * 2 * c.d_model * c.page_tokens * (c.dtype == ANPD_BF16 ? 2 : 4);
+    return (size_t)c.n_layers * 2 * kv_dim_of(c) * c.page_tokens * (c.dtype == ANPD_BF16 ? 2 : 4);
 }
 
 // ---- GEMM dispatch -----------------------------------------------------------
 
-int32_t launch_gemm_dot(const float *X, int M, int K, const void *W0, const void *W1, const void *W2, int nseg,
-                        int n_seg, float *Y, int ldy, int dtype, hipStream_t st)
+// Up to three weight matrices side by side: n0 rows of W0, n1 of W1 (0 if absent), n2 of W2.
+int32_t launch_gemm_dot(const float *X, int M, int K, const void *W0, const void *W1, const void *W2, int n0, int n1,
+                        int n2, float *Y, int ldy, int dtype, hipStream_t st)
 {
     constexpr int R = 4;
-    int n_total = nseg * n_seg;
+    int n_total = n0 + n1 + n2;
     dim3 grid((unsigned)((n_total + 4 * R - 1) / (4 * R)));
     if (dtype == ANPD_BF16)
         hipLaunchKernelGGL((gemm_dot_kernel<bf16_t, R>), grid, dim3(256), 0, st, X, M, K, (const bf16_t *)W0,
-                           (const bf16_t *)W1, (const bf16_t *)W2, n_seg, n_total, Y, ldy);
+                           (const bf16_t *)W1, (const bf16_t *)W2, n0, n1, n_total, Y, ldy);
     else
         hipLaunchKernelGGL((gemm_dot_kernel<float, R>), grid, dim3(256), 0, st, X, M, K, (const float *)W0,
-                           (const float *)W1, (const float *)W2, n_seg, n_total, Y, ldy);
+                           (const float *)W1, (const float *)W2, n0, n1, n_total, Y, ldy);
     HIP_TRY(hipGetLastError());
     return ANPD_OK;
 }
@@ -260,12 +266,12 @@ int32_t launch_fast(FastArgs &a, int n_cu, bool force_stream, hipStream_t st)
 }
 
 int32_t launch_pack(const void *s0, const void *s1, const void *s2, void *dst, int mode, int n_tiles, int K, int d,
-                    int head_dim, hipStream_t st)
+                    int head_dim, int kvd, hipStream_t st)
 {
     const int nks = (K + 31) / 32;
     size_t total = (size_t)n_tiles * nks * 64;
     hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const bf16_t *)s0,
-                       (const bf16_t *)s1, (const bf16_t *)s2, (uint4 *)dst, mode, n_tiles, K, nks, d, head_dim);
+                       (const bf16_t *)s1, (const bf16_t *)s2, (uint4 *)dst, mode, n_tiles, K, nks, d, head_dim, kvd);
     HIP_TRY(hipGetLastError());
     return ANPD_OK;
 }
@@ -346,6 +352,7 @@ int32_t run_step_generic(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_
     const Layout &L = m->lay;
     char *ws = m->ws;
     const int d = c.d_model, F = c.d_ffn, V = c.vocab, H = c.n_heads, dh = c.head_dim;
+    const int Hkv = kv_heads_of(c), kvd = kv_dim_of(c);
     float *x = (float *)(ws + L.x), *h = (float *)(ws + L.h), *y = (float *)(ws + L.y);
     float *qkv = (float *)(ws + L.qkv), *att = (float *)(ws + L.att), *gu = (float *)(ws + L.gu);
     float *a = (float *)(ws + L.a), *logits = (float *)(ws + L.logits), *part = (float *)(ws + L.part);
@@ -367,46 +374,46 @@ int32_t run_step_generic(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_
         hipLaunchKernelGGL((addnorm_kernel<KT>), dim3(M), dim3(256), 0, st, x, l == 0 ? (const float *)nullptr : y,
                            (const KT *)m->attn_norm[l], h, d, c.rms_eps);
         mark(m, ANPD_PROF_OTHER, st);
-        if ((rc = launch_gemm_dot(h, M, d, m->wq[l], m->wk[l], m->wv[l], 3, d, qkv, 3 * d, c.dtype, st)) != ANPD_OK) return rc;
+        if ((rc = launch_gemm_dot(h, M, d, m->wq[l], m->wk[l], m->wv[l], d, kvd, kvd, qkv, d + 2 * kvd, c.dtype, st)) != ANPD_OK) return rc;
         mark(m, ANPD_PROF_GEMM_QKV, st);
         hipLaunchKernelGGL((rope_kv_kernel<KT>), dim3(M), dim3(256), 0, st, qkv, rope, pool, kv->d_table, kv->d_len, l,
-                           c.n_layers, H, dh, c.page_tokens, t_depth);
+                           c.n_layers, H, Hkv, dh, c.page_tokens, t_depth);
         mark(m, ANPD_PROF_OTHER, st);
         if (dh == 128) {
-            hipLaunchKernelGGL((attn_kernel<KT, 128>), dim3(H, n_splits), dim3(256), 0, st, qkv, 3 * d, pool, kv->d_table,
-                               kv->d_len, M, l, c.n_layers, H, c.page_tokens, c.max_window, L.max_splits, scale, part, t_mask);
+            hipLaunchKernelGGL((attn_kernel<KT, 128>), dim3(H, n_splits), dim3(256), 0, st, qkv, d + 2 * kvd, pool, kv->d_table,
+                               kv->d_len, M, l, c.n_layers, H, Hkv, c.page_tokens, c.max_window, L.max_splits, scale, part, t_mask);
             hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(M, H), dim3(128), 0, st, part, kv->d_len, H,
                                c.max_window, L.max_splits, att, (bf16_t *)nullptr, 8);
         } else {
-            hipLaunchKernelGGL((attn_kernel<KT, 64>), dim3(H, n_splits), dim3(256), 0, st, qkv, 3 * d, pool, kv->d_table,
-                               kv->d_len, M, l, c.n_layers, H, c.page_tokens, c.max_window, L.max_splits, scale, part, t_mask);
+            hipLaunchKernelGGL((attn_kernel<KT, 64>), dim3(H, n_splits), dim3(256), 0, st, qkv, d + 2 * kvd, pool, kv->d_table,
+                               kv->d_len, M, l, c.n_layers, H, Hkv, c.page_tokens, c.max_window, L.max_splits, scale, part, t_mask);
             hipLaunchKernelGGL((attn_combine_kernel<64>), dim3(M, H), dim3(64), 0, st, part, kv->d_len, H, c.max_window,
                                L.max_splits, att, (bf16_t *)nullptr, 8);
         }
         mark(m, ANPD_PROF_ATTN, st);
-        if ((rc = launch_gemm_dot(att, M, d, m->wo[l], nullptr, nullptr, 1, d, y, d, c.dtype, st)) != ANPD_OK) return rc;
+        if ((rc = launch_gemm_dot(att, M, d, m->wo[l], nullptr, nullptr, d, 0, 0, y, d, c.dtype, st)) != ANPD_OK) return rc;
         mark(m, ANPD_PROF_GEMM_O, st);
         hipLaunchKernelGGL((addnorm_kernel<KT>), dim3(M), dim3(256), 0, st, x, y, (const KT *)m->ffn_norm[l], h, d,
                            c.rms_eps);
         mark(m, ANPD_PROF_OTHER, st);
-        if ((rc = launch_gemm_dot(h, M, d, m->w_gate[l], m->w_up[l], nullptr, 2, F, gu, 2 * F, c.dtype, st)) != ANPD_OK) return rc;
+        if ((rc = launch_gemm_dot(h, M, d, m->w_gate[l], m->w_up[l], nullptr, F, F, 0, gu, 2 * F, c.dtype, st)) != ANPD_OK) return rc;
         mark(m, ANPD_PROF_GEMM_GATE_UP, st);
         hipLaunchKernelGGL(swiglu_kernel, dim3((F + 255) / 256, M), dim3(256), 0, st, gu, a, F);
         mark(m, ANPD_PROF_OTHER, st);
-        if ((rc = launch_gemm_dot(a, M, F, m->w_down[l], nullptr, nullptr, 1, d, y, d, c.dtype, st)) != ANPD_OK) return rc;
+        if ((rc = launch_gemm_dot(a, M, F, m->w_down[l], nullptr, nullptr, d, 0, 0, y, d, c.dtype, st)) != ANPD_OK) return rc;
         mark(m, ANPD_PROF_GEMM_DOWN, st);
     }
     hipLaunchKernelGGL((addnorm_kernel<KT>), dim3(M), dim3(256), 0, st, x, y, (const KT *)m->final_norm, h, d,
                        c.rms_eps);
     mark(m, ANPD_PROF_OTHER, st);
-    if ((rc = launch_gemm_dot(h, M, d, m->lm_head, nullptr, nullptr, 1, V, logits, V, c.dtype, st)) != ANPD_OK) return rc;
+    if ((rc = launch_gemm_dot(h, M, d, m->lm_head, nullptr, nullptr, V, 0, 0, logits, V, c.dtype, st)) != ANPD_OK) return rc;
     mark(m, ANPD_PROF_GEMM_LM_HEAD, st);
     hipLaunchKernelGGL(argmax_accept_kernel, dim3(M), dim3(1024), 0, st, logits, V, M, tok, mode, result, kv->d_len,
                        counter);
     if (tree) {
         hipLaunchKernelGGL(accept_tree_kernel, dim3(1), dim3(64), 0, st, tok, t_parent, t_depth, M, result, kv->d_len, kv->len);
-        hipLaunchKernelGGL((kv_compact_kernel<KT>), dim3((unsigned)(c.n_layers * 2 * H)), dim3(128), 0, st, pool, kv->d_table,
-                           (const int32_t *)result, kv->len, c.n_layers, H, dh, c.page_tokens);
+        hipLaunchKernelGGL((kv_compact_kernel<KT>), dim3((unsigned)(c.n_layers * 2 * Hkv)), dim3(128), 0, st, pool, kv->d_table,
+                           (const int32_t *)result, kv->len, c.n_layers, Hkv, dh, c.page_tokens);
     }
     mark(m, ANPD_PROF_OTHER, st);
     HIP_TRY(hipGetLastError());
@@ -421,6 +428,7 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
     const Layout &L = m->lay;
     char *ws = m->ws;
     const int d = c.d_model, F = c.d_ffn, V = c.vocab, H = c.n_heads, dh = c.head_dim;
+    const int Hkv = kv_heads_of(c), kvd = kv_dim_of(c);
     const int cls = window_class(M);
     float *x = (float *)(ws + L.x);
     float *logits = (float *)(ws + L.logits), *part = (float *)(ws + L.part);
@@ -453,6 +461,7 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
     base.rope = (const float2 *)(ws + L.rope_tab);
     base.n_layers = c.n_layers;
     base.n_heads = H;
+    base.n_kv_heads = Hkv;
     base.head_dim = dh;
 
     m->ev_used = 0;
@@ -471,7 +480,7 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
             a.Wp = (const uint4 *)(ws + L.wp_qkv[(size_t)l]);
             a.Xp = (const uint4 *)xp_d;
             a.nks = nks_d;
-            a.n_tiles = 3 * d / 16;
+            a.n_tiles = (d + 2 * kvd) / 16;
             a.ssp = ssp_a;
             a.qp = qp;
             a.layer = l;
@@ -482,7 +491,7 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
         mark(m, ANPD_PROF_GEMM_QKV, st);
 #define ANPD_ATTN(DH_, TREE_)                                                                                              \
     hipLaunchKernelGGL((attn_fast_kernel<DH_, TREE_>), dim3(H, n_splits), dim3(kFastThreads), 0, st, (const uint4 *)qp,  \
-                       (const bf16_t *)kv->pool, kv->d_table, kv->d_len, M, l, c.n_layers, H, L.max_splits, scale, part,   \
+                       (const bf16_t *)kv->pool, kv->d_table, kv->d_len, M, l, c.n_layers, H, Hkv, L.max_splits, scale, part,   \
                        head_ctr, xp_att, cls, t_mask)
         if (dh == 128) { if (tree) ANPD_ATTN(128, true); else ANPD_ATTN(128, false); }
         else { if (tree) ANPD_ATTN(64, true); else ANPD_ATTN(64, false); }
@@ -540,8 +549,8 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
                        counter);
     if (tree) {
         hipLaunchKernelGGL(accept_tree_kernel, dim3(1), dim3(64), 0, st, tok, t_parent, t_depth, M, result, kv->d_len, kv->len);
-        hipLaunchKernelGGL(kvf_compact_kernel, dim3((unsigned)(c.n_layers * 2 * H)), dim3(128), 0, st, (bf16_t *)kv->pool,
-                           kv->d_table, (const int32_t *)result, kv->len, c.n_layers, H, dh);
+        hipLaunchKernelGGL(kvf_compact_kernel, dim3((unsigned)(c.n_layers * 2 * Hkv)), dim3(128), 0, st, (bf16_t *)kv->pool,
+                           kv->d_table, (const int32_t *)result, kv->len, c.n_layers, Hkv, dh);
     }
     mark(m, ANPD_PROF_OTHER, st);
     HIP_TRY(hipGetLastError());
@@ -563,7 +572,7 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, 
     g.wp_lm = (const uint4 *)(ws + L.wp_lm);
     g.final_gain = (const bf16_t *)m->final_norm;
     g.embed = (const bf16_t *)m->embed;
-    g.d = c.d_model; g.F = c.d_ffn; g.V = c.vocab; g.n_heads = c.n_heads; g.head_dim = c.head_dim;
+    g.d = c.d_model; g.F = c.d_ffn; g.V = c.vocab; g.n_heads = c.n_heads; g.n_kv_heads = kv_heads_of(c); g.head_dim = c.head_dim;
     g.M = M; g.mode = mode;
     g.inv_d = 1.0f / (float)c.d_model; g.eps = c.rms_eps; g.scale = 1.0f / sqrtf((float)c.head_dim);
     g.x = (float *)(ws + L.x);
@@ -608,8 +617,8 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, 
     m->ready_epoch += (uint32_t)c.n_layers;
     if (tree) {
         // the winning path's K and V to consecutive positions (a no-op kernel when it is the first candidate)
-        hipLaunchKernelGGL(kvf_compact_kernel, dim3((unsigned)(c.n_layers * 2 * c.n_heads)), dim3(128), 0, st, (bf16_t *)kv->pool,
-                           kv->d_table, (const int32_t *)(ws + L.result), kv->len, c.n_layers, c.n_heads, c.head_dim);
+        hipLaunchKernelGGL(kvf_compact_kernel, dim3((unsigned)(c.n_layers * 2 * kv_heads_of(c))), dim3(128), 0, st, (bf16_t *)kv->pool,
+                           kv->d_table, (const int32_t *)(ws + L.result), kv->len, c.n_layers, kv_heads_of(c), c.head_dim);
         HIP_TRY(hipGetLastError());
     }
     mark(m, ANPD_PROF_STEP, st);
@@ -664,6 +673,7 @@ int32_t run_prefill_mfma(anpd_model *m, anpd_kv *kv, int P, char *pws, const Pre
     base.rope = (const float2 *)(ws + L.rope_tab);
     base.n_layers = c.n_layers;
     base.n_heads = H;
+    base.n_kv_heads = kv_heads_of(c);
     base.head_dim = dh;
 
     m->ev_used = 0;
@@ -679,17 +689,17 @@ int32_t run_prefill_mfma(anpd_model *m, anpd_kv *kv, int P, char *pws, const Pre
             a.Wp = (const uint4 *)(ws + L.wp_qkv[(size_t)l]);
             a.Xq = (const uint4 *)xq;
             a.nks = nks_d;
-            a.n_tiles = 3 * d / 16;
+            a.n_tiles = (d + 2 * kv_dim_of(c)) / 16;
             a.layer = l;
             if ((rc = launch_prefill_gemm<EPI_QKV>(a, st)) != ANPD_OK) return rc;
         }
         mark(m, ANPD_PROF_GEMM_QKV, st);
         if (dh == 128)
             hipLaunchKernelGGL((prefill_attn_kernel<128>), dim3((unsigned)H, (unsigned)((G + 3) / 4)), dim3(256), 0, st, (const uint4 *)qp,
-                               (const bf16_t *)kv->pool, kv->d_table, G, len, P, l, c.n_layers, H, scale, xq_att, nks_d);
+                               (const bf16_t *)kv->pool, kv->d_table, G, len, P, l, c.n_layers, H, kv_heads_of(c), scale, xq_att, nks_d);
         else
             hipLaunchKernelGGL((prefill_attn_kernel<64>), dim3((unsigned)H, (unsigned)((G + 3) / 4)), dim3(256), 0, st, (const uint4 *)qp,
-                               (const bf16_t *)kv->pool, kv->d_table, G, len, P, l, c.n_layers, H, scale, xq_att, nks_d);
+                               (const bf16_t *)kv->pool, kv->d_table, G, len, P, l, c.n_layers, H, kv_heads_of(c), scale, xq_att, nks_d);
         mark(m, ANPD_PROF_ATTN, st);
         {
             PrefillArgs a = base;
@@ -903,14 +913,14 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
     }
     if (e == hipSuccess && m->mfma) {
         // repack every matrix into MFMA-fragment order inside the workspace
-        const int d = cfg->d_model, F = cfg->d_ffn, dh = cfg->head_dim;
+        const int d = cfg->d_model, F = cfg->d_ffn, dh = cfg->head_dim, kvd = kv_dim_of(*cfg);
         for (int l = 0; l < cfg->n_layers && prc == ANPD_OK; ++l) {
-            prc = launch_pack(m->wq[l], m->wk[l], m->wv[l], m->ws + lay.wp_qkv[(size_t)l], PACK_QKV, 3 * d / 16, d, d, dh, st);
-            if (prc == ANPD_OK) prc = launch_pack(m->wo[l], nullptr, nullptr, m->ws + lay.wp_o[(size_t)l], PACK_PLAIN, d / 16, d, d, dh, st);
-            if (prc == ANPD_OK) prc = launch_pack(m->w_gate[l], m->w_up[l], nullptr, m->ws + lay.wp_gu[(size_t)l], PACK_GATE_UP, F / 8, d, d, dh, st);
-            if (prc == ANPD_OK) prc = launch_pack(m->w_down[l], nullptr, nullptr, m->ws + lay.wp_down[(size_t)l], PACK_PLAIN, d / 16, F, d, dh, st);
+            prc = launch_pack(m->wq[l], m->wk[l], m->wv[l], m->ws + lay.wp_qkv[(size_t)l], PACK_QKV, (d + 2 * kvd) / 16, d, d, dh, kvd, st);
+            if (prc == ANPD_OK) prc = launch_pack(m->wo[l], nullptr, nullptr, m->ws + lay.wp_o[(size_t)l], PACK_PLAIN, d / 16, d, d, dh, kvd, st);
+            if (prc == ANPD_OK) prc = launch_pack(m->w_gate[l], m->w_up[l], nullptr, m->ws + lay.wp_gu[(size_t)l], PACK_GATE_UP, F / 8, d, d, dh, kvd, st);
+            if (prc == ANPD_OK) prc = launch_pack(m->w_down[l], nullptr, nullptr, m->ws + lay.wp_down[(size_t)l], PACK_PLAIN, d / 16, F, d, dh, kvd, st);
         }
-        if (prc == ANPD_OK) prc = launch_pack(m->lm_head, nullptr, nullptr, m->ws + lay.wp_lm, PACK_PLAIN, cfg->vocab / 16, d, d, dh, st);
+        if (prc == ANPD_OK) prc = launch_pack(m->lm_head, nullptr, nullptr, m->ws + lay.wp_lm, PACK_PLAIN, cfg->vocab / 16, d, d, dh, kvd, st);
     }
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess || prc != ANPD_OK) {
@@ -1078,14 +1088,14 @@ static int32_t kv_copy(anpd_kv *kv, int32_t layer, int32_t pos0, int32_t n, floa
     }
 #define KV_COPY(KT, TO)                                                                                          \
     hipLaunchKernelGGL((kv_copy_kernel<KT, TO>), dim3(n), dim3(256), 0, st, (KT *)kv->pool, kv->d_table, k, v, pos0, \
-                       layer, c.n_layers, c.n_heads, c.head_dim, c.page_tokens)
+                       layer, c.n_layers, kv_heads_of(c), c.head_dim, c.page_tokens)
     if (kv->m->mfma) {
         if (to_cache)
             hipLaunchKernelGGL((kvf_copy_kernel<true>), dim3(n), dim3(256), 0, st, (bf16_t *)kv->pool, kv->d_table, k, v, pos0,
-                               layer, c.n_layers, c.n_heads, c.head_dim);
+                               layer, c.n_layers, kv_heads_of(c), c.head_dim);
         else
             hipLaunchKernelGGL((kvf_copy_kernel<false>), dim3(n), dim3(256), 0, st, (bf16_t *)kv->pool, kv->d_table, k, v, pos0,
-                               layer, c.n_layers, c.n_heads, c.head_dim);
+                               layer, c.n_layers, kv_heads_of(c), c.head_dim);
     } else if (c.dtype == ANPD_BF16) { if (to_cache) KV_COPY(bf16_t, true); else KV_COPY(bf16_t, false); }
     else { if (to_cache) KV_COPY(float, true); else KV_COPY(float, false); }
 #undef KV_COPY
@@ -1294,7 +1304,7 @@ int32_t anpd_pack_weights(const void *W, int32_t N, int32_t K, void *packed, siz
     size_t need = anpd_packed_bytes(N, K);
     if (need == 0) return fail(ANPD_E_INVAL, "anpd_pack_weights: need N %% 16 == 0 and K %% 8 == 0");
     if (packed_bytes_given < need) return fail(ANPD_E_CAPACITY, "anpd_pack_weights: buffer has %zu bytes, %zu needed", packed_bytes_given, need);
-    return launch_pack(W, nullptr, nullptr, packed, PACK_PLAIN, N / 16, K, 0, 0, (hipStream_t)stream);
+    return launch_pack(W, nullptr, nullptr, packed, PACK_PLAIN, N / 16, K, 0, 0, 0, (hipStream_t)stream);
 }
 
 int32_t anpd_linear(const float *X, const void *W, float *Y, int32_t M, int32_t N, int32_t K, int32_t dtype,
@@ -1305,7 +1315,7 @@ int32_t anpd_linear(const float *X, const void *W, float *Y, int32_t M, int32_t 
         return fail(ANPD_E_INVAL, "anpd_linear: need 1 <= M <= %d, K %% 8 == 0, N %% 16 == 0", ANPD_MAX_WINDOW);
     if (dtype != ANPD_F32 && dtype != ANPD_BF16) return fail(ANPD_E_INVAL, "anpd_linear: unknown dtype");
     hipStream_t st = (hipStream_t)stream;
-    if (path == ANPD_GEMM_DOT) return launch_gemm_dot(X, M, K, W, nullptr, nullptr, 1, N, Y, N, dtype, st);
+    if (path == ANPD_GEMM_DOT) return launch_gemm_dot(X, M, K, W, nullptr, nullptr, N, 0, 0, Y, N, dtype, st);
     if (path != ANPD_GEMM_MFMA && path != ANPD_GEMM_MFMA_STREAM)
         return fail(ANPD_E_INVAL, "anpd_linear: unknown path %d", path);
     if (dtype != ANPD_BF16) return fail(ANPD_E_INVAL, "anpd_linear: the MFMA path needs bf16 weights");

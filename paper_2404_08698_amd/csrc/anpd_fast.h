@@ -80,12 +80,13 @@ enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
 
 // One thread per 16-byte fragment slot of the packed matrix.
 // PLAIN:   tile t row r = src0 row 16 t + r.
-// QKV:     tiles [0,T) from src0 (q), [T,2T) from src1 (k), [2T,3T) from src2 (v), T = d / 16;
+// QKV:     tiles [0,Tq) from src0 (q), [Tq,Tq+Tkv) from src1 (k), then Tkv from src2 (v), Tq = d / 16,
+//          Tkv = kvd / 16 (kvd = key / value heads x head_dim);
 //          q/k tile (head h, j): row r < 8 -> dim 8j + r, r >= 8 -> dim head_dim/2 + 8j + r - 8.
 // GATE_UP: tile t row r < 8 -> src0 (gate) row 8t + r, r >= 8 -> src1 (up) row 8t + r - 8.
 __global__ __launch_bounds__(256) void pack_kernel(const bf16_t *__restrict__ src0, const bf16_t *__restrict__ src1,
                                                     const bf16_t *__restrict__ src2, uint4 *__restrict__ dst, int mode,
-                                                    int n_tiles, int K, int nks, int d, int head_dim)
+                                                    int n_tiles, int K, int nks, int d, int head_dim, int kvd)
 {
     size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     size_t total = (size_t)n_tiles * nks * 64;
@@ -99,7 +100,8 @@ __global__ __launch_bounds__(256) void pack_kernel(const bf16_t *__restrict__ sr
     if (mode == PACK_PLAIN) {
         row = tile * 16 + r;
     } else if (mode == PACK_QKV) {
-        int T = d / 16, which = tile / T, t = tile - which * T;
+        int Tq = d / 16, Tkv = kvd / 16;
+        int which = tile < Tq ? 0 : (tile < Tq + Tkv ? 1 : 2), t = tile - (which == 0 ? 0 : (which == 1 ? Tq : Tq + Tkv));
         src = which == 0 ? src0 : (which == 1 ? src1 : src2);
         if (which < 2) {
             int tph = head_dim / 16, h = t / tph, j = t - h * tph;
@@ -143,6 +145,7 @@ struct FastArgs {
     const int32_t *page_table, *len_ptr;
     const float2 *rope;
     int layer, n_layers, n_heads, head_dim;
+    int n_kv_heads;       // key / value heads (query head h reads head h / (n_heads / n_kv_heads))
     // RESIDUAL
     float *x;             // residual stream fp32 [M][d], updated in place
     const bf16_t *gain;   // gain of the norm that follows
@@ -254,8 +257,8 @@ __device__ __forceinline__ void epilogue_preload(const FastArgs &a, int tile, in
                             __uint_as_float(gb.y & 0xffff0000u)};
         }
     } else if (epi_is_qkv(EPI)) {
-        const int T = a.n_heads * a.head_dim / 16;
-        const int which = tile / T, t = tile - which * T;
+        const int Tq = a.n_heads * a.head_dim / 16, Tkv = a.n_kv_heads * a.head_dim / 16;
+        const int which = tile < Tq ? 0 : (tile < Tq + Tkv ? 1 : 2), t = tile - (which == 0 ? 0 : (which == 1 ? Tq : Tq + Tkv));
         const int pos = *a.len_ptr + m;
         pre.page = 0;
 #pragma unroll
@@ -328,8 +331,8 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
     } else if (epi_is_qkv(EPI)) {
         const float r = valid ? rinv[m] : 0.f;
         y = y * r;
-        const int T = a.n_heads * a.head_dim / 16;
-        const int which = tile / T, t = tile - which * T;
+        const int Tq = a.n_heads * a.head_dim / 16, Tkv = a.n_kv_heads * a.head_dim / 16;
+        const int which = tile < Tq ? 0 : (tile < Tq + Tkv ? 1 : 2), t = tile - (which == 0 ? 0 : (which == 1 ? Tq : Tq + Tkv));
         const int pos = *a.len_ptr + m;   // the row's cache slot
         f32x4 other;
 #pragma unroll
@@ -360,13 +363,13 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
                 stc8<COH>(a.qp + qp_offset(h, a.head_dim, m, dim, 1),
                           make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)));
             } else {
-                bf16_t *dst = a.pool + kvf_base(page, a.layer, a.n_layers, 0, h, a.n_heads, a.head_dim) + kf_elem(tok, dim);
+                bf16_t *dst = a.pool + kvf_base(page, a.layer, a.n_layers, 0, h, a.n_kv_heads, a.head_dim) + kf_elem(tok, dim);
                 stc8<COH>(dst, make_uint2((uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16),
                                           (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16)));
             }
         } else {
             const int n = t * 16 + 4 * kg, h = n / a.head_dim, dim = n - h * a.head_dim;
-            bf16_t *dst = a.pool + kvf_base(page, a.layer, a.n_layers, 1, h, a.n_heads, a.head_dim);
+            bf16_t *dst = a.pool + kvf_base(page, a.layer, a.n_layers, 1, h, a.n_kv_heads, a.head_dim);
 #pragma unroll
             for (int i = 0; i < 4; ++i) stc2<COH>(dst + vf_elem(tok, dim + i), f32_to_bf16(y[i]));
         }
@@ -709,6 +712,7 @@ struct AttnKV {
 // Requests the wave's K / V page.  With only_old, only a page that lies wholly below position L:
 // such a page was written by earlier steps, so the persistent kernel can request it before the
 // barrier that ends the QKV phase (the window's own rows are written in that phase).
+// `head` is the key / value head, one of n_kv_heads.
 template <int DH, bool COH>
 __device__ __forceinline__ void attn_load_kv(AttnKV<DH> &kv, int head, int split, int L, int M,
                                              const bf16_t *__restrict__ pool, const int32_t *__restrict__ page_table,
@@ -756,7 +760,7 @@ template <int DH, bool COH = false, typename AfterLoads = NoPrefetch, bool TREE 
 __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, int head, int split, int L,
                                           const uint4 *__restrict__ qp, const bf16_t *__restrict__ pool,
                                           const int32_t *__restrict__ page_table, int M, int layer, int n_layers, int n_heads,
-                                          int max_splits, float scale, float *__restrict__ part,
+                                          int n_kv_heads, int max_splits, float scale, float *__restrict__ part,
                                           uint32_t *__restrict__ head_counter, bf16_t *__restrict__ xp_att, int cls,
                                           AfterLoads after_loads = AfterLoads(), const uint32_t *__restrict__ row_mask = nullptr)
 {
@@ -767,7 +771,8 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
     const bool active = key0 < L + M;
     ANPD_STAMP(0);
 
-    if (!kv.loaded) attn_load_kv<DH, COH>(kv, head, split, L, M, pool, page_table, layer, n_layers, n_heads, false);
+    if (!kv.loaded)
+        attn_load_kv<DH, COH>(kv, head / (n_heads / n_kv_heads), split, L, M, pool, page_table, layer, n_layers, n_kv_heads, false);
     uint4 qf[NKS];
     {
         const uint4 *q = qp + ((size_t)(head * 4) * NKS) * 64;
@@ -945,9 +950,10 @@ template <int DH, bool TREE = false>
 __global__ __launch_bounds__(kFastThreads) void attn_fast_kernel(const uint4 *__restrict__ qp, const bf16_t *__restrict__ pool,
                                                           const int32_t *__restrict__ page_table,
                                                           const int32_t *__restrict__ len_ptr, int M, int layer, int n_layers,
-                                                          int n_heads, int max_splits, float scale, float *__restrict__ part,
-                                                          uint32_t *__restrict__ head_counter, bf16_t *__restrict__ xp_att,
-                                                          int cls, const uint32_t *__restrict__ row_mask)
+                                                          int n_heads, int n_kv_heads, int max_splits, float scale,
+                                                          float *__restrict__ part, uint32_t *__restrict__ head_counter,
+                                                          bf16_t *__restrict__ xp_att, int cls,
+                                                          const uint32_t *__restrict__ row_mask)
 {
     __shared__ AttnShared<DH> sh;
     const int L = *len_ptr;
@@ -955,7 +961,7 @@ __global__ __launch_bounds__(kFastThreads) void attn_fast_kernel(const uint4 *__
     AttnKV<DH> kv;
     kv.loaded = false;
     attn_task<DH, false, NoPrefetch, TREE>(sh, kv, blockIdx.x, blockIdx.y, L, qp, pool, page_table, M, layer, n_layers, n_heads,
-                                           max_splits, scale, part, head_counter, xp_att, cls, NoPrefetch(), row_mask);
+                                           n_kv_heads, max_splits, scale, part, head_counter, xp_att, cls, NoPrefetch(), row_mask);
 }
 
 // After a draft tree has been verified: the accepted path's rows path[1..a] sit in cache slots

@@ -263,19 +263,20 @@ __global__ __launch_bounds__(256) void addnorm_kernel(float *__restrict__ x, con
 // load of bf16 weights per lane per row), multiply against the fp32 rows of X
 // and finish with a butterfly sum over the lanes.  Exact fp32 products, fp32
 // accumulation.  The weight matrix may be given as up to three row segments
-// (Wq|Wk|Wv or Wgate|Wup) of n_seg rows each, written side by side into Y.
-// grid: (nseg * n_seg) / (4 * R) blocks of 4 waves.
+// (Wq|Wk|Wv or Wgate|Wup) of n_seg0, n_seg1 and the remaining rows (multiples of
+// R), written side by side into Y.
+// grid: n_total / (4 * R) blocks of 4 waves.
 template <typename WT, int R>
 __global__ __launch_bounds__(256) void gemm_dot_kernel(const float *__restrict__ X, int M, int K,
                                                         const WT *__restrict__ W0, const WT *__restrict__ W1,
-                                                        const WT *__restrict__ W2, int n_seg, int n_total,
+                                                        const WT *__restrict__ W2, int n_seg0, int n_seg1, int n_total,
                                                         float *__restrict__ Y, int ldy)
 {
     const int lane = threadIdx.x & 63;
     const int n0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * R;
     if (n0 >= n_total) return;
-    const int seg = n0 / n_seg;
-    const WT *W = (seg == 0 ? W0 : (seg == 1 ? W1 : W2)) + (size_t)(n0 - seg * n_seg) * K;
+    const int seg = n0 < n_seg0 ? 0 : (n0 < n_seg0 + n_seg1 ? 1 : 2);
+    const WT *W = (seg == 0 ? W0 : (seg == 1 ? W1 : W2)) + (size_t)(n0 - (seg == 0 ? 0 : (seg == 1 ? n_seg0 : n_seg0 + n_seg1))) * K;
 
     for (int m0 = 0; m0 < M; m0 += 8) {
         float acc[R][8];
@@ -320,6 +321,7 @@ __device__ __forceinline__ size_t kv_offset(int page, int layer, int n_layers, i
            (size_t)tok_in_page * head_dim;
 }
 
+// A row of the fused qkv buffer is [q: n_heads * head_dim | k: n_kv_heads * head_dim | v: the same].
 // Rotates q (in place, in the fused qkv buffer) and k by the row's absolute
 // position len + r, pair (i, i + head_dim/2) by angle pos * base^(-2i/head_dim)
 // (cos/sin from a table computed in double on the host), and writes k and v of
@@ -328,14 +330,14 @@ template <typename KT>
 __global__ __launch_bounds__(256) void rope_kv_kernel(float *__restrict__ qkv, const float2 *__restrict__ rope_tab,
                                                        KT *__restrict__ pool, const int32_t *__restrict__ page_table,
                                                        const int32_t *__restrict__ len_ptr, int layer, int n_layers,
-                                                       int n_heads, int head_dim, int page_tokens,
+                                                       int n_heads, int n_kv_heads, int head_dim, int page_tokens,
                                                        const int32_t *__restrict__ depth /* draft tree: nullable */)
 {
-    const int r = blockIdx.x, d = n_heads * head_dim, half = head_dim >> 1;
+    const int r = blockIdx.x, d = n_heads * head_dim, dkv = n_kv_heads * head_dim, half = head_dim >> 1;
     const int pos = *len_ptr + r;                              // the row's cache slot
     const int rpos = depth ? *len_ptr + depth[r] : pos;        // the row's rotary position
     const int page = page_table[pos / page_tokens], tip = pos % page_tokens;
-    float *q = qkv + (size_t)r * 3 * d, *k = q + d, *v = q + 2 * d;
+    float *q = qkv + (size_t)r * (d + 2 * dkv), *k = q + d, *v = k + dkv;
     for (int idx = threadIdx.x; idx < n_heads * half; idx += 256) {
         int hd = idx / half, i = idx - hd * half;
         float2 cs = rope_tab[(size_t)rpos * half + i];
@@ -343,9 +345,10 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(float *__restrict__ qkv, c
         float qa = q[e0], qb = q[e1];
         q[e0] = qa * cs.x - qb * cs.y;
         q[e1] = qb * cs.x + qa * cs.y;
+        if (hd >= n_kv_heads) continue;
         float ka = k[e0], kb = k[e1];
-        size_t ko = kv_offset(page, layer, n_layers, 0, hd, n_heads, tip, page_tokens, head_dim);
-        size_t vo = kv_offset(page, layer, n_layers, 1, hd, n_heads, tip, page_tokens, head_dim);
+        size_t ko = kv_offset(page, layer, n_layers, 0, hd, n_kv_heads, tip, page_tokens, head_dim);
+        size_t vo = kv_offset(page, layer, n_layers, 1, hd, n_kv_heads, tip, page_tokens, head_dim);
         store_kv(pool, ko + i, ka * cs.x - kb * cs.y);
         store_kv(pool, ko + i + half, kb * cs.x + ka * cs.y);
         store_kv(pool, vo + i, v[e0]);
@@ -369,8 +372,8 @@ template <typename KT, int DH>
 __global__ __launch_bounds__(256) void attn_kernel(const float *__restrict__ qkv, int q_stride, const KT *__restrict__ pool,
                                                     const int32_t *__restrict__ page_table,
                                                     const int32_t *__restrict__ len_ptr, int M, int layer, int n_layers,
-                                                    int n_heads, int page_tokens, int max_window, int max_splits,
-                                                    float scale, float *__restrict__ part,
+                                                    int n_heads, int n_kv_heads, int page_tokens, int max_window,
+                                                    int max_splits, float scale, float *__restrict__ part,
                                                     const uint32_t *__restrict__ row_mask /* draft tree: nullable */)
 {
     constexpr int LPK = DH / 8;        // lanes per key
@@ -381,6 +384,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const float *__restrict__ qkv
     __shared__ float red[4][8][DH];
 
     const int head = blockIdx.x, split = blockIdx.y;
+    const int kvh = head / (n_heads / n_kv_heads);   // the key / value head this query head reads
     const int L = *len_ptr;
     const int s0 = split * kAttnSplit;
     if (s0 >= L + M) return;  // no key of this split exists for any row
@@ -405,7 +409,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const float *__restrict__ qkv
             float kv[8];
             if (exists) {
                 int page = page_table[j / page_tokens];
-                load8(pool + kv_offset(page, layer, n_layers, 0, head, n_heads, j % page_tokens, page_tokens, DH) + dg * 8, kv);
+                load8(pool + kv_offset(page, layer, n_layers, 0, kvh, n_kv_heads, j % page_tokens, page_tokens, DH) + dg * 8, kv);
             } else {
 #pragma unroll
                 for (int i = 0; i < 8; ++i) kv[i] = 0.f;
@@ -446,7 +450,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const float *__restrict__ qkv
             if (j < L + M) {
                 float vv[8];
                 int page = page_table[j / page_tokens];
-                load8(pool + kv_offset(page, layer, n_layers, 1, head, n_heads, j % page_tokens, page_tokens, DH) + dg * 8, vv);
+                load8(pool + kv_offset(page, layer, n_layers, 1, kvh, n_kv_heads, j % page_tokens, page_tokens, DH) + dg * 8, vv);
 #pragma unroll
                 for (int mm = 0; mm < 8; ++mm) {
                     float p = sc[mm][jl];

@@ -35,7 +35,7 @@ struct MegaArgs {
     int n_layers;
     const uint4 *wp_lm;
     const bf16_t *final_gain, *embed;
-    int d, F, V, n_heads, head_dim, M, mode;
+    int d, F, V, n_heads, n_kv_heads, head_dim, M, mode;
     float inv_d, eps, scale;
     float *x;
     bf16_t *xp_d, *xp_att, *xp_f, *qp;
@@ -381,11 +381,20 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
             if (lane == 0 && atomicAdd(&sh.tiles_done, mine) + mine == tiles_after) bar_signal(bar);
         }
         if (epi_is_qkv(EPI) && a.ready && lane == 0) {
-            // the attention tasks of a head wait for its 3 * head_dim / 16 tiles only, not for the whole grid
-            const int T = a.n_heads * a.head_dim / 16, tph = a.head_dim / 16;
+            // the attention tasks of a head wait for its 3 * head_dim / 16 tiles only (its own q tiles and the
+            // k and v tiles of its key / value head), not for the whole grid: a k or v tile counts for every
+            // query head of its group
+            const int Tq = a.n_heads * a.head_dim / 16, Tkv = a.n_kv_heads * a.head_dim / 16, tph = a.head_dim / 16;
+            const int grp = a.n_heads / a.n_kv_heads;
             for (int i = wave; i < my_tiles; i += kFastWaves) {
                 const int t = (int)blockIdx.x + i * grid;
-                __hip_atomic_fetch_add(a.ready + kCounterStride * ((t % T) / tph), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (t < Tq) {
+                    __hip_atomic_fetch_add(a.ready + kCounterStride * (t / tph), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    const int kvh = ((t - Tq) % Tkv) / tph;
+                    for (int h = kvh * grp; h < (kvh + 1) * grp; ++h)
+                        __hip_atomic_fetch_add(a.ready + kCounterStride * h, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
         }
         load_wchunk(pf, next, blockIdx.x, 0, wave, lane);
@@ -434,6 +443,7 @@ __device__ __forceinline__ FastArgs base_args(MegaArgsK g)
     a.rope = g->rope;
     a.n_layers = g->n_layers;
     a.n_heads = g->n_heads;
+    a.n_kv_heads = g->n_kv_heads;
     a.head_dim = g->head_dim;
     a.qp = g->qp;
     a.ap = g->xp_f;
@@ -465,7 +475,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
         const int d = g->d;
         const LayerW w0 = layer_weights(g, 0);
         {   // weights of the first QKV tile go out before anything else
-            WSrc first = {w0.qkv, (d + 31) / 32, 3 * d / 16};
+            WSrc first = {w0.qkv, (d + 31) / 32, (d + 2 * g->n_kv_heads * g->head_dim) / 16};
             load_wchunk(pf, first, blockIdx.x, 0, wave, lane);
         }
         // ---- embed (+ operand and sums of squares for the first norm)
@@ -483,7 +493,8 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             const LayerW w = layer_weights(g, l);
             FastArgs a = base_args(g);
             const int nks_d = (g->d + 31) / 32;
-            a.Wp = w.qkv; a.Xp = (const uint4 *)g->xp_d; a.nks = nks_d; a.n_tiles = 3 * g->d / 16;
+            a.Wp = w.qkv; a.Xp = (const uint4 *)g->xp_d; a.nks = nks_d;
+            a.n_tiles = (g->d + 2 * g->n_kv_heads * g->head_dim) / 16;
             a.ssp = g->ssp_a; a.layer = l; a.ready = g->qkv_ready;
             if (TREE) a.depth = (const int32_t *)g->depth;
             WSrc none = {w.o, nks_d, 0};   // the O tile is fetched from inside the attention phase
@@ -502,8 +513,8 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             AttnKV<DH> kv;
             kv.loaded = false;
             if ((int)blockIdx.x < n_tasks)
-                attn_load_kv<DH, true>(kv, blockIdx.x % n_heads, blockIdx.x / n_heads, L, M, g->pool, g->page_table, l,
-                                       n_layers, n_heads, true);
+                attn_load_kv<DH, true>(kv, ((int)blockIdx.x % n_heads) / (n_heads / g->n_kv_heads), blockIdx.x / n_heads, L, M, g->pool,
+                                       g->page_table, l, n_layers, g->n_kv_heads, true);
             // No grid barrier here: a task needs the q / k / v tiles of its own head only, and every
             // block still arrives at the barrier that ends this phase after its QKV tiles, which is
             // what the O phase waits for.
@@ -523,7 +534,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
                 const int head = t % n_heads, split = t / n_heads;
                 if (t != (int)blockIdx.x) kv.loaded = false;
                 attn_task<DH, true, decltype(prefetch_o), TREE>(attn_shared<DH>(sh), kv, head, split, L, (const uint4 *)g->qp, g->pool,
-                                                                g->page_table, M, l, n_layers, n_heads, g->max_splits, g->scale,
+                                                                g->page_table, M, l, n_layers, n_heads, g->n_kv_heads, g->max_splits, g->scale,
                                                                 g->part, g->head_counter, g->xp_att, 8, prefetch_o,
                                                                 (const uint32_t *)g->mask);
                 block_sync_lds();
@@ -558,7 +569,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             const bool more = l + 1 < n_layers;
             a.gain = more ? layer_weights(g, l + 1).attn_gain : g->final_gain;
             a.xp_next = g->xp_d; a.ssp_next = g->ssp_a;
-            WSrc next = {more ? layer_weights(g, l + 1).qkv : g->wp_lm, (g->d + 31) / 32, more ? 3 * g->d / 16 : g->V / 16};
+            WSrc next = {more ? layer_weights(g, l + 1).qkv : g->wp_lm, (g->d + 31) / 32, more ? (g->d + 2 * g->n_kv_heads * g->head_dim) / 16 : g->V / 16};
             gemm_phase<EPI_RESIDUAL, false>(a, next, pf, sh, bar, tiles_before);
         }
     }

@@ -54,6 +54,7 @@ struct PrefillArgs {
     const int32_t *page_table;
     const float2 *rope;
     int layer, n_layers, n_heads, head_dim;
+    int n_kv_heads;
 };
 
 __host__ __device__ __forceinline__ size_t xq_offset(int nks, int m, int k, int lo)
@@ -154,8 +155,8 @@ __device__ __forceinline__ void prefill_epilogue(const PrefillArgs &a, int tile,
             xq_store4(a.out, a.out_nks, m, tile * 8 + 4 * kg, act);
         }
     } else if (EPI == EPI_QKV) {
-        const int T = a.n_heads * a.head_dim / 16;
-        const int which = tile / T, t = tile - which * T;
+        const int Tq = a.n_heads * a.head_dim / 16, Tkv = a.n_kv_heads * a.head_dim / 16;
+        const int which = tile < Tq ? 0 : (tile < Tq + Tkv ? 1 : 2), t = tile - (which == 0 ? 0 : (which == 1 ? Tq : Tq + Tkv));
         const int pos = (a.L & ~15) + m;
         f32x4 other;
 #pragma unroll
@@ -185,13 +186,13 @@ __device__ __forceinline__ void prefill_epilogue(const PrefillArgs &a, int tile,
                 *reinterpret_cast<uint2 *>(a.qp + qpf_offset(h, a.G, a.head_dim, m, dim, 1)) =
                     make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
             } else {
-                bf16_t *dst = a.pool + kvf_base(page, a.layer, a.n_layers, 0, h, a.n_heads, a.head_dim) + kf_elem(tk, dim);
+                bf16_t *dst = a.pool + kvf_base(page, a.layer, a.n_layers, 0, h, a.n_kv_heads, a.head_dim) + kf_elem(tk, dim);
                 *reinterpret_cast<uint2 *>(dst) = make_uint2((uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16),
                                                              (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16));
             }
         } else {
             const int n = t * 16 + 4 * kg, h = n / a.head_dim, dim = n - h * a.head_dim;
-            bf16_t *dst = a.pool + kvf_base(page, a.layer, a.n_layers, 1, h, a.n_heads, a.head_dim);
+            bf16_t *dst = a.pool + kvf_base(page, a.layer, a.n_layers, 1, h, a.n_kv_heads, a.head_dim);
 #pragma unroll
             for (int i = 0; i < 4; ++i) dst[vf_elem(tk, dim + i)] = f32_to_bf16(y[i]);
         }
@@ -378,12 +379,12 @@ __global__ __launch_bounds__(kPgThreads) void prefill_gemm_kernel(PrefillArgs a)
 template <int DH>
 __global__ __launch_bounds__(256) void prefill_attn_kernel(const uint4 *__restrict__ qp, const bf16_t *__restrict__ pool,
                                                             const int32_t *__restrict__ page_table, int G, int L, int P,
-                                                            int layer, int n_layers, int n_heads, float scale,
+                                                            int layer, int n_layers, int n_heads, int n_kv_heads, float scale,
                                                             bf16_t *__restrict__ xq_att, int nks_d)
 {
     constexpr int NKS = DH / 32, NDT = DH / 16;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, slot = lane & 15, kg = lane >> 4;
-    const int head = blockIdx.x;
+    const int head = blockIdx.x, kvh = head / (n_heads / n_kv_heads);
     const int g = ((int)gridDim.y - 1 - (int)blockIdx.y) * 4 + wave;
     if (g >= G) return;   // (no block-wide synchronisation below)
     const int last_page = (L >> 4) + g;
@@ -400,8 +401,8 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const uint4 *__restri
     uint2 vA[NDT], vB[NDT];
     auto load = [&](uint4 (&kf)[NKS], uint2 (&vf)[NDT], int pg) {
         const int page = __builtin_amdgcn_readfirstlane(page_table[pg]);
-        const uint4 *kp = reinterpret_cast<const uint4 *>(pool + kvf_base(page, layer, n_layers, 0, head, n_heads, DH));
-        const uint2 *vp = reinterpret_cast<const uint2 *>(pool + kvf_base(page, layer, n_layers, 1, head, n_heads, DH));
+        const uint4 *kp = reinterpret_cast<const uint4 *>(pool + kvf_base(page, layer, n_layers, 0, kvh, n_kv_heads, DH));
+        const uint2 *vp = reinterpret_cast<const uint2 *>(pool + kvf_base(page, layer, n_layers, 1, kvh, n_kv_heads, DH));
 #pragma unroll
         for (int i = 0; i < NKS; ++i) kf[i] = kp[i * 64 + lane];
 #pragma unroll

@@ -94,17 +94,27 @@ class ModelShape:
     dtype: str = "bf16"          # storage type of weights and KV: "f32" | "bf16"
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
+    n_kv_heads: int = 0          # key/value heads shared by groups of query heads; 0 = one per query head
+
+    @property
+    def kv_heads(self) -> int:
+        return self.n_kv_heads or self.n_heads
+
+    @property
+    def kv_dim(self) -> int:
+        """Width of a cached K (or V) row."""
+        return self.kv_heads * self.head_dim
 
     @property
     def n_params_streamed(self) -> int:
         """Weights read once per forward (embedding rows excluded)."""
         d, f = self.d_model, self.d_ffn
-        return self.n_layers * (4 * d * d + 3 * d * f) + self.vocab * d
+        return self.n_layers * (2 * d * d + 2 * d * self.kv_dim + 3 * d * f) + self.vocab * d
 
     @property
     def kv_bytes_per_token(self) -> int:
         el = 2 if self.dtype == "bf16" else 4
-        return self.n_layers * 2 * self.d_model * el
+        return self.n_layers * 2 * self.kv_dim * el
 
 
 TINY = ModelShape(2, 256, 4, 64, 688, 1024, "f32")
@@ -113,15 +123,21 @@ TINY_BF16 = dataclasses.replace(TINY, dtype="bf16")
 MID_BF16 = ModelShape(3, 512, 4, 128, 1408, 2048, "bf16")
 LLAMA_7B = ModelShape(32, 4096, 32, 128, 11008, 32000, "bf16")
 LLAMA_13B = ModelShape(40, 5120, 40, 128, 13824, 32000, "bf16")
+# Grouped key/value heads and a vocabulary twice LLaMA's: the dimensions of the ChatGLM3-6B model
+# the paper also evaluates (28 layers, 32 query heads over 2 key/value heads, FFN 13696).
+GLM_6B = ModelShape(28, 4096, 32, 128, 13696, 65024, "bf16", n_kv_heads=2)
+MID_GQA = ModelShape(3, 512, 4, 128, 1408, 2048, "bf16", n_kv_heads=2)
+TINY_MQA = ModelShape(2, 256, 4, 64, 688, 1024, "f32", n_kv_heads=1)
+TINY_MQA_BF16 = dataclasses.replace(TINY_MQA, dtype="bf16")
 
 _PER_LAYER = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
 
 
 def weight_shapes(s: ModelShape) -> Dict[str, tuple]:
-    d, f, v = s.d_model, s.d_ffn, s.vocab
+    d, f, v, kvd = s.d_model, s.d_ffn, s.vocab, s.kv_dim
     return {
         "embed": (v, d), "final_norm": (d,), "lm_head": (v, d),
-        "attn_norm": (d,), "wq": (d, d), "wk": (d, d), "wv": (d, d), "wo": (d, d),
+        "attn_norm": (d,), "wq": (d, d), "wk": (kvd, d), "wv": (kvd, d), "wo": (d, d),
         "ffn_norm": (d,), "w_gate": (f, d), "w_up": (f, d), "w_down": (d, f),
     }
 
@@ -189,12 +205,12 @@ def markov_stream(vocab: int, length: int, p_copy: float, span_lo: int, span_hi:
 def kv_fill(s: ModelShape, seed: int, layer: int, n_tokens: int, device="cpu"):
     """Seeded K and V contents for ``n_tokens`` cached positions of one layer.
 
-    Returns two [n_tokens][d_model] tensors in the storage dtype, ~N(0, 1).
+    Returns two [n_tokens][kv_dim] tensors in the storage dtype, ~N(0, 1).
     """
     tdtype = torch.bfloat16 if s.dtype == "bf16" else torch.float32
-    n = n_tokens * s.d_model
-    k = approx_normal(seed, 50000 + 2 * layer, n, 1.0, device).to(tdtype).reshape(n_tokens, s.d_model)
-    v = approx_normal(seed, 50001 + 2 * layer, n, 1.0, device).to(tdtype).reshape(n_tokens, s.d_model)
+    n = n_tokens * s.kv_dim
+    k = approx_normal(seed, 50000 + 2 * layer, n, 1.0, device).to(tdtype).reshape(n_tokens, s.kv_dim)
+    v = approx_normal(seed, 50001 + 2 * layer, n, 1.0, device).to(tdtype).reshape(n_tokens, s.kv_dim)
     return k, v
 
 
@@ -208,6 +224,7 @@ WORKLOADS = {
     "llama7b": dict(shape=LLAMA_7B, prompt=512, p_copy=0.40, span=(4, 16), gen=256, n_min=2, n_max=5, k=5, seed=2),
     "llama13b": dict(shape=LLAMA_13B, prompt=1024, p_copy=0.50, span=(8, 32), gen=256, n_min=2, n_max=7, k=8, seed=4),
     "long7b": dict(shape=LLAMA_7B, prompt=3584, p_copy=0.20, span=(4, 16), gen=512, n_min=2, n_max=6, k=16, seed=5),
+    "glm6b": dict(shape=GLM_6B, prompt=512, p_copy=0.40, span=(4, 16), gen=256, n_min=2, n_max=5, k=5, seed=6),
 }
 
 

@@ -190,3 +190,33 @@ def test_llama7b_prompt_in_one_pass():
         # two bf16 roundings of values that carry the rounding noise of up to 32 layers
         assert float((ka - kb).abs().max()) < 0.05 and float((va - vb).abs().max()) < 0.05
         assert float((ka - kb).abs().mean()) < 2e-3 and float((va - vb).abs().mean()) < 2e-3
+
+
+def test_glm6b_shape_step_with_grouped_heads():
+    """The second model shape at full size (28 layers, 32 query heads over 2 key / value heads, FFN 13696,
+    vocabulary 65024): one verification step of 6 rows over 512 seeded positions, the persistent kernel
+    against the oracle and against the one-launch-per-operation path bit for bit."""
+    shape = synth.GLM_6B
+    L, K = 512, 5
+    w = synth.make_weights(shape, 6, device="cuda")
+    model = B.Model(shape, w, max_window=8, max_positions=L + 64)
+    model_l = B.Model(shape, w, max_window=8, max_positions=L + 64, gemm_path=B.GEMM_MFMA_LAUNCHES)
+    kv, kv_l = B.KVCache(model, L + 64), B.KVCache(model_l, L + 64)
+    w_host = {k_: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k_, v in w.items()}
+    dec = od.Decoder(shape, w_host, L + 64)
+    _seed_both(shape, dec, [kv, kv_l], L, seed=10)
+    window = synth.random_tokens(shape.vocab, K + 1, 6)
+    ref = dec.forward(window)
+    a, nxt, preds, got = _step_logits(model, kv, window)
+    a2, nxt2, preds2, got2 = _step_logits(model_l, kv_l, window)
+    assert torch.equal(got, got2) and (a, nxt, preds) == (a2, nxt2, preds2)
+    err = float(np.max(np.abs(got.cpu().numpy().astype(np.float64) - ref)))
+    print("GLM-6B shape step: max |logit error| = %.2e" % err)
+    assert err < TOL["bf16"]
+    for r in range(K + 1):
+        if top2_gap(ref[r]) > TOL["bf16"]:
+            assert preds[r] == od.argmax(ref[r])
+    k_gpu, v_gpu = kv.read(shape.n_layers - 1, L, 1)
+    k_ref, v_ref = dec.kv_read(shape.n_layers - 1, L, 1)
+    assert k_gpu.shape == (1, shape.kv_dim)
+    assert np.max(np.abs(k_gpu.cpu().numpy() - k_ref)) < 0.05 and np.max(np.abs(v_gpu.cpu().numpy() - v_ref)) < 0.05

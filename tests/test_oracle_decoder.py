@@ -3,6 +3,7 @@ library routines (torch fp64 matmul / softmax / silu), closed forms,
 invariants, and an independent full-sequence (cache-free) expression of the
 LLaMA layer written with torch tensor algebra only in this file.
 """
+import dataclasses
 import math
 
 import numpy as np
@@ -149,6 +150,7 @@ def _torch_full_sequence_logits(shape, w, tokens, kv_bf16):
     f64 = torch.float64
     T = len(tokens)
     H, dh, d = shape.n_heads, shape.head_dim, shape.d_model
+    Hkv = shape.kv_heads
     W = lambda t: t.to(f64)
 
     def norm(x, g):
@@ -158,7 +160,7 @@ def _torch_full_sequence_logits(shape, w, tokens, kv_bf16):
     theta = shape.rope_base ** (-torch.arange(0, dh // 2, dtype=f64) * 2.0 / dh)
     rot = torch.polar(torch.ones(T, dh // 2, dtype=f64), pos[:, None] * theta[None, :])  # [T][dh/2]
 
-    def rope(t):  # t: [T][H][dh]
+    def rope(t):  # t: [T][heads][dh]
         z = torch.complex(t[..., : dh // 2], t[..., dh // 2:]) * rot[:, None, :]
         return torch.cat([z.real, z.imag], dim=-1)
 
@@ -170,8 +172,9 @@ def _torch_full_sequence_logits(shape, w, tokens, kv_bf16):
     for l in range(shape.n_layers):
         h = norm(x, w["attn_norm"][l])
         q = rope((h @ W(w["wq"][l]).T).view(T, H, dh))
-        k = store(rope((h @ W(w["wk"][l]).T).view(T, H, dh)))
-        v = store((h @ W(w["wv"][l]).T).view(T, H, dh))
+        # key/value head j serves the query heads j * (H / Hkv) .. (j + 1) * (H / Hkv) - 1
+        k = store(rope((h @ W(w["wk"][l]).T).view(T, Hkv, dh))).repeat_interleave(H // Hkv, dim=1)
+        v = store((h @ W(w["wv"][l]).T).view(T, Hkv, dh)).repeat_interleave(H // Hkv, dim=1)
         s = torch.einsum("thd,shd->hts", q, k) / math.sqrt(dh) + mask
         o = torch.einsum("hts,shd->thd", torch.softmax(s, -1), v).reshape(T, d)
         x = x + o @ W(w["wo"][l]).T
@@ -200,6 +203,49 @@ def test_incremental_windowed_forward_equals_full_sequence(which, tiny_weights, 
     tol = 1e-9 if which == "f32" else 2e-3
     assert np.max(np.abs(got - ref)) < tol
     assert np.std(ref) > 0.05  # the comparison is not vacuous
+
+
+def test_grouped_attention_is_attention_over_repeated_key_value_heads():
+    rng = np.random.default_rng(5)
+    H, Hkv, dh, n = 6, 2, 8, 11
+    q = rng.standard_normal(H * dh)
+    K = rng.standard_normal((n, Hkv * dh))
+    V = rng.standard_normal((n, Hkv * dh))
+    rep = lambda a: np.repeat(a.reshape(n, Hkv, dh), H // Hkv, axis=1).reshape(n, H * dh)
+    assert np.array_equal(od.attention_grouped(q, K, V, H, Hkv, dh), od.attention(q, rep(K), rep(V), H, dh))
+    assert np.array_equal(od.attention_grouped(q, rep(K), rep(V), H, H, dh), od.attention(q, rep(K), rep(V), H, dh))
+    # one shared key/value head, one key: every query head returns that value row
+    out = od.attention_grouped(q, K[:1, :dh], V[:1, :dh], H, 1, dh)
+    assert np.allclose(out.reshape(H, dh), V[0, :dh])
+
+
+@pytest.mark.parametrize("shape", [synth.TINY_MQA, synth.TINY_MQA_BF16, dataclasses.replace(synth.TINY, n_kv_heads=2)])
+def test_grouped_heads_forward(shape):
+    """Grouped key/value heads: the windowed forward against the cache-free full-sequence statement, and
+    against the same model written with one key/value head per query head (weights repeated per group)."""
+    w = synth.make_weights(shape, 11)
+    tokens = synth.markov_stream(shape.vocab, 30, 0.3, 4, 12, 4)
+    ref = _torch_full_sequence_logits(shape, w, tokens, kv_bf16=(shape.dtype == "bf16"))
+    dec = od.Decoder(shape, w, max_tokens=40)
+    got = []
+    for n in (9, 1, 20):
+        lo = dec.length
+        got.append(dec.forward(tokens[lo:lo + n]))
+        dec.set_length(lo + n)
+    got = np.concatenate(got, 0)
+    assert np.max(np.abs(got - ref)) < (1e-9 if shape.dtype == "f32" else 2e-3)
+    assert np.std(ref) > 0.05
+    k0, _ = dec.kv_read(0, 0, 30)
+    assert k0.shape == (30, shape.kv_dim)
+    # the equivalent model without sharing
+    g, dh = shape.n_heads // shape.kv_heads, shape.head_dim
+    full = dataclasses.replace(shape, n_kv_heads=0)
+    rep = lambda t: t.view(shape.kv_heads, dh, -1).repeat_interleave(g, dim=0).reshape(shape.d_model, -1).contiguous()
+    w2 = dict(w)
+    w2["wk"] = [rep(t) for t in w["wk"]]
+    w2["wv"] = [rep(t) for t in w["wv"]]
+    dec2 = od.Decoder(full, w2, max_tokens=40)
+    assert np.array_equal(dec2.forward(tokens), od.Decoder(shape, w, max_tokens=40).forward(tokens))
 
 
 def test_rollback_then_recompute_equals_fresh_cache(tiny_weights):
