@@ -30,7 +30,7 @@ EXPORTS = (
     "anpd_model_workspace_bytes", "anpd_model_create", "anpd_model_destroy",
     "anpd_kv_pool_bytes", "anpd_kv_create", "anpd_kv_destroy", "anpd_kv_length", "anpd_kv_truncate",
     "anpd_kv_set_page_order", "anpd_kv_num_pages", "anpd_kv_write", "anpd_kv_read",
-    "anpd_verify", "anpd_verify_tree", "anpd_prefill_workspace_bytes", "anpd_prefill", "anpd_linear_workspace_bytes", "anpd_linear",
+    "anpd_verify", "anpd_verify_tree", "anpd_verify_batch", "anpd_prefill_workspace_bytes", "anpd_prefill", "anpd_linear_workspace_bytes", "anpd_linear",
     "anpd_model_profile", "anpd_model_profile_read", "anpd_packed_bytes", "anpd_pack_weights",
     "anpd_model_trace", "anpd_model_set_barrier_spin_limit",
 )
@@ -115,6 +115,8 @@ def lib():
     L.anpd_verify.argtypes = [vp, vp, i32p, C.c_int32, C.c_int32, i32p, i32p, i32p, vp, vp]
     L.anpd_verify_tree.restype = C.c_int32
     L.anpd_verify_tree.argtypes = [vp, vp, i32p, i32p, C.c_int32, i32p, i32p, i32p, i32p, vp, vp]
+    L.anpd_verify_batch.restype = C.c_int32
+    L.anpd_verify_batch.argtypes = [vp, C.POINTER(vp), C.c_int32, C.POINTER(i32p), i32p, C.c_int32, i32p, i32p, vp, vp]
     L.anpd_prefill_workspace_bytes.restype = C.c_size_t
     L.anpd_prefill_workspace_bytes.argtypes = [vp, C.c_int32]
     L.anpd_prefill.restype = C.c_int32
@@ -398,6 +400,26 @@ def verify_tree(model: Model, kv: KVCache, window: Sequence[int], parent: Sequen
     if want_predicts:
         return acc.value, nxt.value, list(path[:acc.value + 1]), list(preds[:n])
     return acc.value, nxt.value, list(path[:acc.value + 1])
+
+
+def verify_batch(model: Model, kvs: Sequence[KVCache], windows: Sequence[Sequence[int]], mode: int = VERIFY,
+                 out_logits=None, stream=None):
+    """anpd_verify_batch: one step for several sequences.  Returns [(accepted, next)] per sequence."""
+    n = len(kvs)
+    assert len(windows) == n
+    handles = (C.c_void_p * max(1, n))(*[kv._h for kv in kvs])
+    rows = [_ints(w) for w in windows]
+    wins = (C.POINTER(C.c_int32) * max(1, n))(*[C.cast(r, C.POINTER(C.c_int32)) for r in rows])
+    counts = _ints([len(w) for w in windows])
+    acc, nxt = (C.c_int32 * max(1, n))(), (C.c_int32 * max(1, n))()
+    lp = 0
+    if out_logits is not None:
+        import torch
+        assert out_logits.is_cuda and out_logits.dtype == torch.float32 and out_logits.is_contiguous()
+        assert out_logits.numel() >= sum(len(w) for w in windows) * model.vocab
+        lp = out_logits.data_ptr()
+    _check(lib().anpd_verify_batch(model._h, handles, n, wins, counts, mode, acc, nxt, lp, _stream_ptr(stream)))
+    return [(acc[i], nxt[i]) for i in range(n)]
 
 
 def pack_weights(W, stream=None):

@@ -35,7 +35,7 @@ int kv_heads_of(const anpd_model_cfg &c) { return c.n_kv_heads > 0 ? c.n_kv_head
 int kv_dim_of(const anpd_model_cfg &c) { return kv_heads_of(c) * c.head_dim; }
 
 struct Layout {  // byte offsets into the model workspace
-    size_t rope_tab, tok, tree, result, counter, x, h, y, qkv, att, gu, a, logits, part;
+    size_t rope_tab, tok, tree, batch, result, counter, x, h, y, qkv, att, gu, a, logits, part;
     // fast path: packed operands, partial sums of squares, packed weights
     size_t xp_d, xp_att, xp_f, ssp_a, ssp_b, qp, head_ctr, layer_tab, amax, row_ctr, bar, wp_lm, total;
     std::vector<size_t> wp_qkv, wp_o, wp_gu, wp_down;
@@ -86,7 +86,9 @@ Layout make_layout(const anpd_model_cfg *c)
     L.rope_tab = take((size_t)c->max_positions * (c->head_dim / 2) * sizeof(float2));
     L.tok = take(ANPD_MAX_WINDOW * sizeof(int32_t));
     L.tree = take(3 * ANPD_MAX_WINDOW * sizeof(int32_t));                 // draft tree: parent, depth, visibility mask
-    L.result = take((2 + ANPD_MAX_WINDOW + ANPD_MAX_WINDOW + 1) * sizeof(int32_t));   // accepted, next, predictions, accepted path
+    L.batch = take(ANPD_MAX_WINDOW * sizeof(int32_t) + ANPD_MAX_WINDOW * sizeof(SeqRef));   // batched step: sequence of every row, sequences
+    // accepted, next, predictions, accepted path of a tree, (accepted, next) of every sequence of a batch
+    L.result = take((2 + ANPD_MAX_WINDOW + ANPD_MAX_WINDOW + 1 + 2 * ANPD_MAX_WINDOW) * sizeof(int32_t));
     L.counter = take(sizeof(uint32_t));
     L.x = take(MW * d * 4);
     L.h = take(MW * d * 4);
@@ -165,7 +167,8 @@ struct anpd_model {
     const void *embed, *final_norm, *lm_head;
     std::vector<const void *> attn_norm, wq, wk, wv, wo, ffn_norm, w_gate, w_up, w_down;
     int32_t *pin;  // pinned host staging: [0..32) window, [32..99) result and accepted path, [100] error flag of the
-                   // persistent kernel, [128..224) draft tree (parent, depth, mask)
+                   // persistent kernel, [128..224) draft tree (parent, depth, mask), [256..320) results of a batch,
+                   // [384..416) sequence of every row of a batch, [512..768) its sequences (SeqRef)
     int32_t *pin_dev;  // the same memory as the device addresses it
     // optional per-kernel timing with events on the launch stream
     bool prof;
@@ -422,7 +425,13 @@ int32_t run_step_generic(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_
 
 // The fused bf16 step: per layer QKV(+norm, RoPE, cache write) -> attention -> combine -> O(+residual)
 // -> gate/up(+norm, SwiGLU) -> down(+residual); then LM head(+norm) -> argmax / accept.
-int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t st, bool tree = false)
+// A batched step: the sequences' descriptions are in the workspace (Layout::batch); `kv` is unused.
+struct BatchLaunch {
+    int n_seq, n_blocks /* (split, sequence) blocks per head */, grid_splits /* splits of the longest sequence */;
+};
+
+int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t st, bool tree = false,
+                      const BatchLaunch *batch = nullptr)
 {
     const anpd_model_cfg &c = m->cfg;
     const Layout &L = m->lay;
@@ -440,8 +449,11 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
     int32_t *result = (int32_t *)(ws + L.result);
     uint32_t *counter = (uint32_t *)(ws + L.counter);
     const float scale = 1.0f / sqrtf((float)dh);
-    const int n_splits = (kv->len + M + kFastSplit - 1) / kFastSplit;
+    const int n_splits = batch ? batch->grid_splits : (kv->len + M + kFastSplit - 1) / kFastSplit;
     const int nks_d = (d + 31) / 32, nks_f = (F + 31) / 32;
+    const int32_t *b_row_seq = (const int32_t *)(ws + L.batch);
+    const SeqRef *b_seqs = (const SeqRef *)(ws + L.batch + ANPD_MAX_WINDOW * sizeof(int32_t));
+    int32_t *dummy_len = (int32_t *)(ws + L.counter) + 16;   // the per-row argmax kernel's length update goes nowhere in a batch
     const int32_t *t_parent = (const int32_t *)(ws + L.tree), *t_depth = t_parent + ANPD_MAX_WINDOW;
     const uint32_t *t_mask = (const uint32_t *)(t_parent + 2 * ANPD_MAX_WINDOW);
     int32_t rc;
@@ -455,9 +467,11 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
     base.n_ss = d / 16;
     base.d = d;
     base.x = x;
-    base.pool = (bf16_t *)kv->pool;
-    base.page_table = kv->d_table;
-    base.len_ptr = kv->d_len;
+    if (!batch) {
+        base.pool = (bf16_t *)kv->pool;
+        base.page_table = kv->d_table;
+        base.len_ptr = kv->d_len;
+    }
     base.rope = (const float2 *)(ws + L.rope_tab);
     base.n_layers = c.n_layers;
     base.n_heads = H;
@@ -485,16 +499,30 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
             a.qp = qp;
             a.layer = l;
             a.depth = t_depth;
-            rc = tree ? launch_fast<EPI_QKV_TREE>(a, m->n_cu, false, st) : launch_fast<EPI_QKV>(a, m->n_cu, false, st);
+            a.seqs = b_seqs;
+            a.row_seq = b_row_seq;
+            rc = batch ? launch_fast<EPI_QKV_BATCH>(a, m->n_cu, false, st)
+                       : (tree ? launch_fast<EPI_QKV_TREE>(a, m->n_cu, false, st) : launch_fast<EPI_QKV>(a, m->n_cu, false, st));
             if (rc != ANPD_OK) return rc;
         }
         mark(m, ANPD_PROF_GEMM_QKV, st);
+        if (batch) {
+            if (dh == 128)
+                hipLaunchKernelGGL((attn_batch_kernel<128>), dim3(H, n_splits, batch->n_seq), dim3(kFastThreads), 0, st, (const uint4 *)qp,
+                                   b_seqs, b_row_seq, batch->n_blocks, M, l, c.n_layers, H, Hkv, L.max_splits, scale, part, head_ctr,
+                                   xp_att, cls);
+            else
+                hipLaunchKernelGGL((attn_batch_kernel<64>), dim3(H, n_splits, batch->n_seq), dim3(kFastThreads), 0, st, (const uint4 *)qp,
+                                   b_seqs, b_row_seq, batch->n_blocks, M, l, c.n_layers, H, Hkv, L.max_splits, scale, part, head_ctr,
+                                   xp_att, cls);
+        } else
 #define ANPD_ATTN(DH_, TREE_)                                                                                              \
     hipLaunchKernelGGL((attn_fast_kernel<DH_, TREE_>), dim3(H, n_splits), dim3(kFastThreads), 0, st, (const uint4 *)qp,  \
                        (const bf16_t *)kv->pool, kv->d_table, kv->d_len, M, l, c.n_layers, H, Hkv, L.max_splits, scale, part,   \
                        head_ctr, xp_att, cls, t_mask)
         if (dh == 128) { if (tree) ANPD_ATTN(128, true); else ANPD_ATTN(128, false); }
-        else { if (tree) ANPD_ATTN(64, true); else ANPD_ATTN(64, false); }
+        else if (tree) ANPD_ATTN(64, true);
+        else ANPD_ATTN(64, false);
 #undef ANPD_ATTN
         mark(m, ANPD_PROF_ATTN, st);
         {
@@ -545,8 +573,9 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
         if ((rc = launch_fast<EPI_LOGITS>(a, m->n_cu, false, st)) != ANPD_OK) return rc;
     }
     mark(m, ANPD_PROF_GEMM_LM_HEAD, st);
-    hipLaunchKernelGGL(argmax_accept_kernel, dim3(M), dim3(1024), 0, st, logits, V, M, tok, mode, result, kv->d_len,
-                       counter);
+    hipLaunchKernelGGL(argmax_accept_kernel, dim3(M), dim3(1024), 0, st, logits, V, M, tok, batch ? (int)ANPD_APPEND : mode, result,
+                       batch ? dummy_len : kv->d_len, counter);
+    if (batch) hipLaunchKernelGGL(accept_batch_kernel, dim3(1), dim3(64), 0, st, tok, b_seqs, batch->n_seq, mode, result);
     if (tree) {
         hipLaunchKernelGGL(accept_tree_kernel, dim3(1), dim3(64), 0, st, tok, t_parent, t_depth, M, result, kv->d_len, kv->len);
         hipLaunchKernelGGL(kvf_compact_kernel, dim3((unsigned)(c.n_layers * 2 * Hkv)), dim3(128), 0, st, (bf16_t *)kv->pool,
@@ -859,9 +888,9 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
             tab[(size_t)p * half + i] = make_float2((float)std::cos(ang), (float)std::sin(ang));
         }
     }
-    hipError_t e = hipHostMalloc((void **)&m->pin, 256 * sizeof(int32_t), hipHostMallocDefault);
+    hipError_t e = hipHostMalloc((void **)&m->pin, 1024 * sizeof(int32_t), hipHostMallocDefault);
     if (e != hipSuccess) { delete m; return fail(ANPD_E_HIP, "hipHostMalloc: %s", hipGetErrorString(e)); }
-    std::memset(m->pin, 0, 256 * sizeof(int32_t));
+    std::memset(m->pin, 0, 1024 * sizeof(int32_t));
     e = hipHostGetDevicePointer((void **)&m->pin_dev, m->pin, 0);
     if (e != hipSuccess) { (void)hipHostFree(m->pin); delete m; return fail(ANPD_E_HIP, "hipHostGetDevicePointer: %s", hipGetErrorString(e)); }
     e = hipMemsetAsync(m->ws, 0, m->mfma ? lay.wp_lm : lay.total, st);
@@ -1223,6 +1252,78 @@ int32_t anpd_verify_tree(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, 
     if (out_path) std::memcpy(out_path, res + 34, sizeof(int32_t) * (size_t)(res[0] + 1));
     kv->len += 1 + res[0];
     release_pages(kv, kv->len);
+    return ANPD_OK;
+}
+
+int32_t anpd_verify_batch(anpd_model_t *m, anpd_kv_t *const *kvs, int32_t n_seq, const int32_t *const *windows,
+                          const int32_t *n_windows, int32_t mode, int32_t *out_accepted, int32_t *out_next, float *out_logits,
+                          void *stream)
+{
+    if (!m || !kvs || !windows || !n_windows || !out_accepted || !out_next) return fail(ANPD_E_INVAL, "anpd_verify_batch: NULL argument");
+    if (mode != ANPD_VERIFY && mode != ANPD_APPEND) return fail(ANPD_E_INVAL, "anpd_verify_batch: unknown mode %d", mode);
+    if (n_seq < 1 || n_seq > ANPD_MAX_WINDOW) return fail(ANPD_E_INVAL, "anpd_verify_batch: n_seq must be in 1..%d", ANPD_MAX_WINDOW);
+    if (!m->mfma) return fail(ANPD_E_UNIMPLEMENTED, "anpd_verify_batch: needs the matrix-core path (bf16 weights)");
+    int total = 0;
+    for (int s = 0; s < n_seq; ++s) {
+        anpd_kv *kv = kvs[s];
+        if (!kv || !windows[s]) return fail(ANPD_E_INVAL, "anpd_verify_batch: NULL cache or window of sequence %d", s);
+        if (kv->m != m) return fail(ANPD_E_INVAL, "anpd_verify_batch: cache %d belongs to another model", s);
+        for (int t = 0; t < s; ++t)
+            if (kvs[t] == kv) return fail(ANPD_E_INVAL, "anpd_verify_batch: sequences %d and %d share a cache", t, s);
+        if (n_windows[s] < 1) return fail(ANPD_E_INVAL, "anpd_verify_batch: n_windows[%d] must be >= 1", s);
+        if (kv->len + n_windows[s] > kv->max_tokens)
+            return fail(ANPD_E_CAPACITY, "anpd_verify_batch: sequence %d: length %d + window %d exceeds capacity %d", s, kv->len,
+                        n_windows[s], kv->max_tokens);
+        for (int i = 0; i < n_windows[s]; ++i)
+            if (windows[s][i] < 0 || windows[s][i] >= m->cfg.vocab)
+                return fail(ANPD_E_RANGE, "anpd_verify_batch: token %d at window %d row %d outside [0, %d)", windows[s][i], s, i, m->cfg.vocab);
+        total += n_windows[s];
+        if (total > m->cfg.max_window)
+            return fail(ANPD_E_CAPACITY, "anpd_verify_batch: %d rows in all exceed max_window %d", total, m->cfg.max_window);
+    }
+    hipStream_t st = (hipStream_t)stream;
+    for (int s = 0; s < n_seq; ++s) {
+        int32_t rc = ensure_pages(kvs[s], kvs[s]->len + n_windows[s], st);
+        if (rc != ANPD_OK) return rc;
+    }
+    // joint window, sequence of every row, sequences
+    int32_t *row_seq = m->pin + 384;
+    SeqRef *seqs = (SeqRef *)(m->pin + 512);
+    BatchLaunch bl = {n_seq, 0, 0};
+    int row = 0;
+    for (int s = 0; s < n_seq; ++s) {
+        anpd_kv *kv = kvs[s];
+        seqs[s].pool = (bf16_t *)kv->pool;
+        seqs[s].page_table = kv->d_table;
+        seqs[s].len_ptr = kv->d_len;
+        seqs[s].row0 = row;
+        seqs[s].n_rows = n_windows[s];
+        const int splits = (kv->len + n_windows[s] + kFastSplit - 1) / kFastSplit;
+        bl.n_blocks += splits;
+        if (splits > bl.grid_splits) bl.grid_splits = splits;
+        for (int i = 0; i < n_windows[s]; ++i, ++row) {
+            m->pin[row] = windows[s][i];
+            row_seq[row] = s;
+        }
+    }
+    HIP_TRY(hipMemcpyAsync(m->ws + m->lay.tok, m->pin, sizeof(int32_t) * (size_t)total, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(m->ws + m->lay.batch, row_seq, sizeof(int32_t) * (size_t)total, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(m->ws + m->lay.batch + ANPD_MAX_WINDOW * sizeof(int32_t), seqs, sizeof(SeqRef) * (size_t)n_seq,
+                           hipMemcpyHostToDevice, st));
+    int32_t rc = run_step_fast(m, nullptr, total, mode, st, false, &bl);
+    if (rc != ANPD_OK) return rc;
+    int32_t *res = m->pin + 256;
+    HIP_TRY(hipMemcpyAsync(res, m->ws + m->lay.result + 67 * sizeof(int32_t), sizeof(int32_t) * 2 * (size_t)n_seq, hipMemcpyDeviceToHost, st));
+    if (out_logits)
+        HIP_TRY(hipMemcpyAsync(out_logits, m->ws + m->lay.logits, sizeof(float) * (size_t)total * m->cfg.vocab, hipMemcpyDeviceToDevice, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    collect_marks(m);
+    for (int s = 0; s < n_seq; ++s) {
+        out_accepted[s] = res[2 * s];
+        out_next[s] = res[2 * s + 1];
+        kvs[s]->len += 1 + res[2 * s];
+        release_pages(kvs[s], kvs[s]->len);
+    }
     return ANPD_OK;
 }
 

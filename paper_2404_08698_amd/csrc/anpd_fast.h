@@ -123,9 +123,18 @@ __global__ __launch_bounds__(256) void pack_kernel(const bf16_t *__restrict__ sr
 // --------------------------------------------------------------- epilogues
 
 enum { EPI_PLAIN = 0, EPI_QKV = 1, EPI_RESIDUAL = 2, EPI_GATE_UP = 3, EPI_LOGITS = 4, EPI_LM_ARGMAX = 5,
-       EPI_QKV_TREE = 6 /* QKV of a draft tree: a row's rotary position is length + its depth, not length + its index */ };
-__host__ __device__ constexpr bool epi_is_qkv(int epi) { return epi == EPI_QKV || epi == EPI_QKV_TREE; }
+       EPI_QKV_TREE = 6 /* QKV of a draft tree: a row's rotary position is length + its depth, not length + its index */,
+       EPI_QKV_BATCH = 7 /* QKV of several sequences' windows side by side: cache, page table and length per row */ };
+__host__ __device__ constexpr bool epi_is_qkv(int epi) { return epi == EPI_QKV || epi == EPI_QKV_TREE || epi == EPI_QKV_BATCH; }
 __host__ __device__ constexpr bool epi_has_norm(int epi) { return epi_is_qkv(epi) || epi == EPI_GATE_UP || epi == EPI_LOGITS; }
+
+// One sequence of a batched step: its cache and the window rows it owns (consecutive rows of the joint window).
+struct SeqRef {
+    bf16_t *pool;
+    const int32_t *page_table;
+    int32_t *len_ptr;
+    int32_t row0, n_rows;
+};
 
 struct FastArgs {
     // GEMM proper
@@ -160,6 +169,9 @@ struct FastArgs {
     uint32_t *ready;
     // QKV_TREE: depth of every window row in the draft tree
     const int32_t *depth;
+    // QKV_BATCH: the sequences and, for every window row, the index of its sequence
+    const SeqRef *seqs;
+    const int32_t *row_seq;
 };
 
 // rinv[m] = 1 / sqrt(mean(x[m]^2) + eps) for the window rows, from the producer's per-tile partial
@@ -333,12 +345,22 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
         y = y * r;
         const int Tq = a.n_heads * a.head_dim / 16, Tkv = a.n_kv_heads * a.head_dim / 16;
         const int which = tile < Tq ? 0 : (tile < Tq + Tkv ? 1 : 2), t = tile - (which == 0 ? 0 : (which == 1 ? Tq : Tq + Tkv));
-        const int pos = *a.len_ptr + m;   // the row's cache slot
         f32x4 other;
 #pragma unroll
         for (int i = 0; i < 4; ++i) other[i] = __shfl_xor(y[i], 32, kWave);
         if (!valid) return;
-        const int page = pre ? pre->page : a.page_table[pos >> 4], tok = pos & 15;
+        int pos, page;          // the row's cache slot and the page it lies in
+        bf16_t *pool = a.pool;
+        if (EPI == EPI_QKV_BATCH) {
+            const SeqRef sq = a.seqs[a.row_seq[m]];
+            pos = *sq.len_ptr + (m - sq.row0);
+            page = sq.page_table[pos >> 4];
+            pool = sq.pool;
+        } else {
+            pos = *a.len_ptr + m;
+            page = pre ? pre->page : a.page_table[pos >> 4];
+        }
+        const int tok = pos & 15;
         if (which < 2) {
             const int tph = a.head_dim / 16, half = a.head_dim / 2;
             const int h = t / tph, j = t - h * tph;
@@ -363,13 +385,13 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
                 stc8<COH>(a.qp + qp_offset(h, a.head_dim, m, dim, 1),
                           make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)));
             } else {
-                bf16_t *dst = a.pool + kvf_base(page, a.layer, a.n_layers, 0, h, a.n_kv_heads, a.head_dim) + kf_elem(tok, dim);
+                bf16_t *dst = pool + kvf_base(page, a.layer, a.n_layers, 0, h, a.n_kv_heads, a.head_dim) + kf_elem(tok, dim);
                 stc8<COH>(dst, make_uint2((uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16),
                                           (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16)));
             }
         } else {
             const int n = t * 16 + 4 * kg, h = n / a.head_dim, dim = n - h * a.head_dim;
-            bf16_t *dst = a.pool + kvf_base(page, a.layer, a.n_layers, 1, h, a.n_kv_heads, a.head_dim);
+            bf16_t *dst = pool + kvf_base(page, a.layer, a.n_layers, 1, h, a.n_kv_heads, a.head_dim);
 #pragma unroll
             for (int i = 0; i < 4; ++i) stc2<COH>(dst + vf_elem(tok, dim + i), f32_to_bf16(y[i]));
         }
@@ -754,37 +776,51 @@ __device__ __forceinline__ size_t part_s_index(int n_heads, int head, int split,
 // kv.loaded, else it is requested here.  `after_loads` runs right after the task's own loads have
 // been issued (the persistent kernel puts its weight prefetch there, so that the prefetch queues
 // behind the loads attention is waiting for, not in front of them).
-// TREE: the window is a draft tree; row_mask[m] has bit r set if window row r is row m itself or one
-// of its ancestors, and row m sees the cached positions plus exactly those rows.
-template <int DH, bool COH = false, typename AfterLoads = NoPrefetch, bool TREE = false>
+// MODE 1 (tree): the window is a draft tree; row_mask[m] has bit r set if window row r is row m itself
+// or one of its ancestors, and row m sees the cached positions plus exactly those rows.
+// MODE 2 (batch): the window holds several sequences side by side; this task belongs to the sequence
+// whose cache is (pool, page_table, L) and works on its rows [batch->row0, + n_rows) only; the head's
+// splits of ALL sequences are merged by the last of batch->n_blocks blocks.
+enum { ATTN_CHAIN = 0, ATTN_TREE = 1, ATTN_BATCH = 2 };
+struct AttnBatch {
+    int row0, n_rows, n_blocks;
+    const SeqRef *seqs;
+    const int32_t *row_seq;
+};
+template <int DH, bool COH = false, typename AfterLoads = NoPrefetch, int MODE = ATTN_CHAIN>
 __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, int head, int split, int L,
                                           const uint4 *__restrict__ qp, const bf16_t *__restrict__ pool,
                                           const int32_t *__restrict__ page_table, int M, int layer, int n_layers, int n_heads,
                                           int n_kv_heads, int max_splits, float scale, float *__restrict__ part,
                                           uint32_t *__restrict__ head_counter, bf16_t *__restrict__ xp_att, int cls,
-                                          AfterLoads after_loads = AfterLoads(), const uint32_t *__restrict__ row_mask = nullptr)
+                                          AfterLoads after_loads = AfterLoads(), const uint32_t *__restrict__ row_mask = nullptr,
+                                          const AttnBatch *batch = nullptr)
 {
+    constexpr bool TREE = MODE == ATTN_TREE, BATCH = MODE == ATTN_BATCH;
     const int tid = fresh_tid();
     constexpr int NKS = DH / 32, NDT = DH / 16;
     const int lane = tid & 63, wave = tid >> 6, slot = lane & 15, kg = lane >> 4;
     const int key0 = split * kFastSplit + wave * 16;
-    const bool active = key0 < L + M;
+    const int row0 = BATCH ? batch->row0 : 0, row_end = BATCH ? batch->row0 + batch->n_rows : M;   // this task's rows
+    const int rg0 = row0 >> 3;
+    const bool active = key0 < L + (row_end - row0);
     ANPD_STAMP(0);
 
     if (!kv.loaded)
-        attn_load_kv<DH, COH>(kv, head / (n_heads / n_kv_heads), split, L, M, pool, page_table, layer, n_layers, n_kv_heads, false);
+        attn_load_kv<DH, COH>(kv, head / (n_heads / n_kv_heads), split, L, row_end - row0, pool, page_table, layer, n_layers,
+                              n_kv_heads, false);
     uint4 qf[NKS];
     {
-        const uint4 *q = qp + ((size_t)(head * 4) * NKS) * 64;
+        const uint4 *q = qp + ((size_t)(head * 4 + rg0) * NKS) * 64;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) qf[ks] = ld16_at<COH>(q, (uint32_t)(ks * 64 + lane));
     }
     after_loads();
 
-    for (int rg = 0; rg * 8 < M; ++rg) {
+    for (int rg = rg0; rg * 8 < row_end; ++rg) {
         // ---- scores S[key][row]
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        if (rg > 0) {
+        if (rg > rg0) {
             const uint4 *q = qp + ((size_t)(head * 4 + rg) * NKS) * 64;
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) qf[ks] = ld16_at<COH>(q, (uint32_t)(ks * 64 + lane));
@@ -801,7 +837,9 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
         for (int i = 0; i < 4; ++i) {
             float lo = row_down8(acc[i]);
             const int key = key0 + 4 * kg + i;
-            const bool sees = TREE ? (key < L || (key - L < 32 && ((vis >> (key - L)) & 1u))) : key <= L + m;
+            const bool sees = TREE    ? (key < L || (key - L < 32 && ((vis >> (key - L)) & 1u)))
+                              : BATCH ? (m >= row0 && m < row_end && key <= L + (m - row0))
+                                      : key <= L + m;
             const bool ok = active && slot < 8 && m < M && sees;
             sc[i] = ok ? (acc[i] + lo) * scale : kMasked;
             mx = fmaxf(mx, sc[i]);
@@ -869,10 +907,11 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
                 f32x4 tot = *reinterpret_cast<const f32x4 *>(&sh.red[0][dt][cl][0]);
 #pragma unroll
                 for (int w = 1; w < HW; ++w) tot += *reinterpret_cast<const f32x4 *>(&sh.red[w][dt][cl][0]);
-                if (row < M) stc16<true>(part + part_o_index(head, split, max_splits, row, DH) + 16 * dt + 4 * kg, tot);
+                if (row < M && row >= row0 && row < row_end)
+                    stc16<true>(part + part_o_index(head, split, max_splits, row, DH) + 16 * dt + 4 * kg, tot);
             }
         }
-        if (tid < 8 && rg * 8 + tid < M) {
+        if (tid < 8 && rg * 8 + tid < M && rg * 8 + tid >= row0 && rg * 8 + tid < row_end) {
             const int mm = tid;
             float bmx = sh.wmax[0][mm], dsum = sh.wden[0][mm];
 #pragma unroll
@@ -890,7 +929,7 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
     wait_stores();
     block_sync_lds();
     ANPD_STAMP(3);
-    const int n_blocks = (L + M + kFastSplit - 1) / kFastSplit;
+    const int n_blocks = BATCH ? batch->n_blocks : (L + M + kFastSplit - 1) / kFastSplit;
     if (tid == 0)
         sh.last = __hip_atomic_fetch_add(&head_counter[head * kCounterStride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
                   (uint32_t)(n_blocks - 1);
@@ -907,7 +946,11 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
     const uint2 *ps = reinterpret_cast<const uint2 *>(part + part_s_index(n_heads, head, 0, max_splits, 0, DH));
     for (int idx = tid; idx < M * DQ; idx += kFastThreads) {
         const int row = idx / DQ, e4 = idx - row * DQ;
-        const int ns = (L + row) / kFastSplit + 1;
+        int ns = (L + row) / kFastSplit + 1;
+        if (BATCH) {   // the row's own sequence decides how many splits it has
+            const SeqRef sq = batch->seqs[batch->row_seq[row]];
+            ns = (*sq.len_ptr + (row - sq.row0)) / kFastSplit + 1;
+        }
         float g = kMasked;
         if (ns > SB)   // long contexts: the maximum needs a pass of its own
             for (int s2 = 0; s2 < ns; ++s2) g = fmaxf(g, __uint_as_float(ld8_at<true>(ps, (uint32_t)(s2 * 32 + row)).x));
@@ -960,8 +1003,31 @@ __global__ __launch_bounds__(kFastThreads) void attn_fast_kernel(const uint4 *__
     if ((int)blockIdx.y * kFastSplit >= L + M) return;
     AttnKV<DH> kv;
     kv.loaded = false;
-    attn_task<DH, false, NoPrefetch, TREE>(sh, kv, blockIdx.x, blockIdx.y, L, qp, pool, page_table, M, layer, n_layers, n_heads,
-                                           n_kv_heads, max_splits, scale, part, head_counter, xp_att, cls, NoPrefetch(), row_mask);
+    attn_task<DH, false, NoPrefetch, TREE ? ATTN_TREE : ATTN_CHAIN>(sh, kv, blockIdx.x, blockIdx.y, L, qp, pool, page_table, M, layer,
+                                                                    n_layers, n_heads, n_kv_heads, max_splits, scale, part,
+                                                                    head_counter, xp_att, cls, NoPrefetch(), row_mask);
+}
+
+// Several sequences' windows in one step: block (head, split, sequence) works on that sequence's rows
+// against that sequence's cache.   grid: (n_heads, largest number of splits of any sequence, n_seq).
+template <int DH>
+__global__ __launch_bounds__(kFastThreads) void attn_batch_kernel(const uint4 *__restrict__ qp, const SeqRef *__restrict__ seqs,
+                                                           const int32_t *__restrict__ row_seq, int n_blocks, int M, int layer,
+                                                           int n_layers, int n_heads, int n_kv_heads, int max_splits,
+                                                           float scale, float *__restrict__ part,
+                                                           uint32_t *__restrict__ head_counter, bf16_t *__restrict__ xp_att,
+                                                           int cls)
+{
+    __shared__ AttnShared<DH> sh;
+    const SeqRef sq = seqs[blockIdx.z];
+    const int L = *sq.len_ptr;
+    if ((int)blockIdx.y * kFastSplit >= L + sq.n_rows) return;
+    AttnKV<DH> kv;
+    kv.loaded = false;
+    AttnBatch bt = {sq.row0, sq.n_rows, n_blocks, seqs, row_seq};
+    attn_task<DH, false, NoPrefetch, ATTN_BATCH>(sh, kv, blockIdx.x, blockIdx.y, L, qp, sq.pool, sq.page_table, M, layer, n_layers,
+                                                 n_heads, n_kv_heads, max_splits, scale, part, head_counter, xp_att, cls,
+                                                 NoPrefetch(), nullptr, &bt);
 }
 
 // After a draft tree has been verified: the accepted path's rows path[1..a] sit in cache slots
@@ -985,6 +1051,29 @@ __global__ __launch_bounds__(128) void kvf_compact_kernel(bf16_t *__restrict__ p
             pool[dofs] = pool[so];
         }
         __syncthreads();
+    }
+}
+
+// Acceptance for several sequences verified in one step, after argmax_accept_kernel has left the
+// per-row predictions in result[2..]: Algorithm 1's rule inside every sequence's own rows.  Sequence s
+// gets result[67 + 2 s] = accepted, result[68 + 2 s] = next, and its length advances by 1 + accepted.
+// One thread.
+__global__ void accept_batch_kernel(const int32_t *__restrict__ window, const SeqRef *__restrict__ seqs, int n_seq, int mode,
+                                    int32_t *__restrict__ result)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const int32_t *pred = result + 2;
+    for (int s = 0; s < n_seq; ++s) {
+        const int r0 = seqs[s].row0, n = seqs[s].n_rows;
+        int a = 0;
+        if (mode == 0) {
+            while (a < n - 1 && window[r0 + a + 1] == pred[r0 + a]) ++a;
+        } else {
+            a = n - 1;
+        }
+        result[67 + 2 * s] = a;
+        result[68 + 2 * s] = pred[r0 + a];
+        *seqs[s].len_ptr += 1 + a;
     }
 }
 

@@ -533,7 +533,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             for (int t = blockIdx.x; t < n_tasks; t += grid) {
                 const int head = t % n_heads, split = t / n_heads;
                 if (t != (int)blockIdx.x) kv.loaded = false;
-                attn_task<DH, true, decltype(prefetch_o), TREE>(attn_shared<DH>(sh), kv, head, split, L, (const uint4 *)g->qp, g->pool,
+                attn_task<DH, true, decltype(prefetch_o), TREE ? ATTN_TREE : ATTN_CHAIN>(attn_shared<DH>(sh), kv, head, split, L, (const uint4 *)g->qp, g->pool,
                                                                 g->page_table, M, l, n_layers, n_heads, g->n_kv_heads, g->max_splits, g->scale,
                                                                 g->part, g->head_counter, g->xp_att, 8, prefetch_o,
                                                                 (const uint32_t *)g->mask);
