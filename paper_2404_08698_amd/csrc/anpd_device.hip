@@ -248,9 +248,17 @@ int32_t launch_fast(FastArgs &a, int n_cu, bool force_stream, hipStream_t st)
         if (blocks < 1) blocks = 1;
         dim3 grid((unsigned)blocks), block(kFastWaves * 64);
         const int per_block = (a.n_tiles + blocks - 1) / blocks;
-        if (nt == 2) {
+        if (nt == 2 && per_block <= 2) {
             size_t smem = (size_t)2 * kFastWaves * 2 * 256 * sizeof(float);
             hipLaunchKernelGGL((gemm_group_kernel<2, 2, EPI>), grid, block, smem, st, a);
+        } else if (nt == 2) {
+            size_t smem = (size_t)4 * kFastWaves * 2 * 256 * sizeof(float);
+            static bool attr_set2 = false;
+            if (!attr_set2) {
+                HIP_TRY(hipFuncSetAttribute((const void *)gemm_group_kernel<2, 4, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+                attr_set2 = true;
+            }
+            hipLaunchKernelGGL((gemm_group_kernel<2, 4, EPI>), grid, block, smem, st, a);
         } else if (per_block <= 2) {
             size_t smem = (size_t)2 * kFastWaves * 4 * 256 * sizeof(float);
             hipLaunchKernelGGL((gemm_group_kernel<4, 2, EPI>), grid, block, smem, st, a);
