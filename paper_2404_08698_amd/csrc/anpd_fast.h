@@ -787,14 +787,17 @@ struct AttnBatch {
     const SeqRef *seqs;
     const int32_t *row_seq;
 };
-template <int DH, bool COH = false, typename AfterLoads = NoPrefetch, int MODE = ATTN_CHAIN>
+// `after_values` runs once the task's last use of its K / V registers is behind it (the persistent kernel
+// requests its next task's page there: into the same registers, while this task's partial results are
+// reduced, stored and merged).
+template <int DH, bool COH = false, typename AfterLoads = NoPrefetch, int MODE = ATTN_CHAIN, typename AfterValues = NoPrefetch>
 __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, int head, int split, int L,
                                           const uint4 *__restrict__ qp, const bf16_t *__restrict__ pool,
                                           const int32_t *__restrict__ page_table, int M, int layer, int n_layers, int n_heads,
                                           int n_kv_heads, int max_splits, float scale, float *__restrict__ part,
                                           uint32_t *__restrict__ head_counter, bf16_t *__restrict__ xp_att, int cls,
                                           AfterLoads after_loads = AfterLoads(), const uint32_t *__restrict__ row_mask = nullptr,
-                                          const AttnBatch *batch = nullptr)
+                                          const AttnBatch *batch = nullptr, AfterValues after_values = AfterValues())
 {
     constexpr bool TREE = MODE == ATTN_TREE, BATCH = MODE == ATTN_BATCH;
     const int tid = fresh_tid();
@@ -883,6 +886,7 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
             for (int i = 0; i < 4; ++i) lo[i] = row_down8(o[i]);
             ot[dt] = o + lo;
         }
+        if ((rg + 1) * 8 >= row_end) after_values();
         // ---- add the waves' tiles: wave w + H into wave w (H = half the waves), then waves 0..H-1 in
         // order, one or two dim tiles per wave.  LDS is addressed by compacted lane (kg * 8 + slot).
         const int cl = kg * 8 + (slot & 7);

@@ -532,11 +532,18 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             };
             for (int t = blockIdx.x; t < n_tasks; t += grid) {
                 const int head = t % n_heads, split = t / n_heads;
-                if (t != (int)blockIdx.x) kv.loaded = false;
-                attn_task<DH, true, decltype(prefetch_o), TREE ? ATTN_TREE : ATTN_CHAIN>(attn_shared<DH>(sh), kv, head, split, L, (const uint4 *)g->qp, g->pool,
-                                                                g->page_table, M, l, n_layers, n_heads, g->n_kv_heads, g->max_splits, g->scale,
-                                                                g->part, g->head_counter, g->xp_att, 8, prefetch_o,
-                                                                (const uint32_t *)g->mask);
+                // a block with several tasks (long contexts) requests the next task's page as soon as this
+                // task has used its own: every wait for the block's counters is over by now
+                const int tn = t + grid;
+                auto next_page = [&]() {
+                    if (tn < n_tasks)
+                        attn_load_kv<DH, true>(kv, (tn % n_heads) / (n_heads / g->n_kv_heads), tn / n_heads, L, M, g->pool, g->page_table,
+                                               l, n_layers, g->n_kv_heads, false);
+                };
+                attn_task<DH, true, decltype(prefetch_o), TREE ? ATTN_TREE : ATTN_CHAIN, decltype(next_page)>(
+                    attn_shared<DH>(sh), kv, head, split, L, (const uint4 *)g->qp, g->pool, g->page_table, M, l, n_layers, n_heads,
+                    g->n_kv_heads, g->max_splits, g->scale, g->part, g->head_counter, g->xp_att, 8, prefetch_o,
+                    (const uint32_t *)g->mask, nullptr, next_page);
                 block_sync_lds();
             }
             prefetch_o();
