@@ -956,8 +956,15 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
             ns = (*sq.len_ptr + (row - sq.row0)) / kFastSplit + 1;
         }
         float g = kMasked;
-        if (ns > SB)   // long contexts: the maximum needs a pass of its own
-            for (int s2 = 0; s2 < ns; ++s2) g = fmaxf(g, __uint_as_float(ld8_at<true>(ps, (uint32_t)(s2 * 32 + row)).x));
+        if (ns > SB) {   // long contexts: the maximum needs a pass of its own, SB splits per round trip
+            for (int s0 = 0; s0 < ns; s0 += SB) {
+                float mv[SB];
+#pragma unroll
+                for (int j = 0; j < SB; ++j) mv[j] = __uint_as_float(ld8_at<true>(ps, (uint32_t)((s0 + j < ns ? s0 + j : s0) * 32 + row)).x);
+#pragma unroll
+                for (int j = 0; j < SB; ++j) g = fmaxf(g, mv[j]);
+            }
+        }
         f32x4 o = {0.f, 0.f, 0.f, 0.f};
         float den = 0.f;
         for (int s0 = 0; s0 < ns; s0 += SB) {
