@@ -787,6 +787,7 @@ struct AttnBatch {
     const SeqRef *seqs;
     const int32_t *row_seq;
 };
+// `publish`: see the merge step below.
 // `after_values` runs once the task's last use of its K / V registers is behind it (the persistent kernel
 // requests its next task's page there: into the same registers, while this task's partial results are
 // reduced, stored and merged).
@@ -797,7 +798,8 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
                                           int n_kv_heads, int max_splits, float scale, float *__restrict__ part,
                                           uint32_t *__restrict__ head_counter, bf16_t *__restrict__ xp_att, int cls,
                                           AfterLoads after_loads = AfterLoads(), const uint32_t *__restrict__ row_mask = nullptr,
-                                          const AttnBatch *batch = nullptr, AfterValues after_values = AfterValues())
+                                          const AttnBatch *batch = nullptr, AfterValues after_values = AfterValues(),
+                                          int publish = 1)
 {
     constexpr bool TREE = MODE == ATTN_TREE, BATCH = MODE == ATTN_BATCH;
     const int tid = fresh_tid();
@@ -928,15 +930,18 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
         ANPD_STAMP(11);
     }
 
-    // ---- the last block of this head merges the splits
+    // ---- the last block of this head merges the splits.  publish = number of finished tasks of this head
+    // that this call reports (a block that runs several tasks of one head reports them together with the
+    // last one: one wait for the stores and one trip to the counter instead of one per task); 0 = none yet.
     ANPD_STAMP(2);
+    if (publish == 0) return;
     wait_stores();
     block_sync_lds();
     ANPD_STAMP(3);
     const int n_blocks = BATCH ? batch->n_blocks : (L + M + kFastSplit - 1) / kFastSplit;
     if (tid == 0)
-        sh.last = __hip_atomic_fetch_add(&head_counter[head * kCounterStride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                  (uint32_t)(n_blocks - 1);
+        sh.last = __hip_atomic_fetch_add(&head_counter[head * kCounterStride], (uint32_t)publish, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT) + (uint32_t)publish == (uint32_t)n_blocks;
     block_sync_lds();
     ANPD_STAMP(4);
     if (!sh.last) return;

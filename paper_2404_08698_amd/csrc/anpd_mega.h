@@ -530,8 +530,15 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
                 if (!fetched) load_wchunk(pf, o_src, blockIdx.x, 0, wave, lane);
                 fetched = true;
             };
+            // with the grid a multiple of the head count all tasks of a block belong to one head: they are
+            // reported to the head's counter together, by the last one
+            const bool one_head = grid % n_heads == 0;
+            int unreported = 0;
             for (int t = blockIdx.x; t < n_tasks; t += grid) {
                 const int head = t % n_heads, split = t / n_heads;
+                unreported += 1;
+                const int publish = (!one_head || t + grid >= n_tasks) ? unreported : 0;
+                if (publish) unreported = 0;
                 // a block with several tasks (long contexts) requests the next task's page as soon as this
                 // task has used its own: every wait for the block's counters is over by now
                 const int tn = t + grid;
@@ -543,7 +550,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
                 attn_task<DH, true, decltype(prefetch_o), TREE ? ATTN_TREE : ATTN_CHAIN, decltype(next_page)>(
                     attn_shared<DH>(sh), kv, head, split, L, (const uint4 *)g->qp, g->pool, g->page_table, M, l, n_layers, n_heads,
                     g->n_kv_heads, g->max_splits, g->scale, g->part, g->head_counter, g->xp_att, 8, prefetch_o,
-                    (const uint32_t *)g->mask, nullptr, next_page);
+                    (const uint32_t *)g->mask, nullptr, next_page, publish);
                 block_sync_lds();
             }
             prefetch_o();
