@@ -520,7 +520,9 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             // what the O phase waits for.
             if (tid == 0) {
                 const uint32_t target = (uint32_t)(3 * g->head_dim / 16) * (g->ready_epoch + (uint32_t)l + 1u);
-                for (int t = blockIdx.x; t < n_tasks; t += grid) wait_count(bar, g->qkv_ready + kCounterStride * (t % n_heads), target);
+                // (with the grid a multiple of the head count all of a block's tasks wait for the same head)
+                const int t_end = grid % n_heads == 0 ? ((int)blockIdx.x < n_tasks ? (int)blockIdx.x + 1 : 0) : n_tasks;
+                for (int t = blockIdx.x; t < t_end; t += grid) wait_count(bar, g->qkv_ready + kCounterStride * (t % n_heads), target);
             }
             block_sync_lds();
             bar_stamp(bar);
