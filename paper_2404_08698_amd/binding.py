@@ -67,6 +67,13 @@ def lib():
     if not os.path.exists(LIB_PATH):
         raise ImportError("libanpd.so is not built: run `python -m paper_2404_08698_amd.build` "
                           "(there is no fallback path)")
+    # PyTorch ships its own copy of the HIP runtime.  Load it first, so that this library binds to the
+    # runtime the device memory comes from: with the order reversed the process ends up with two runtimes,
+    # and the second one finds no device.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = C.CDLL(LIB_PATH)
     i32p, vp = C.POINTER(C.c_int32), C.c_void_p
     L.anpd_last_error.restype = C.c_char_p
