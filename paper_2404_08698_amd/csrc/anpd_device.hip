@@ -251,6 +251,14 @@ int32_t launch_fast(FastArgs &a, int n_cu, bool force_stream, hipStream_t st)
         if (nt == 2 && per_block <= 2) {
             size_t smem = (size_t)2 * kFastWaves * 2 * 256 * sizeof(float);
             hipLaunchKernelGGL((gemm_group_kernel<2, 2, EPI>), grid, block, smem, st, a);
+        } else if (nt == 2 && per_block > 4) {
+            size_t smem = (size_t)8 * kFastWaves * 2 * 256 * sizeof(float);
+            static bool attr_set3 = false;
+            if (!attr_set3) {
+                HIP_TRY(hipFuncSetAttribute((const void *)gemm_group_kernel<2, 8, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+                attr_set3 = true;
+            }
+            hipLaunchKernelGGL((gemm_group_kernel<2, 8, EPI>), grid, block, smem, st, a);
         } else if (nt == 2) {
             size_t smem = (size_t)4 * kFastWaves * 2 * 256 * sizeof(float);
             static bool attr_set2 = false;
