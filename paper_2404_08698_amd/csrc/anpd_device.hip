@@ -1382,6 +1382,7 @@ int32_t anpd_prefill(anpd_model_t *m, anpd_kv_t *kv, const int32_t *tokens, int3
         return ANPD_OK;
     }
 
+    if (m->cfg.d_model > 8192) return fail(ANPD_E_UNIMPLEMENTED, "anpd_prefill: d_model above 8192 is not supported in one pass");
     const PrefillLayout PL = make_prefill_layout(m->cfg, n_tokens);
     if (!workspace || ((uintptr_t)workspace & 255) != 0) return fail(ANPD_E_INVAL, "anpd_prefill: workspace must be a 256-byte aligned device buffer");
     if (workspace_bytes < PL.total)

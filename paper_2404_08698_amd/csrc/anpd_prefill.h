@@ -97,34 +97,57 @@ __global__ __launch_bounds__(256) void prefill_norm_kernel(const bf16_t *__restr
                                                             const bf16_t *__restrict__ gain, bf16_t *__restrict__ xq, int nks,
                                                             int d, int L, int P, float inv_d, float eps)
 {
+    constexpr int NV = 8;   // 1024-column pieces of a row kept in registers (d <= 8192)
     __shared__ float red[4];
     const int m = blockIdx.x, r = m - (L & 15);
     const bool valid = r >= 0 && r < P;
     const size_t rows = (size_t)gridDim.x;
     float *xr = x + (size_t)m * d;
+    f32x4 v[NV];
     float ss = 0.f;
     if (valid) {
+        // every load of the row is requested before the first one is used
         const bf16_t *er = EMBED ? E + (size_t)tok[r] * d : nullptr;
-        for (int k = 4 * threadIdx.x; k < d; k += 1024) {
-            f32x4 v;
-            if (EMBED) {
-                v = widen4(*reinterpret_cast<const uint2 *>(er + k));
-            } else {
-                v = *reinterpret_cast<const f32x4 *>(xr + k);
-                for (int s = 0; s < S; ++s) v += *reinterpret_cast<const f32x4 *>(part + ((size_t)s * rows + m) * d + k);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int k = 4 * threadIdx.x + 1024 * i;
+            v[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            if (k < d) v[i] = EMBED ? widen4(*reinterpret_cast<const uint2 *>(er + k)) : *reinterpret_cast<const f32x4 *>(xr + k);
+        }
+        if (!EMBED) {
+            for (int s = 0; s < S; ++s) {   // split order
+                f32x4 p[NV];
+#pragma unroll
+                for (int i = 0; i < NV; ++i) {
+                    const int k = 4 * threadIdx.x + 1024 * i;
+                    p[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    if (k < d) p[i] = *reinterpret_cast<const f32x4 *>(part + ((size_t)s * rows + m) * d + k);
+                }
+#pragma unroll
+                for (int i = 0; i < NV; ++i) v[i] += p[i];
             }
-            if (EMBED || S > 0) *reinterpret_cast<f32x4 *>(xr + k) = v;
-            ss = fmaf(v[3], v[3], fmaf(v[2], v[2], fmaf(v[1], v[1], fmaf(v[0], v[0], ss))));
+        }
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int k = 4 * threadIdx.x + 1024 * i;
+            if (k < d) {
+                if (EMBED || S > 0) *reinterpret_cast<f32x4 *>(xr + k) = v[i];
+                ss = fmaf(v[i][3], v[i][3], fmaf(v[i][2], v[i][2], fmaf(v[i][1], v[i][1], fmaf(v[i][0], v[i][0], ss))));
+            }
         }
     }
     ss = wave_sum(ss);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
     const float rinv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) * inv_d + eps);
-    for (int k = 4 * threadIdx.x; k < d; k += 1024) {
-        f32x4 h = {0.f, 0.f, 0.f, 0.f};
-        if (valid) h = *reinterpret_cast<const f32x4 *>(xr + k) * rinv * widen4(*reinterpret_cast<const uint2 *>(gain + k));
-        xq_store4(xq, nks, m, k, h);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int k = 4 * threadIdx.x + 1024 * i;
+        if (k < d) {
+            f32x4 h = {0.f, 0.f, 0.f, 0.f};
+            if (valid) h = v[i] * rinv * widen4(*reinterpret_cast<const uint2 *>(gain + k));
+            xq_store4(xq, nks, m, k, h);
+        }
     }
 }
 
