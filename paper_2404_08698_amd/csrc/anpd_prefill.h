@@ -31,7 +31,7 @@ namespace anpd {
 constexpr int kPgThreads = 512;       // GEMM block: 8 waves, 4 (features) x 2 (rows)
 constexpr int kPfTN = 4, kPfTM = 4;   // wave tile: 4 weight tiles x 4 row groups
 constexpr int kPgStages = 4;          // LDS ring of k-steps
-constexpr int kPgLead = 3;            // k-steps requested ahead of the one being multiplied
+constexpr int kPgLead = 2;            // k-steps per block barrier (a round); the next round is requested one round ahead
 constexpr int kPgUnits = 32;          // 1 KiB fragments per k-step: 16 weight tiles, 8 row groups x (hi, lo)
 constexpr int kPgSplit = 4;           // K splits of the residual GEMMs
 constexpr size_t kPgLdsBytes = (size_t)kPgStages * kPgUnits * 1024;
@@ -230,13 +230,14 @@ __device__ __forceinline__ void prefill_epilogue(const PrefillArgs &a, int tile,
 // needs 16 weight fragments and 16 activation fragments of 1 KiB; each wave
 // requests four of them straight into LDS (buffer loads with the LDS bit:
 // lane i's 16 bytes land at base + 16 i, the fragment order itself; absent
-// tiles and row groups read zeros and fetch nothing), three k-steps ahead of
-// the matrix cores through a ring of four stages, and every wave then reads
-// its 12 fragments from LDS.  A fragment thus crosses the L2 -> CU path once
-// per block instead of once per wave that uses it.
-// One block barrier per k-step: it publishes the stage whose loads the waves
-// have just waited for, and frees the stage read in the previous iteration
-// for the request that follows it.
+// tiles and row groups read zeros and fetch nothing), one round of two k-steps
+// ahead of the matrix cores through a ring of four stages, and every wave then
+// reads its 12 fragments per k-step from LDS.  A fragment thus crosses the
+// L2 -> CU path once per block instead of once per wave that uses it.
+// One block barrier per round of two k-steps: it publishes the two stages
+// whose loads the waves have just waited for, and frees the two stages read in
+// the previous round for the requests that follow it (one barrier per k-step
+// with three stages in flight measured 2 % slower).
 // RESIDUAL GEMMs (few output features) are split S ways along K so that the
 // grid fills the chip; the S partial tiles go to `part` and are added to the
 // residual stream, in split order, by the norm kernel that follows.  S is
@@ -339,37 +340,31 @@ __global__ __launch_bounds__(kPgThreads) void prefill_gemm_kernel(PrefillArgs a)
                 acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[t]), __builtin_bit_cast(bf16x8, xl[g]),
                                                                     acc[t][g], 0, 0, 0);
     };
-    // Stage s is published by a block barrier that every wave reaches after its own loads of that
-    // stage have landed (at most the two younger stages still outstanding) and its own reads of
-    // stage s - 1 have returned; that barrier also frees the slot of stage s - 1 for stage s + 3.
-    auto publish = [&](int s) {
-        if (s + 2 < n_it) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        asm volatile("s_barrier" ::: "memory");
-        if (s + kPgLead < n_it) request(s + kPgLead);
-    };
+    // Two k-steps per block barrier.  The barrier of round j is reached by a wave once its own loads of
+    // stages 2j and 2j + 1 have landed (at most the two younger stages still outstanding) and its reads of
+    // the previous round's stages have returned; it publishes this round's stages and frees the previous
+    // round's slots for stages 2j + 2 and 2j + 3.  All four slots are requested before the first round.
     u32x4_t wA[kPfTN], hA[kPfTM], lA[kPfTM], wB[kPfTN], hB[kPfTM], lB[kPfTM];
 #pragma unroll
-    for (int s = 0; s < kPgLead; ++s)
+    for (int s = 0; s < kPgStages; ++s)
         if (s < n_it) request(s);
-    if (n_it > 0) {
-        publish(0);
-        read_stage(wA, hA, lA, 0);
-    }
-    // the reads of the next stage are in flight during the MFMAs of this one
     for (int it = 0; it < n_it; it += 2) {
-        wait_reads(wA, hA, lA);
-        if (it + 1 < n_it) {
-            publish(it + 1);
-            read_stage(wB, hB, lB, it + 1);
+        // (the next round's stages are requested after this barrier, so only in round 0 is anything younger
+        // than this round's stages outstanding: stages 2 and 3 from the prologue)
+        if (it == 0 && n_it > 3) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if (it == 0 && n_it == 3) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("s_barrier" ::: "memory");
+        if (it > 0) {
+            if (it + 2 < n_it) request(it + 2);
+            if (it + 3 < n_it) request(it + 3);
         }
+        read_stage(wA, hA, lA, it);
+        if (it + 1 < n_it) read_stage(wB, hB, lB, it + 1);
+        wait_reads(wA, hA, lA);
         mma(wA, hA, lA);
         if (it + 1 < n_it) {
             wait_reads(wB, hB, lB);
-            if (it + 2 < n_it) {
-                publish(it + 2);
-                read_stage(wA, hA, lA, it + 2);
-            }
             mma(wB, hB, lB);
         }
     }
