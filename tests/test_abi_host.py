@@ -92,3 +92,12 @@ def test_device_side_argument_errors_need_no_gpu():
     assert L.anpd_verify(None, None, None, 1, 0, ctypes.byref(a), ctypes.byref(a), None, None, None) == B.E_INVAL
     assert L.anpd_linear(None, None, None, 1, 16, 8, 0, 1, None, 0, None) == B.E_INVAL
     assert L.anpd_linear_workspace_bytes(0, 64) == 0
+    assert L.anpd_verify_tree(None, None, None, None, 1, ctypes.byref(a), ctypes.byref(a), None, None, None, None) == B.E_INVAL
+    assert L.anpd_verify_batch(None, None, 1, None, None, 0, ctypes.byref(a), ctypes.byref(a), None, None) == B.E_INVAL
+    assert L.anpd_prefill(None, None, None, 1, ctypes.byref(a), None, None, 0, None) == B.E_INVAL
+    assert L.anpd_prefill_workspace_bytes(None, 5) == 0
+    grouped = B.ModelCfg(2, 256, 4, 64, 688, 1024, 1e-5, 10000.0, B.BF16, 16, 8, 256, B.GEMM_AUTO, 2)
+    plain = B.ModelCfg(2, 256, 4, 64, 688, 1024, 1e-5, 10000.0, B.BF16, 16, 8, 256, B.GEMM_AUTO, 0)
+    assert 0 < L.anpd_model_workspace_bytes(ctypes.byref(grouped)) < L.anpd_model_workspace_bytes(ctypes.byref(plain))
+    bad = B.ModelCfg(2, 256, 4, 64, 688, 1024, 1e-5, 10000.0, B.BF16, 16, 8, 256, B.GEMM_AUTO, 3)
+    assert L.anpd_model_workspace_bytes(ctypes.byref(bad)) == 0 and b"n_kv_heads" in L.anpd_last_error()
