@@ -248,7 +248,9 @@ int32_t anpd_verify_tree(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, 
  *   length advances by 1 + its own accepted count.
  *   out_logits (nullable, DEVICE, total rows * vocab floats): rows in sequence order.
  * A sequence's rows, results and cache contents are bit-identical to verifying it alone with
- * anpd_verify.  Matrix-core path only (bf16 weights): ANPD_E_UNIMPLEMENTED otherwise.
+ * anpd_verify.  Batches of at most 8 rows in all run as the one-kernel step (its several-sequences
+ * form), larger ones as one launch per operation.  Matrix-core path only (bf16 weights):
+ * ANPD_E_UNIMPLEMENTED otherwise.
  * Errors: as anpd_verify; ANPD_E_INVAL if two sequences share a cache. */
 int32_t anpd_verify_batch(anpd_model_t *m, anpd_kv_t *const *kvs, int32_t n_seq, const int32_t *const *windows,
                           const int32_t *n_windows, int32_t mode, int32_t *out_accepted, int32_t *out_next,

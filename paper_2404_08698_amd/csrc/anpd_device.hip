@@ -158,6 +158,7 @@ struct anpd_model {
     int n_cu;
     bool mega;            // the one-kernel step is available
     bool mega_tree;       // ... and so is its draft-tree form
+    bool mega_batch;      // ... and its several-sequences form
     long long *trace;     // optional device buffer for barrier timestamps
     int mega_grid;
     bool plain_launch;    // launch the one-kernel step without the cooperative-launch API (profiling aid)
@@ -604,8 +605,16 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
 
 // The step as one persistent kernel (window class 8).
 // tree (nullable): the pinned draft-tree arrays parent[32], depth[32], mask[32] of a window of at most 8 rows.
+// batch (nullable): several sequences side by side (kv is null then): seqs[n_seq], row_seq[M] and the lengths the host
+// knows them to have.
+struct MegaBatch {
+    int n_seq;
+    const SeqRef *seqs;
+    const int32_t *row_seq;
+    const int32_t *len;
+};
 int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, int mode, bool want_logits, hipStream_t st,
-                      const int32_t *tree = nullptr)
+                      const int32_t *tree = nullptr, const MegaBatch *batch = nullptr)
 {
     const anpd_model_cfg &c = m->cfg;
     const Layout &L = m->lay;
@@ -625,7 +634,7 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, 
     g.qp = (bf16_t *)(ws + L.qp);
     g.ssp_a = (float *)(ws + L.ssp_a); g.ssp_b = (float *)(ws + L.ssp_b); g.part = (float *)(ws + L.part);
     g.head_counter = (uint32_t *)(ws + L.head_ctr);
-    g.pool = (bf16_t *)kv->pool; g.page_table = kv->d_table; g.len_ptr = kv->d_len;
+    if (kv) { g.pool = (bf16_t *)kv->pool; g.page_table = kv->d_table; g.len_ptr = kv->d_len; }
     g.rope = (const float2 *)(ws + L.rope_tab);
     g.max_splits = L.max_splits;
     g.logits = want_logits ? (float *)(ws + L.logits) : nullptr;
@@ -647,11 +656,29 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, 
             g.depth[i] = tree[ANPD_MAX_WINDOW + i];
             g.mask[i] = (uint32_t)tree[2 * ANPD_MAX_WINDOW + i];
         }
+    if (batch) {
+        g.n_seq = batch->n_seq;
+        g.host_batch = m->pin_dev + 256;
+        int tasks = 0;
+        for (int s = 0; s < batch->n_seq; ++s) {
+            g.seqs[s] = batch->seqs[s];
+            g.task0[s] = tasks;
+            const int splits = (batch->len[s] + batch->seqs[s].n_rows + kFastSplit - 1) / kFastSplit;
+            tasks += splits * c.n_heads;
+            g.n_att_blocks += splits;
+        }
+        g.task0[batch->n_seq] = tasks;
+        for (int i = 0; i < M; ++i) g.row_seq[i] = batch->row_seq[i];
+    }
     m->ev_used = 0;
     mark(m, -1, st);
     void *args[] = {&g};
-    const void *fn = c.head_dim == 128 ? (tree ? (const void *)verify_mega_kernel<128, true> : (const void *)verify_mega_kernel<128, false>)
-                                       : (tree ? (const void *)verify_mega_kernel<64, true> : (const void *)verify_mega_kernel<64, false>);
+    const int form = batch ? MEGA_BATCH : (tree ? MEGA_TREE : MEGA_CHAIN);
+    const void *fn128[] = {(const void *)verify_mega_kernel<128, MEGA_CHAIN>, (const void *)verify_mega_kernel<128, MEGA_TREE>,
+                           (const void *)verify_mega_kernel<128, MEGA_BATCH>};
+    const void *fn64[] = {(const void *)verify_mega_kernel<64, MEGA_CHAIN>, (const void *)verify_mega_kernel<64, MEGA_TREE>,
+                          (const void *)verify_mega_kernel<64, MEGA_BATCH>};
+    const void *fn = c.head_dim == 128 ? fn128[form] : fn64[form];
     if (m->plain_launch) {
         // profiling aid (see anpd_model_create): an ordinary launch of the same grid
         HIP_TRY(hipLaunchKernel(fn, dim3((unsigned)m->mega_grid), dim3(kFastThreads), args, 0, st));
@@ -914,6 +941,7 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
     int32_t prc = ANPD_OK;
     m->mega = false;
     m->mega_tree = false;
+    m->mega_batch = false;
     m->trace = nullptr;
     m->mega_grid = 0;
     m->bar_epoch = 0;
@@ -948,9 +976,15 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
             m->mega_grid = m->n_cu;
             int per_cu_t = 0;
             hipError_t te = cfg->head_dim == 128
-                                ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_t, verify_mega_kernel<128, true>, kFastThreads, 0)
-                                : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_t, verify_mega_kernel<64, true>, kFastThreads, 0);
+                                ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_t, verify_mega_kernel<128, MEGA_TREE>, kFastThreads, 0)
+                                : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_t, verify_mega_kernel<64, MEGA_TREE>, kFastThreads, 0);
             m->mega_tree = te == hipSuccess && per_cu_t >= 1;
+            if (te != hipSuccess) (void)hipGetLastError();
+            int per_cu_b = 0;
+            te = cfg->head_dim == 128
+                     ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_b, verify_mega_kernel<128, MEGA_BATCH>, kFastThreads, 0)
+                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_b, verify_mega_kernel<64, MEGA_BATCH>, kFastThreads, 0);
+            m->mega_batch = te == hipSuccess && per_cu_b >= 1;
             if (te != hipSuccess) (void)hipGetLastError();
         } else {
             (void)hipGetLastError();
@@ -1322,17 +1356,30 @@ int32_t anpd_verify_batch(anpd_model_t *m, anpd_kv_t *const *kvs, int32_t n_seq,
             row_seq[row] = s;
         }
     }
-    HIP_TRY(hipMemcpyAsync(m->ws + m->lay.tok, m->pin, sizeof(int32_t) * (size_t)total, hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(m->ws + m->lay.batch, row_seq, sizeof(int32_t) * (size_t)total, hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(m->ws + m->lay.batch + ANPD_MAX_WINDOW * sizeof(int32_t), seqs, sizeof(SeqRef) * (size_t)n_seq,
-                           hipMemcpyHostToDevice, st));
-    int32_t rc = run_step_fast(m, nullptr, total, mode, st, false, &bl);
-    if (rc != ANPD_OK) return rc;
+    // At most 8 rows in all (decoding batches, short windows): the persistent kernel takes the sequences by
+    // value and writes the results into the pinned buffer itself; otherwise copies and the fused launches.
+    const bool one_kernel = m->mega && m->mega_batch && total <= 8;
     int32_t *res = m->pin + 256;
-    HIP_TRY(hipMemcpyAsync(res, m->ws + m->lay.result + 67 * sizeof(int32_t), sizeof(int32_t) * 2 * (size_t)n_seq, hipMemcpyDeviceToHost, st));
+    int32_t rc;
+    if (one_kernel) {
+        int32_t lens[8];
+        for (int s = 0; s < n_seq; ++s) lens[s] = kvs[s]->len;
+        MegaBatch mb = {n_seq, seqs, row_seq, lens};
+        rc = run_step_mega(m, nullptr, m->pin, total, mode, out_logits != nullptr, st, nullptr, &mb);
+        if (rc != ANPD_OK) return rc;
+    } else {
+        HIP_TRY(hipMemcpyAsync(m->ws + m->lay.tok, m->pin, sizeof(int32_t) * (size_t)total, hipMemcpyHostToDevice, st));
+        HIP_TRY(hipMemcpyAsync(m->ws + m->lay.batch, row_seq, sizeof(int32_t) * (size_t)total, hipMemcpyHostToDevice, st));
+        HIP_TRY(hipMemcpyAsync(m->ws + m->lay.batch + ANPD_MAX_WINDOW * sizeof(int32_t), seqs, sizeof(SeqRef) * (size_t)n_seq,
+                               hipMemcpyHostToDevice, st));
+        rc = run_step_fast(m, nullptr, total, mode, st, false, &bl);
+        if (rc != ANPD_OK) return rc;
+        HIP_TRY(hipMemcpyAsync(res, m->ws + m->lay.result + 67 * sizeof(int32_t), sizeof(int32_t) * 2 * (size_t)n_seq, hipMemcpyDeviceToHost, st));
+    }
     if (out_logits)
         HIP_TRY(hipMemcpyAsync(out_logits, m->ws + m->lay.logits, sizeof(float) * (size_t)total * m->cfg.vocab, hipMemcpyDeviceToDevice, st));
     HIP_TRY(hipStreamSynchronize(st));
+    if (one_kernel && barrier_gave_up(m, st)) return fail(ANPD_E_HIP, "anpd_verify_batch: the persistent kernel timed out at a grid barrier");
     collect_marks(m);
     for (int s = 0; s < n_seq; ++s) {
         out_accepted[s] = res[2 * s];

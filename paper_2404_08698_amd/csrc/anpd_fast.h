@@ -271,12 +271,19 @@ __device__ __forceinline__ void epilogue_preload(const FastArgs &a, int tile, in
     } else if (epi_is_qkv(EPI)) {
         const int Tq = a.n_heads * a.head_dim / 16, Tkv = a.n_kv_heads * a.head_dim / 16;
         const int which = tile < Tq ? 0 : (tile < Tq + Tkv ? 1 : 2), t = tile - (which == 0 ? 0 : (which == 1 ? Tq : Tq + Tkv));
-        const int pos = *a.len_ptr + m;
+        int pos = 0;
         pre.page = 0;
 #pragma unroll
         for (int i = 0; i < 4; ++i) pre.cs[i] = make_float2(1.f, 0.f);
         if (valid) {
-            pre.page = a.page_table[pos >> 4];
+            if (EPI == EPI_QKV_BATCH) {
+                const SeqRef sq = a.seqs[a.row_seq[m]];
+                pos = *sq.len_ptr + (m - sq.row0);
+                pre.page = sq.page_table[pos >> 4];
+            } else {
+                pos = *a.len_ptr + m;
+                pre.page = a.page_table[pos >> 4];
+            }
             if (which < 2) {
                 const int tph = a.head_dim / 16, half = a.head_dim / 2;
                 const int j = t % tph;
@@ -354,7 +361,7 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
         if (EPI == EPI_QKV_BATCH) {
             const SeqRef sq = a.seqs[a.row_seq[m]];
             pos = *sq.len_ptr + (m - sq.row0);
-            page = sq.page_table[pos >> 4];
+            page = pre ? pre->page : sq.page_table[pos >> 4];
             pool = sq.pool;
         } else {
             pos = *a.len_ptr + m;

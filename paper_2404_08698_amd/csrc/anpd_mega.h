@@ -63,6 +63,14 @@ struct MegaArgs {
     // rows a row sees (itself and its ancestors) as a bit mask
     int32_t parent[8], depth[8];
     uint32_t mask[8];
+    // several sequences in one step, by value as well: the sequences, the sequence of every row, and the
+    // first attention task of every sequence (tasks run sequence by sequence: n_heads * splits each)
+    SeqRef seqs[8];
+    int32_t row_seq[8];
+    int32_t task0[9];
+    int32_t n_seq;
+    int32_t n_att_blocks;    // (split, sequence) pairs per head
+    int32_t *host_batch;     // pinned host memory: (accepted, next) of every sequence
 };
 
 constexpr int kTraceEvents = 1024;
@@ -450,12 +458,15 @@ __device__ __forceinline__ FastArgs base_args(MegaArgsK g)
     return a;
 }
 
-// TREE: the window is a draft tree (see MegaArgs::parent): rotary positions by depth, attention over
-// ancestors only, acceptance along the paths.  A separate instantiation, so the chain form keeps its
-// registers.
-template <int DH, bool TREE = false>
+// MODE 1 (tree): the window is a draft tree (see MegaArgs::parent): rotary positions by depth, attention
+// over ancestors only, acceptance along the paths.  MODE 2 (batch): the window holds several sequences
+// side by side (MegaArgs::seqs): cache, length and position per row, attention per sequence, acceptance
+// inside every sequence.  Separate instantiations, so the chain form keeps its registers.
+enum { MEGA_CHAIN = 0, MEGA_TREE = 1, MEGA_BATCH = 2 };
+template <int DH, int MODE = MEGA_CHAIN>
 __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* read through phase_args() */)
 {
+    constexpr bool TREE = MODE == MEGA_TREE, BATCH = MODE == MEGA_BATCH;
     __shared__ MegaShared sh;
     __shared__ float bval[kFastWaves];
     __shared__ int bidx[kFastWaves];
@@ -469,7 +480,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
         bar_init(bar, g);
         bar_stamp(bar);
         if (threadIdx.x == 0) sh.tiles_done = 0;   // ordered by the first block barrier below
-        L = *g->len_ptr;
+        L = BATCH ? 0 : *g->len_ptr;
         n_layers = g->n_layers;
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
         const int d = g->d;
@@ -497,9 +508,83 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             a.n_tiles = (g->d + 2 * g->n_kv_heads * g->head_dim) / 16;
             a.ssp = g->ssp_a; a.layer = l; a.ready = g->qkv_ready;
             if (TREE) a.depth = (const int32_t *)g->depth;
+            if (BATCH) {
+                a.seqs = (const SeqRef *)g->seqs;
+                a.row_seq = (const int32_t *)g->row_seq;
+            }
             WSrc none = {w.o, nks_d, 0};   // the O tile is fetched from inside the attention phase
-            gemm_phase<TREE ? EPI_QKV_TREE : EPI_QKV, true, false>(a, none, pf, sh, bar, tiles_before);
+            gemm_phase<BATCH ? EPI_QKV_BATCH : (TREE ? EPI_QKV_TREE : EPI_QKV), true, false>(a, none, pf, sh, bar, tiles_before);
         }
+        if (BATCH) {   // attention, several sequences: tasks (sequence, head, split), sequence by sequence
+            MegaArgsK g = phase_args();
+            const LayerW w = layer_weights(g, l);
+            const int tid = fresh_tid();
+            const int lane = tid & 63, wave = tid >> 6;
+            const int M = g->M, n_heads = g->n_heads, n_seq = g->n_seq;
+            const int n_tasks = g->task0[n_seq];
+            const int grp = n_heads / g->n_kv_heads;
+            // task -> (sequence, head, split) and the sequence's cache
+            auto locate = [&](int t, int &s, int &head, int &split) {
+                s = 0;
+                while (s + 1 < n_seq && t >= g->task0[s + 1]) ++s;
+                const int local = t - g->task0[s];
+                head = local % n_heads;
+                split = local / n_heads;
+            };
+            AttnKV<DH> kv;
+            kv.loaded = false;
+            if ((int)blockIdx.x < n_tasks) {
+                int s, head, split;
+                locate(blockIdx.x, s, head, split);
+                attn_load_kv<DH, true>(kv, head / grp, split, *g->seqs[s].len_ptr, g->seqs[s].n_rows, g->seqs[s].pool,
+                                       g->seqs[s].page_table, l, n_layers, g->n_kv_heads, true);
+            }
+            if (tid == 0) {
+                const uint32_t target = (uint32_t)(3 * g->head_dim / 16) * (g->ready_epoch + (uint32_t)l + 1u);
+                // (every sequence has a multiple of n_heads tasks: with the grid a multiple of the head count
+                // all of a block's tasks wait for the same head)
+                const int t_end = grid % n_heads == 0 ? ((int)blockIdx.x < n_tasks ? (int)blockIdx.x + 1 : 0) : n_tasks;
+                for (int t = blockIdx.x; t < t_end; t += grid) {
+                    int s, head, split;
+                    locate(t, s, head, split);
+                    wait_count(bar, g->qkv_ready + kCounterStride * head, target);
+                }
+            }
+            block_sync_lds();
+            bar_stamp(bar);
+            const WSrc o_src = {w.o, (g->d + 31) / 32, g->d / 16};
+            bool fetched = false;
+            auto prefetch_o = [&]() {
+                if (!fetched) load_wchunk(pf, o_src, blockIdx.x, 0, wave, lane);
+                fetched = true;
+            };
+            const bool one_head = grid % n_heads == 0;
+            int unreported = 0;
+            for (int t = blockIdx.x; t < n_tasks; t += grid) {
+                int s, head, split;
+                locate(t, s, head, split);
+                unreported += 1;
+                const int publish = (!one_head || t + grid >= n_tasks) ? unreported : 0;
+                if (publish) unreported = 0;
+                const int tn = t + grid;
+                auto next_page = [&]() {
+                    if (tn < n_tasks) {
+                        int s2, head2, split2;
+                        locate(tn, s2, head2, split2);
+                        attn_load_kv<DH, true>(kv, head2 / grp, split2, *g->seqs[s2].len_ptr, g->seqs[s2].n_rows, g->seqs[s2].pool,
+                                               g->seqs[s2].page_table, l, n_layers, g->n_kv_heads, false);
+                    }
+                };
+                AttnBatch bt = {g->seqs[s].row0, g->seqs[s].n_rows, g->n_att_blocks, (const SeqRef *)g->seqs, (const int32_t *)g->row_seq};
+                attn_task<DH, true, decltype(prefetch_o), ATTN_BATCH, decltype(next_page)>(
+                    attn_shared<DH>(sh), kv, head, split, *g->seqs[s].len_ptr, (const uint4 *)g->qp, g->seqs[s].pool,
+                    g->seqs[s].page_table, M, l, n_layers, n_heads, g->n_kv_heads, g->max_splits, g->scale, g->part,
+                    g->head_counter, g->xp_att, 8, prefetch_o, nullptr, &bt, next_page, publish);
+                block_sync_lds();
+            }
+            prefetch_o();
+            bar_arrive(bar);
+        } else
         {   // attention: (head, split) tasks; the O weights stream in meanwhile.  Cache pages wholly
             // below the committed length do not depend on this step: the first task's page is
             // requested before the barrier.
@@ -633,7 +718,25 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             int acc_n = 0;
             int32_t next;
             int32_t *hr = g->host_result;
-            if (TREE) {
+            if (BATCH) {
+                // Algorithm 1's rule inside every sequence's own rows
+                for (int s = 0; s < g->n_seq; ++s) {
+                    const int r0 = g->seqs[s].row0, n = g->seqs[s].n_rows;
+                    int a = 0;
+                    if (g->mode == 0) {
+                        while (a < n - 1 && g->tok[r0 + a + 1] == ld_agent(pred + r0 + a)) ++a;
+                    } else {
+                        a = n - 1;
+                    }
+                    const int32_t nx = ld_agent(pred + r0 + a);
+                    g->result[67 + 2 * s] = a;
+                    g->result[68 + 2 * s] = nx;
+                    st_system(g->host_batch + 2 * s, (int32_t)a);
+                    st_system(g->host_batch + 2 * s + 1, nx);
+                    *g->seqs[s].len_ptr += 1 + a;
+                }
+                next = 0;
+            } else if (TREE) {
                 // row r > 0 is accepted iff its parent is and its token is the prediction made there; the
                 // deepest accepted row wins, the lowest index among equally deep ones
                 uint32_t ok = 1u;
@@ -664,7 +767,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             st_system(hr, (int32_t)acc_n);
             st_system(hr + 1, next);
             for (int i = 0; i < g->M; ++i) st_system(hr + 2 + i, ld_agent(pred + i));
-            *g->len_ptr = L + 1 + acc_n;
+            if (!BATCH) *g->len_ptr = L + 1 + acc_n;
             st_agent(g->row_counter, 0u);
         }
     }

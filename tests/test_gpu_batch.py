@@ -30,7 +30,7 @@ def test_each_sequence_gets_what_it_gets_alone(shape_name):
     shape = getattr(synth, shape_name)
     lengths = [37, 150, 290, 16]
     w, model, prompts, alone, joint = _setup(shape, lengths, 51)
-    for round_, rows in enumerate(([5, 1, 9, 3], [1, 1, 1, 1], [8, 8, 8, 8], [2, 17, 1, 4])):
+    for round_, rows in enumerate(([5, 1, 9, 3], [1, 1, 1, 1], [8, 8, 8, 8], [2, 17, 1, 4], [2, 1, 3, 2], [1, 4, 1, 1])):
         windows = [synth.random_tokens(shape.vocab, n, 200 + 10 * round_ + i) for i, n in enumerate(rows)]
         for kv_a, kv_j, n in zip(alone, joint, lengths):
             kv_a.truncate(n)
@@ -80,6 +80,47 @@ def test_thirty_two_sequences_decoding_one_token_each():
         joint.append([nxt for _, nxt in B.verify_batch(model, kvs_j, [[t] for t in joint[-1]])])
     assert alone == joint
     assert [kv.length for kv in kvs_a] == [kv.length for kv in kvs_j]
+
+
+def test_eight_rows_or_fewer_run_in_the_persistent_kernel_with_the_same_bits():
+    """Batches of at most 8 rows take the one-kernel form of the step; a model built for separate launches
+    takes the fused launches.  Same results, bit for bit, over several decoding steps with lengths that
+    cross a page and an attention split."""
+    shape = synth.MID_BF16
+    w = synth.make_weights(shape, 55, device="cuda")
+    one = B.Model(shape, w, max_window=8, max_positions=400)
+    many = B.Model(shape, w, max_window=8, max_positions=400, gemm_path=B.GEMM_MFMA_LAUNCHES)
+    lengths = [125, 15, 260, 1, 127, 64, 31, 200]
+    state = []
+    for model in (one, many):
+        kvs, cur = [], []
+        for i, n in enumerate(lengths):
+            kv = B.KVCache(model, 400)
+            cur.append(B.prefill(model, kv, synth.markov_stream(shape.vocab, n, 0.3, 4, 12, 500 + i)))
+            kvs.append(kv)
+        state.append((model, kvs, cur))
+    assert state[0][2] == state[1][2]
+    bufs = [torch.empty(8, shape.vocab, dtype=torch.float32, device="cuda") for _ in range(2)]
+    for step in range(5):
+        outs = []
+        for (model, kvs, cur), buf in zip(state, bufs):
+            res = B.verify_batch(model, kvs, [[t] for t in cur], out_logits=buf)
+            outs.append(res)
+            cur[:] = [nxt for _, nxt in res]
+        assert outs[0] == outs[1], step
+        assert torch.equal(bufs[0], bufs[1]), step
+    assert [kv.length for kv in state[0][1]] == [kv.length for kv in state[1][1]] == [n + 5 for n in lengths]
+    # ragged windows with drafts: 3 sequences, 8 rows in all, verification mode
+    for (model, kvs, cur), buf in zip(state, bufs):
+        wins = [[cur[0], 5, 6], [cur[1]], [cur[2], 7, 8, 9]]
+        res = B.verify_batch(model, kvs[:3], wins, out_logits=buf)
+        state[state.index((model, kvs, cur))] = (model, kvs, res)
+    assert state[0][2] == state[1][2] and torch.equal(bufs[0], bufs[1])
+    for layer in range(shape.n_layers):
+        for a, b, n in zip(state[0][1], state[1][1], lengths):
+            ka, va = a.read(layer, 0, a.length)
+            kb, vb = b.read(layer, 0, b.length)
+            assert a.length == b.length and torch.equal(ka, kb) and torch.equal(va, vb)
 
 
 def test_batch_argument_errors():
