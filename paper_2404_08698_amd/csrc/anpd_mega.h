@@ -515,91 +515,53 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             WSrc none = {w.o, nks_d, 0};   // the O tile is fetched from inside the attention phase
             gemm_phase<BATCH ? EPI_QKV_BATCH : (TREE ? EPI_QKV_TREE : EPI_QKV), true, false>(a, none, pf, sh, bar, tiles_before);
         }
-        if (BATCH) {   // attention, several sequences: tasks (sequence, head, split), sequence by sequence
-            MegaArgsK g = phase_args();
-            const LayerW w = layer_weights(g, l);
-            const int tid = fresh_tid();
-            const int lane = tid & 63, wave = tid >> 6;
-            const int M = g->M, n_heads = g->n_heads, n_seq = g->n_seq;
-            const int n_tasks = g->task0[n_seq];
-            const int grp = n_heads / g->n_kv_heads;
-            // task -> (sequence, head, split) and the sequence's cache
-            auto locate = [&](int t, int &s, int &head, int &split) {
-                s = 0;
-                while (s + 1 < n_seq && t >= g->task0[s + 1]) ++s;
-                const int local = t - g->task0[s];
-                head = local % n_heads;
-                split = local / n_heads;
-            };
-            AttnKV<DH> kv;
-            kv.loaded = false;
-            if ((int)blockIdx.x < n_tasks) {
-                int s, head, split;
-                locate(blockIdx.x, s, head, split);
-                attn_load_kv<DH, true>(kv, head / grp, split, *g->seqs[s].len_ptr, g->seqs[s].n_rows, g->seqs[s].pool,
-                                       g->seqs[s].page_table, l, n_layers, g->n_kv_heads, true);
-            }
-            if (tid == 0) {
-                const uint32_t target = (uint32_t)(3 * g->head_dim / 16) * (g->ready_epoch + (uint32_t)l + 1u);
-                // (every sequence has a multiple of n_heads tasks: with the grid a multiple of the head count
-                // all of a block's tasks wait for the same head)
-                const int t_end = grid % n_heads == 0 ? ((int)blockIdx.x < n_tasks ? (int)blockIdx.x + 1 : 0) : n_tasks;
-                for (int t = blockIdx.x; t < t_end; t += grid) {
-                    int s, head, split;
-                    locate(t, s, head, split);
-                    wait_count(bar, g->qkv_ready + kCounterStride * head, target);
-                }
-            }
-            block_sync_lds();
-            bar_stamp(bar);
-            const WSrc o_src = {w.o, (g->d + 31) / 32, g->d / 16};
-            bool fetched = false;
-            auto prefetch_o = [&]() {
-                if (!fetched) load_wchunk(pf, o_src, blockIdx.x, 0, wave, lane);
-                fetched = true;
-            };
-            const bool one_head = grid % n_heads == 0;
-            int unreported = 0;
-            for (int t = blockIdx.x; t < n_tasks; t += grid) {
-                int s, head, split;
-                locate(t, s, head, split);
-                unreported += 1;
-                const int publish = (!one_head || t + grid >= n_tasks) ? unreported : 0;
-                if (publish) unreported = 0;
-                const int tn = t + grid;
-                auto next_page = [&]() {
-                    if (tn < n_tasks) {
-                        int s2, head2, split2;
-                        locate(tn, s2, head2, split2);
-                        attn_load_kv<DH, true>(kv, head2 / grp, split2, *g->seqs[s2].len_ptr, g->seqs[s2].n_rows, g->seqs[s2].pool,
-                                               g->seqs[s2].page_table, l, n_layers, g->n_kv_heads, false);
-                    }
-                };
-                AttnBatch bt = {g->seqs[s].row0, g->seqs[s].n_rows, g->n_att_blocks, (const SeqRef *)g->seqs, (const int32_t *)g->row_seq};
-                attn_task<DH, true, decltype(prefetch_o), ATTN_BATCH, decltype(next_page)>(
-                    attn_shared<DH>(sh), kv, head, split, *g->seqs[s].len_ptr, (const uint4 *)g->qp, g->seqs[s].pool,
-                    g->seqs[s].page_table, M, l, n_layers, n_heads, g->n_kv_heads, g->max_splits, g->scale, g->part,
-                    g->head_counter, g->xp_att, 8, prefetch_o, nullptr, &bt, next_page, publish);
-                block_sync_lds();
-            }
-            prefetch_o();
-            bar_arrive(bar);
-        } else
-        {   // attention: (head, split) tasks; the O weights stream in meanwhile.  Cache pages wholly
-            // below the committed length do not depend on this step: the first task's page is
-            // requested before the barrier.
+        {   // attention: (head, split) tasks - per sequence when the step holds several; the O weights stream
+            // in meanwhile.  Cache pages wholly below the committed length do not depend on this step: the
+            // first task's page is requested before the barrier.
             MegaArgsK g = phase_args();
             const LayerW w = layer_weights(g, l);
             const int tid = fresh_tid();
             const int lane = tid & 63, wave = tid >> 6;
             const int M = g->M, n_heads = g->n_heads;
-            const int n_splits = (L + M + kFastSplit - 1) / kFastSplit;
-            const int n_tasks = n_heads * n_splits;
+            const int grp = n_heads / g->n_kv_heads;
+            const int n_tasks = BATCH ? g->task0[g->n_seq] : n_heads * ((L + M + kFastSplit - 1) / kFastSplit);
+            // task -> (head, split) and the cache it works on.  Several sequences: tasks run sequence by
+            // sequence, every sequence has a multiple of n_heads of them
+            struct Task {
+                int head, split, L, rows, row0;
+                const bf16_t *pool;
+                const int32_t *table;
+            };
+            auto locate = [&](int t) {
+                Task k;
+                if (BATCH) {
+                    int s = 0;
+                    while (s + 1 < g->n_seq && t >= g->task0[s + 1]) ++s;
+                    const int local = t - g->task0[s];
+                    k.head = local % n_heads;
+                    k.split = local / n_heads;
+                    k.L = *g->seqs[s].len_ptr;
+                    k.rows = g->seqs[s].n_rows;
+                    k.row0 = g->seqs[s].row0;
+                    k.pool = g->seqs[s].pool;
+                    k.table = g->seqs[s].page_table;
+                } else {
+                    k.head = t % n_heads;
+                    k.split = t / n_heads;
+                    k.L = L;
+                    k.rows = M;
+                    k.row0 = 0;
+                    k.pool = g->pool;
+                    k.table = g->page_table;
+                }
+                return k;
+            };
             AttnKV<DH> kv;
             kv.loaded = false;
-            if ((int)blockIdx.x < n_tasks)
-                attn_load_kv<DH, true>(kv, ((int)blockIdx.x % n_heads) / (n_heads / g->n_kv_heads), blockIdx.x / n_heads, L, M, g->pool,
-                                       g->page_table, l, n_layers, g->n_kv_heads, true);
+            if ((int)blockIdx.x < n_tasks) {
+                const Task k = locate(blockIdx.x);
+                attn_load_kv<DH, true>(kv, k.head / grp, k.split, k.L, k.rows, k.pool, k.table, l, n_layers, g->n_kv_heads, true);
+            }
             // No grid barrier here: a task needs the q / k / v tiles of its own head only, and every
             // block still arrives at the barrier that ends this phase after its QKV tiles, which is
             // what the O phase waits for.
@@ -622,7 +584,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             const bool one_head = grid % n_heads == 0;
             int unreported = 0;
             for (int t = blockIdx.x; t < n_tasks; t += grid) {
-                const int head = t % n_heads, split = t / n_heads;
+                const Task k = locate(t);
                 unreported += 1;
                 const int publish = (!one_head || t + grid >= n_tasks) ? unreported : 0;
                 if (publish) unreported = 0;
@@ -630,14 +592,17 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
                 // task has used its own: every wait for the block's counters is over by now
                 const int tn = t + grid;
                 auto next_page = [&]() {
-                    if (tn < n_tasks)
-                        attn_load_kv<DH, true>(kv, (tn % n_heads) / (n_heads / g->n_kv_heads), tn / n_heads, L, M, g->pool, g->page_table,
-                                               l, n_layers, g->n_kv_heads, false);
+                    if (tn < n_tasks) {
+                        const Task k2 = locate(tn);
+                        attn_load_kv<DH, true>(kv, k2.head / grp, k2.split, k2.L, k2.rows, k2.pool, k2.table, l, n_layers, g->n_kv_heads,
+                                               false);
+                    }
                 };
-                attn_task<DH, true, decltype(prefetch_o), TREE ? ATTN_TREE : ATTN_CHAIN, decltype(next_page)>(
-                    attn_shared<DH>(sh), kv, head, split, L, (const uint4 *)g->qp, g->pool, g->page_table, M, l, n_layers, n_heads,
+                AttnBatch bt = {k.row0, k.rows, g->n_att_blocks, (const SeqRef *)g->seqs, (const int32_t *)g->row_seq};
+                attn_task<DH, true, decltype(prefetch_o), BATCH ? ATTN_BATCH : (TREE ? ATTN_TREE : ATTN_CHAIN), decltype(next_page)>(
+                    attn_shared<DH>(sh), kv, k.head, k.split, k.L, (const uint4 *)g->qp, k.pool, k.table, M, l, n_layers, n_heads,
                     g->n_kv_heads, g->max_splits, g->scale, g->part, g->head_counter, g->xp_att, 8, prefetch_o,
-                    (const uint32_t *)g->mask, nullptr, next_page, publish);
+                    TREE ? (const uint32_t *)g->mask : nullptr, BATCH ? &bt : nullptr, next_page, publish);
                 block_sync_lds();
             }
             prefetch_o();
