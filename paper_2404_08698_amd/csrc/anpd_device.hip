@@ -699,18 +699,30 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, 
 
 // ---- prompt processing on the matrix cores ------------------------------------
 
-template <int EPI>
-int32_t launch_prefill_gemm(const PrefillArgs &a, hipStream_t st)
+template <int EPI, int TN>
+int32_t launch_prefill_gemm_tn(const PrefillArgs &a, int n_bt, int n_br, hipStream_t st)
 {
-    const int n_bt = (a.n_tiles + 15) / 16, n_br = (a.G + 7) / 8;
-    static bool attr_set = false;   // per epilogue
+    static bool attr_set = false;   // per instantiation
     if (!attr_set) {
-        HIP_TRY(hipFuncSetAttribute((const void *)prefill_gemm_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPgLdsBytes));
+        HIP_TRY(hipFuncSetAttribute((const void *)prefill_gemm_kernel<EPI, TN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPgLdsBytes));
         attr_set = true;
     }
-    hipLaunchKernelGGL((prefill_gemm_kernel<EPI>), dim3((unsigned)(n_bt * a.S * n_br)), dim3(kPgThreads), kPgLdsBytes, st, a);
+    hipLaunchKernelGGL((prefill_gemm_kernel<EPI, TN>), dim3((unsigned)(n_bt * a.S * n_br)), dim3(kPgThreads), kPgLdsBytes, st, a);
     HIP_TRY(hipGetLastError());
     return ANPD_OK;
+}
+
+// Blocks of 256 or of 192 output features, whichever takes fewer rounds of the chip's compute units, a
+// round of the smaller block counted as kPfSmallBlock of the larger one's (measured at the 7B shape: 0.85 - 0.89).
+constexpr double kPfSmallBlock = 0.87;
+template <int EPI>
+int32_t launch_prefill_gemm(const PrefillArgs &a, int n_cu, hipStream_t st)
+{
+    const int n_br = (a.G + 7) / 8;
+    const int bt4 = (a.n_tiles + 15) / 16, bt3 = (a.n_tiles + 11) / 12;
+    const int rounds4 = (bt4 * a.S * n_br + n_cu - 1) / n_cu, rounds3 = (bt3 * a.S * n_br + n_cu - 1) / n_cu;
+    const bool small = kPfSmallBlock * rounds3 < (double)rounds4;
+    return small ? launch_prefill_gemm_tn<EPI, 3>(a, bt3, n_br, st) : launch_prefill_gemm_tn<EPI, 4>(a, bt4, n_br, st);
 }
 
 // All P rows at once; per layer norm -> QKV(+RoPE, cache write) -> attention -> O(+residual) -> norm ->
@@ -763,7 +775,7 @@ int32_t run_prefill_mfma(anpd_model *m, anpd_kv *kv, int P, char *pws, const Pre
             a.nks = nks_d;
             a.n_tiles = (d + 2 * kv_dim_of(c)) / 16;
             a.layer = l;
-            if ((rc = launch_prefill_gemm<EPI_QKV>(a, st)) != ANPD_OK) return rc;
+            if ((rc = launch_prefill_gemm<EPI_QKV>(a, m->n_cu, st)) != ANPD_OK) return rc;
         }
         mark(m, ANPD_PROF_GEMM_QKV, st);
         if (dh == 128)
@@ -780,7 +792,7 @@ int32_t run_prefill_mfma(anpd_model *m, anpd_kv *kv, int P, char *pws, const Pre
             a.nks = nks_d;
             a.n_tiles = d / 16;
             a.S = kPgSplit;
-            if ((rc = launch_prefill_gemm<EPI_RESIDUAL>(a, st)) != ANPD_OK) return rc;
+            if ((rc = launch_prefill_gemm<EPI_RESIDUAL>(a, m->n_cu, st)) != ANPD_OK) return rc;
         }
         mark(m, ANPD_PROF_GEMM_O, st);
         hipLaunchKernelGGL((prefill_norm_kernel<false>), dim3((unsigned)(G * 16)), dim3(256), 0, st, (const bf16_t *)nullptr, tok, x,
@@ -794,7 +806,7 @@ int32_t run_prefill_mfma(anpd_model *m, anpd_kv *kv, int P, char *pws, const Pre
             a.n_tiles = F / 8;
             a.out = xq_f;
             a.out_nks = nks_f;
-            if ((rc = launch_prefill_gemm<EPI_GATE_UP>(a, st)) != ANPD_OK) return rc;
+            if ((rc = launch_prefill_gemm<EPI_GATE_UP>(a, m->n_cu, st)) != ANPD_OK) return rc;
         }
         mark(m, ANPD_PROF_GEMM_GATE_UP, st);
         {
@@ -804,7 +816,7 @@ int32_t run_prefill_mfma(anpd_model *m, anpd_kv *kv, int P, char *pws, const Pre
             a.nks = nks_f;
             a.n_tiles = d / 16;
             a.S = kPgSplit;
-            if ((rc = launch_prefill_gemm<EPI_RESIDUAL>(a, st)) != ANPD_OK) return rc;
+            if ((rc = launch_prefill_gemm<EPI_RESIDUAL>(a, m->n_cu, st)) != ANPD_OK) return rc;
         }
         mark(m, ANPD_PROF_GEMM_DOWN, st);
         if (l + 1 < c.n_layers) {

@@ -253,9 +253,13 @@ __device__ __forceinline__ u32x4_t lds_read16(uint32_t addr)
     return v;
 }
 
-template <int EPI>
+// TN: weight fragments per wave (4: the 256-feature tile above; 3: 192 features).  The launcher picks the
+// one whose grid fills the chip's compute units better (QKV of 512 rows: 192 blocks of 256 features, or 256
+// blocks of 192); an output element's sums do not depend on it.
+template <int EPI, int TN = kPfTN>
 __global__ __launch_bounds__(kPgThreads) void prefill_gemm_kernel(PrefillArgs a)
 {
+    static_assert(TN == 3 || TN == 4, "a wave holds 3 or 4 weight fragments");
     extern __shared__ uint4 ring[];   // [kPgStages][kPgUnits][64]
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wf = wave & 3, wr = wave >> 2;
@@ -272,19 +276,21 @@ __global__ __launch_bounds__(kPgThreads) void prefill_gemm_kernel(PrefillArgs a)
     const int br = id % n_br;
     id /= n_br;
     const int sp = id % a.S, bt = id / a.S;
-    const int F0 = bt * 16, G0 = br * 8;
+    const int F0 = bt * 4 * TN, G0 = br * 8;
     const int nks = a.nks;
     const int ks0 = (int)((long long)sp * nks / a.S), n_it = (int)((long long)(sp + 1) * nks / a.S) - ks0;
 
-    // this wave's share of a stage: units 4 wave .. 4 wave + 3 (waves 0..3 weights, 4..7 activations)
+    // this wave's share of a stage: units 4 wave .. 4 wave + 3 (waves 0..3 weights, 4..7 activations); with
+    // TN = 3 a weight wave's fourth unit is an empty descriptor (zeros, nothing fetched): every wave still
+    // issues four loads per stage, which is what the waits below count
     __amdgpu_buffer_rsrc_t rs[4];
     int uoff[4];
     const int ustride = wave < 4 ? 1024 : 2048;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         if (wave < 4) {
-            const int tile = F0 + 4 * wave + j;
-            const bool have = tile < a.n_tiles;
+            const int tile = F0 + TN * wave + j;
+            const bool have = j < TN && tile < a.n_tiles;
             rs[j] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(a.Wp + (size_t)(have ? tile : 0) * nks * 64), 0,
                                                       have ? nks * 1024 : 0, 0x00020000);
             uoff[j] = 0;
@@ -304,9 +310,9 @@ __global__ __launch_bounds__(kPgThreads) void prefill_gemm_kernel(PrefillArgs a)
                                                      uoff[j] + (ks0 + it) * ustride + lane * 16, 0, 0, 0);
     };
 
-    f32x4 acc[kPfTN][kPfTM];
+    f32x4 acc[TN][kPfTM];
 #pragma unroll
-    for (int t = 0; t < kPfTN; ++t)
+    for (int t = 0; t < TN; ++t)
 #pragma unroll
         for (int g = 0; g < kPfTM; ++g) acc[t][g] = (f32x4){0.f, 0.f, 0.f, 0.f};
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)ring;
@@ -314,27 +320,29 @@ __global__ __launch_bounds__(kPgThreads) void prefill_gemm_kernel(PrefillArgs a)
     // The fragment reads are written as assembly: reads the compiler can see would make it wait for
     // every outstanding load into LDS first (it cannot tell the ring's stages apart), and the ring
     // exists to keep three stages in flight.
-    auto read_stage = [&](u32x4_t (&w)[kPfTN], u32x4_t (&xh)[kPfTM], u32x4_t (&xl)[kPfTM], int it) {
+    auto read_stage = [&](u32x4_t (&w)[4], u32x4_t (&xh)[kPfTM], u32x4_t (&xl)[kPfTM], int it) {
         const uint32_t sbase = lds_base + (uint32_t)(it & (kPgStages - 1)) * (kPgUnits * 1024) + (uint32_t)lane * 16;
         const uint32_t aw = sbase + (uint32_t)(4 * wf) * 1024, ax = sbase + (uint32_t)(16 + 8 * wr) * 1024;
-        w[0] = lds_read16<0>(aw); w[1] = lds_read16<1024>(aw); w[2] = lds_read16<2048>(aw); w[3] = lds_read16<3072>(aw);
+        w[0] = lds_read16<0>(aw); w[1] = lds_read16<1024>(aw); w[2] = lds_read16<2048>(aw);
+        if (TN == 4) w[3] = lds_read16<3072>(aw);
+        else w[3] = w[2];
         xh[0] = lds_read16<0>(ax); xh[1] = lds_read16<2048>(ax); xh[2] = lds_read16<4096>(ax); xh[3] = lds_read16<6144>(ax);
         xl[0] = lds_read16<1024>(ax); xl[1] = lds_read16<3072>(ax); xl[2] = lds_read16<5120>(ax); xl[3] = lds_read16<7168>(ax);
     };
-    auto wait_reads = [&](u32x4_t (&w)[kPfTN], u32x4_t (&xh)[kPfTM], u32x4_t (&xl)[kPfTM]) {
+    auto wait_reads = [&](u32x4_t (&w)[4], u32x4_t (&xh)[kPfTM], u32x4_t (&xl)[kPfTM]) {
         asm volatile("s_waitcnt lgkmcnt(0)"
                      : "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]), "+v"(xh[0]), "+v"(xh[1]), "+v"(xh[2]), "+v"(xh[3]),
                        "+v"(xl[0]), "+v"(xl[1]), "+v"(xl[2]), "+v"(xl[3]));
     };
-    auto mma = [&](const u32x4_t (&w)[kPfTN], const u32x4_t (&xh)[kPfTM], const u32x4_t (&xl)[kPfTM]) {
+    auto mma = [&](const u32x4_t (&w)[4], const u32x4_t (&xh)[kPfTM], const u32x4_t (&xl)[kPfTM]) {
 #pragma unroll
-        for (int t = 0; t < kPfTN; ++t)
+        for (int t = 0; t < TN; ++t)
 #pragma unroll
             for (int g = 0; g < kPfTM; ++g)
                 acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[t]), __builtin_bit_cast(bf16x8, xh[g]),
                                                                     acc[t][g], 0, 0, 0);
 #pragma unroll
-        for (int t = 0; t < kPfTN; ++t)
+        for (int t = 0; t < TN; ++t)
 #pragma unroll
             for (int g = 0; g < kPfTM; ++g)
                 acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[t]), __builtin_bit_cast(bf16x8, xl[g]),
@@ -344,7 +352,7 @@ __global__ __launch_bounds__(kPgThreads) void prefill_gemm_kernel(PrefillArgs a)
     // stages 2j and 2j + 1 have landed (at most the two younger stages still outstanding) and its reads of
     // the previous round's stages have returned; it publishes this round's stages and frees the previous
     // round's slots for stages 2j + 2 and 2j + 3.  All four slots are requested before the first round.
-    u32x4_t wA[kPfTN], hA[kPfTM], lA[kPfTM], wB[kPfTN], hB[kPfTM], lB[kPfTM];
+    u32x4_t wA[4], hA[kPfTM], lA[kPfTM], wB[4], hB[kPfTM], lB[kPfTM];
 #pragma unroll
     for (int s = 0; s < kPgStages; ++s)
         if (s < n_it) request(s);
@@ -371,9 +379,9 @@ __global__ __launch_bounds__(kPgThreads) void prefill_gemm_kernel(PrefillArgs a)
 
     const int slot = lane & 15, kg = lane >> 4;
     const int r0 = a.L & 15;
-    const int f0 = F0 + 4 * wf, g0 = G0 + 4 * wr;
+    const int f0 = F0 + TN * wf, g0 = G0 + 4 * wr;
 #pragma unroll
-    for (int t = 0; t < kPfTN; ++t) {
+    for (int t = 0; t < TN; ++t) {
         if (f0 + t >= a.n_tiles) break;   // wave-uniform
 #pragma unroll
         for (int g = 0; g < kPfTM; ++g) {
