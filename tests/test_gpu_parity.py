@@ -208,6 +208,36 @@ def test_same_step_twice_is_bit_identical(dt, path):
     assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("dt", ["f32", "mid"])
+def test_a_callers_stream_gives_the_same_bits(dt):
+    """Every entry point takes the caller's stream: prompt, steps of every window class, a draft tree and a
+    batch on a stream of the caller's own (default priority) against the same calls on the default stream."""
+    shape = _shape(dt)
+    w = to_cuda(synth.make_weights(shape, 3))
+    toks = synth.markov_stream(shape.vocab, 140, 0.3, 4, 12, 11)
+    side = torch.cuda.Stream()
+    runs = []
+    for stream in (None, side):
+        model = B.Model(shape, w, max_window=32, max_positions=256, stream=stream)
+        kv, kv2 = B.KVCache(model, 256), B.KVCache(model, 256)
+        out = [B.prefill(model, kv, toks[:90], stream=stream), B.prefill(model, kv2, toks[:41], stream=stream)]
+        for M in (1, 6, 8, 13, 29):
+            buf = torch.empty(M, shape.vocab, dtype=torch.float32, device="cuda")
+            out.append(B.verify(model, kv, toks[90:90 + M], B.VERIFY, want_predicts=True, out_logits=buf, stream=stream))
+            torch.cuda.synchronize()
+            out.append(buf.cpu())
+        out.append(B.verify_tree(model, kv, toks[100:107], [-1, 0, 1, 0, 3, 0, 5], stream=stream))
+        if shape.dtype == "bf16":
+            out.append(B.verify_batch(model, [kv, kv2], [toks[110:113], toks[120:122]], stream=stream))
+        out.append((kv.length, kv2.length))
+        k, v = kv.read(shape.n_layers - 1, 0, kv.length, stream=stream)
+        torch.cuda.synchronize()
+        out += [k.cpu(), v.cpu()]
+        runs.append(out)
+    for a, b in zip(*runs):
+        assert torch.equal(a, b) if isinstance(a, torch.Tensor) else a == b
+
+
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 def test_rollback_leaves_the_cache_of_plain_decoding(dt):
     shape = _shape(dt)
