@@ -468,7 +468,7 @@ __global__ __launch_bounds__(kFastThreads) void gemm_xs_kernel(FastArgs a)
 #pragma unroll
         for (int u = 0; u < C; ++u) {
             int ks = wave + u * kFastWaves;
-            w0[u] = ks < nks ? W[(size_t)ks * 64] : make_uint4(0, 0, 0, 0);
+            w0[u] = ks < nks ? ld_stream(W + (size_t)ks * 64) : make_uint4(0, 0, 0, 0);
         }
     }
     uint4 x[KPW];
@@ -485,7 +485,7 @@ __global__ __launch_bounds__(kFastThreads) void gemm_xs_kernel(FastArgs a)
 #pragma unroll
             for (int u = C; u < KPW; ++u) {
                 int ks = wave + u * kFastWaves;
-                w1[u - C] = ks < nks ? W[(size_t)ks * 64] : make_uint4(0, 0, 0, 0);
+                w1[u - C] = ks < nks ? ld_stream(W + (size_t)ks * 64) : make_uint4(0, 0, 0, 0);
             }
         }
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -499,7 +499,7 @@ __global__ __launch_bounds__(kFastThreads) void gemm_xs_kernel(FastArgs a)
 #pragma unroll
             for (int u = 0; u < C; ++u) {
                 int ks = wave + u * kFastWaves;
-                w0[u] = ks < nks ? Wn[(size_t)ks * 64] : make_uint4(0, 0, 0, 0);
+                w0[u] = ks < nks ? ld_stream(Wn + (size_t)ks * 64) : make_uint4(0, 0, 0, 0);
             }
         }
         if (KPW > C) {
@@ -540,7 +540,7 @@ __global__ __launch_bounds__(kFastThreads) void gemm_stream_kernel(FastArgs a)
         for (int c = 0; c < C; ++c) {
             int ks = wave + (u0 + c) * kFastWaves;
             bool ok = ks < nks;
-            wv[c] = ok ? W[(size_t)ks * 64] : make_uint4(0, 0, 0, 0);
+            wv[c] = ok ? ld_stream(W + (size_t)ks * 64) : make_uint4(0, 0, 0, 0);
 #pragma unroll
             for (int t = 0; t < NT; ++t) xv[c][t] = ok ? X[((size_t)ks * NT + t) * 64] : make_uint4(0, 0, 0, 0);
         }
@@ -608,7 +608,7 @@ __global__ __launch_bounds__(kFastThreads) void gemm_group_kernel(FastArgs a)
                 const int ks = wave + kFastWaves * (i * C + c);   // past the end: outside every buffer, reads zeros
 #pragma unroll
                 for (int t = 0; t < TG; ++t) {
-                    u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rw[t], (ks * 64 + lane) * 16, 0, 0);
+                    u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rw[t], (ks * 64 + lane) * 16, 0, kAuxStream);
                     w[t][c] = make_uint4(v.x, v.y, v.z, v.w);
                 }
 #pragma unroll

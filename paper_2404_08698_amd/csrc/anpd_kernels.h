@@ -126,6 +126,16 @@ __device__ __forceinline__ void stc2(bf16_t *p, bf16_t v)
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 constexpr int kAuxCoherent = 17;  // sc0 | sc1
+// Weights are read once per step and never again before 13 GB of other weights have gone by: loads
+// marked non-temporal stream them past the caches instead of displacing what is re-read (activations,
+// the cache pages).  Measured on the weight access pattern alone: 7.1 TB/s against 6.4 TB/s unmarked.
+constexpr int kAuxStream = 2;     // nt
+__device__ __forceinline__ uint4 ld_stream(const uint4 *p)
+{
+    typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+    u4 v = __builtin_nontemporal_load(reinterpret_cast<const u4 *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t wave_buffer(const void *base)
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0x7fffffff, 0x00020000);

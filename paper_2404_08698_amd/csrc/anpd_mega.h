@@ -191,7 +191,7 @@ __device__ __forceinline__ void load_wchunk(uint4 (&w)[kChunk], const WSrc &s, i
     const int voff = (wave * 64 + lane) * 16;
 #pragma unroll
     for (int u = 0; u < kChunk; ++u) {
-        u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, (kChunk * c + u) * kFastWaves * 1024, 0);
+        u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, (kChunk * c + u) * kFastWaves * 1024, kAuxStream);
         w[u] = make_uint4(v.x, v.y, v.z, v.w);
     }
 }
