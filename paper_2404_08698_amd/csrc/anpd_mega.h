@@ -196,9 +196,9 @@ __device__ __forceinline__ void load_wchunk(uint4 (&w)[kChunk], const WSrc &s, i
     }
 }
 
-__device__ __forceinline__ void load_xchunk(uint4 (&x)[kChunk], const uint4 *Xp, int nks, int c, int wave, int lane)
+__device__ __forceinline__ void load_xchunk(uint4 (&x)[kChunk], const uint4 *Xp, int nks, int c, int wave, int lane, bool have = true)
 {
-    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(Xp), 0, nks * 1024, 0x00020000);
+    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(Xp), 0, have ? nks * 1024 : 0, 0x00020000);
     const int voff = (wave * 64 + lane) * 16;
 #pragma unroll
     for (int u = 0; u < kChunk; ++u) {
@@ -291,21 +291,27 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     bool next_issued = false;         // the next phase's first chunk has been requested
     // may_cross: the request may go to the next phase's first chunk when this phase has nothing left
     // (only on entry: later it would sit in front of the last epilogue's stores)
+    // Every call issues kChunk loads, also past the block's last item (an empty descriptor: zeros, nothing
+    // is fetched): the compiler counts the loads issued after the ones it waits for, and a request that
+    // may or may not have been made counts as not made, which turns every wait into a wait for all loads.
     auto fetch = [&](uint4 (&dst)[kChunk], bool may_cross) {
         if (++lc == n_chunks) { lc = 0; lt += grid; }
-        if (lt < cur.n_tiles) {
-            load_wchunk(dst, cur, lt, lc, wave, lane);
-        } else if (may_cross && !next_issued && !reducer) {
+        if (may_cross && !(lt < cur.n_tiles) && !next_issued && !reducer) {
             load_wchunk(dst, next, blockIdx.x, 0, wave, lane);
             next_issued = true;
+        } else {
+            load_wchunk(dst, cur, lt, lc, wave, lane);
         }
     };
     constexpr bool kHasPre = (EPI == EPI_RESIDUAL || epi_is_qkv(EPI));
     const bool stages = kHasPre && wave < kPreTiles && wave < my_tiles;   // this wave finishes tile number `wave`
     EpiPre pre0;
     if (stages) epilogue_preload<EPI>(a, blockIdx.x + wave * grid, lane, pre0);
-    fetch(wb, true);
+    fetch(wb, false);
     fetch(wc, true);
+    // at most two items: wc holds the next phase's first item (the same for a whole wave: told to the
+    // compiler, or it takes everything a step does under this flag for lane-dependent)
+    const bool cross_wc = __builtin_amdgcn_readfirstlane((int)next_issued) != 0;
     if (stages) pre_to_lds<EPI>(sh.pre[wave], pre0, lane);
 
     bar_wait(bar);
@@ -326,58 +332,92 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     else if (kNorm) compute_rinv<true>(a, sh.rinv, &sh.red[1][0][0]);
 
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    int it = 0, par = 0;
+    int it = 0;
     int step = 0;
-    while (tile < cur.n_tiles) {
-        if (STATIONARY ? c == 1 : par == 1) {
+    // pf, wb and wc form a ring: a step multiplies the oldest buffer and requests the item three steps
+    // ahead into the same registers, so three items stay in flight per wave.  (Passing the items down a
+    // chain pf <- wb <- wc by value makes every step wait for the load it has just issued.)
+    // xs: the operand buffer of this step when the operand is streamed (x0 and x1 in turn).
+    // active: the block still has an item for this step.  The loop has one exit, at its top, and every
+    // step issues the same number of loads whether it is active or not (empty descriptors once the items
+    // have run out): with several exits, or requests made on some paths only, the compiler must assume
+    // that the buffer a step waits for was requested last, and makes every step wait for all loads.
+    // keep: buf holds the next phase's first item and is not refilled.
+    auto do_step = [&](uint4 (&buf)[kChunk], uint4 (&xs)[kChunk], bool active, bool keep) __attribute__((always_inline)) {
+        if (active) {
+            if (STATIONARY) {
+                if (c == 1) {
 #pragma unroll
-            for (int u = 0; u < kChunk; ++u)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pf[u]),
-                                                              __builtin_bit_cast(bf16x8, x1[u]), acc, 0, 0, 0);
-        } else {
-#pragma unroll
-            for (int u = 0; u < kChunk; ++u)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pf[u]),
-                                                              __builtin_bit_cast(bf16x8, x0[u]), acc, 0, 0, 0);
-        }
-        if (!STATIONARY && step + 2 < n_steps) {
-            if (par == 1) load_xchunk(x1, a.Xp, a.nks, (step + 2) % n_chunks, wave, lane);
-            else load_xchunk(x0, a.Xp, a.nks, (step + 2) % n_chunks, wave, lane);
-        }
-        ++step;
-        par ^= 1;
-#pragma unroll
-        for (int u = 0; u < kChunk; ++u) { pf[u] = wb[u]; wb[u] = wc[u]; }
-        fetch(wc, false);
-        const bool tile_done = (c == n_chunks - 1);
-        const int finished = tile;
-        if (++c == n_chunks) { c = 0; tile += grid; }
-        if (tile_done) {
-            float *r = &sh.red[it & 1][0][0];
-            *reinterpret_cast<f32x4 *>(r + ((size_t)wave * 64 + lane) * 4) = acc;
-            if (late_norm && it == 0) rinv_partial_to_lds(nv, sh.rscratch, tid);
-            block_sync_lds();
-            if (late_norm && it == 0) rinv_from_lds(a, sh.rinv, sh.rscratch, tid);   // wave 0, which also finishes tile 0
-            if (wave == (it & (kFastWaves - 1))) {
-                if (kHasPre && it < kPreTiles) {
-                    EpiPre pre;
-                    pre_from_lds<EPI>(pre, sh.pre[it], lane);
-                    reduce_and_finish<1, EPI, true>(a, finished, r, kFastWaves, lane, sh.rinv, &pre);
+                    for (int u = 0; u < kChunk; ++u)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, buf[u]),
+                                                                      __builtin_bit_cast(bf16x8, x1[u]), acc, 0, 0, 0);
                 } else {
-                    reduce_and_finish<1, EPI, true>(a, finished, r, kFastWaves, lane, sh.rinv);
+#pragma unroll
+                    for (int u = 0; u < kChunk; ++u)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, buf[u]),
+                                                                      __builtin_bit_cast(bf16x8, x0[u]), acc, 0, 0, 0);
                 }
+            } else {
+#pragma unroll
+                for (int u = 0; u < kChunk; ++u)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, buf[u]),
+                                                                  __builtin_bit_cast(bf16x8, xs[u]), acc, 0, 0, 0);
             }
-            acc = (f32x4){0.f, 0.f, 0.f, 0.f};
-            ++it;
         }
+        if (!STATIONARY) load_xchunk(xs, a.Xp, a.nks, (step + 2) % n_chunks, wave, lane, active && step + 2 < n_steps);
+        if (!keep) fetch(buf, false);
+        if (active) {
+            ++step;
+            const bool tile_done = (c == n_chunks - 1);
+            const int finished = tile;
+            if (++c == n_chunks) { c = 0; tile += grid; }
+            if (tile_done) {
+                float *r = &sh.red[it & 1][0][0];
+                *reinterpret_cast<f32x4 *>(r + ((size_t)wave * 64 + lane) * 4) = acc;
+                if (late_norm && it == 0) rinv_partial_to_lds(nv, sh.rscratch, tid);
+                block_sync_lds();
+                if (late_norm && it == 0) rinv_from_lds(a, sh.rinv, sh.rscratch, tid);   // wave 0, which also finishes tile 0
+                if (wave == (it & (kFastWaves - 1))) {
+                    if (kHasPre && it < kPreTiles) {
+                        EpiPre pre;
+                        pre_from_lds<EPI>(pre, sh.pre[it], lane);
+                        reduce_and_finish<1, EPI, true>(a, finished, r, kFastWaves, lane, sh.rinv, &pre);
+                    } else {
+                        reduce_and_finish<1, EPI, true>(a, finished, r, kFastWaves, lane, sh.rinv);
+                    }
+                }
+                acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+                ++it;
+            }
+        }
+    };
+    // The loop is entered with the operand in registers (it is the youngest request, so the three weight
+    // items have arrived as well): inside the loop the compiler then sees that the buffer a step needs has
+    // two younger requests behind it and lets those stay in flight.
+#pragma unroll
+    for (int u = 0; u < kChunk; ++u) {
+        u32x4_t t0 = __builtin_bit_cast(u32x4_t, x0[u]), t1 = __builtin_bit_cast(u32x4_t, x1[u]);
+        asm volatile("" : "+v"(t0), "+v"(t1));
+        x0[u] = __builtin_bit_cast(uint4, t0);
+        x1[u] = __builtin_bit_cast(uint4, t1);
+    }
+    while (tile < cur.n_tiles) {
+        do_step(pf, x0, true, false);
+        do_step(wb, x1, tile < cur.n_tiles, false);
+        do_step(wc, x0, tile < cur.n_tiles, cross_wc);
+        if (!STATIONARY) {   // three weight buffers, two operand buffers: the pattern repeats after six steps
+            do_step(pf, x1, tile < cur.n_tiles, false);
+            do_step(wb, x0, tile < cur.n_tiles, false);
+            do_step(wc, x1, tile < cur.n_tiles, cross_wc);
+        }
+    }
+    if (cross_wc) {   // the next phase expects its first item in pf
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u) pf[u] = wc[u];
     }
     // Order in this compute unit's memory queue at the end of a phase: the last epilogue's stores,
     // then the other waves' first chunk of the next phase, then (after the acknowledgement) the
     // barrier signal, and only then the rest of the next phase's requests.
-    if (my_tiles == 0 && next_issued) {     // nothing was consumed: the chunk requested on entry sits in wb
-#pragma unroll
-        for (int u = 0; u < kChunk; ++u) pf[u] = wb[u];
-    }
     block_sync_lds();                       // the last epilogue's stores have been issued
     if (!reducer && !next_issued) load_wchunk(pf, next, blockIdx.x, 0, wave, lane);
     if (reducer) {
