@@ -196,6 +196,32 @@ __device__ __forceinline__ void load_wchunk(uint4 (&w)[kChunk], const WSrc &s, i
     }
 }
 
+// Tiles are dealt out in rounds of one per block.  An incomplete last round goes to the even-numbered
+// blocks first: blocks are placed on the eight XCDs in turn, and the odd XCDs are served about a tenth
+// slower by the memory system (stand-alone streaming probe: equal work ends 10-12 % later there), so a
+// round that does not reach every block should not end on them.
+__device__ __forceinline__ int deal_rank()   // position of this block in an incomplete round
+{
+    const int b = blockIdx.x, grid = gridDim.x;
+    return (b & 1) ? (grid + 1) / 2 + (b >> 1) : (b >> 1);
+}
+// Number of tiles of this block in a phase of n_tiles tiles, its tile number i, and its first tile
+// (>= n_tiles if it has none).
+__device__ __forceinline__ int block_tiles(int n_tiles)
+{
+    const int grid = gridDim.x;
+    return n_tiles / grid + (deal_rank() < n_tiles % grid ? 1 : 0);
+}
+__device__ __forceinline__ int block_tile(int n_tiles, int i)
+{
+    const int grid = gridDim.x, full_rounds = n_tiles / grid;
+    return i < full_rounds ? (int)blockIdx.x + i * grid : full_rounds * grid + deal_rank();
+}
+__device__ __forceinline__ int first_tile(const WSrc &s)
+{
+    return s.n_tiles >= (int)gridDim.x ? (int)blockIdx.x : deal_rank();
+}
+
 __device__ __forceinline__ void load_xchunk(uint4 (&x)[kChunk], const uint4 *Xp, int nks, int c, int wave, int lane, bool have = true)
 {
     __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(Xp), 0, have ? nks * 1024 : 0, 0x00020000);
@@ -278,7 +304,8 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     const int lane = tid & 63, wave = tid >> 6, grid = gridDim.x;
     const WSrc cur = {a.Wp, a.nks, a.n_tiles};
     const int n_chunks = (((a.nks + kFastWaves - 1) / kFastWaves) + kChunk - 1) / kChunk;
-    const int my_tiles = (int)blockIdx.x < cur.n_tiles ? (cur.n_tiles - 1 - (int)blockIdx.x) / grid + 1 : 0;
+    const int my_tiles = block_tiles(cur.n_tiles);
+    auto tile_at = [&](int i) { return block_tile(cur.n_tiles, i); };
     const int tiles_after = tiles_before + my_tiles;
     // Waves that finish tiles in this phase have stores to wait for at its end; they fetch their share
     // of the next phase's first weights only after that wait, so the wait stays short.
@@ -286,8 +313,8 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     uint4 wb[kChunk], wc[kChunk], x0[kChunk], x1[kChunk];
 
     // work items of this block: (tile, chunk) in order; pf holds item 0, wb and wc the two after it
-    int tile = blockIdx.x, c = 0;     // item being computed
-    int lt = blockIdx.x, lc = 0;      // last item whose weights have been requested
+    int ti = 0, c = 0;     // item being computed: chunk c of the block's tile number ti
+    int li = 0, lc = 0;    // last item whose weights have been requested
     bool next_issued = false;         // the next phase's first chunk has been requested
     // may_cross: the request may go to the next phase's first chunk when this phase has nothing left
     // (only on entry: later it would sit in front of the last epilogue's stores)
@@ -295,18 +322,18 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     // is fetched): the compiler counts the loads issued after the ones it waits for, and a request that
     // may or may not have been made counts as not made, which turns every wait into a wait for all loads.
     auto fetch = [&](uint4 (&dst)[kChunk], bool may_cross) {
-        if (++lc == n_chunks) { lc = 0; lt += grid; }
-        if (may_cross && !(lt < cur.n_tiles) && !next_issued && !reducer) {
-            load_wchunk(dst, next, blockIdx.x, 0, wave, lane);
+        if (++lc == n_chunks) { lc = 0; ++li; }
+        if (may_cross && !(li < my_tiles) && !next_issued && !reducer) {
+            load_wchunk(dst, next, first_tile(next), 0, wave, lane);
             next_issued = true;
         } else {
-            load_wchunk(dst, cur, lt, lc, wave, lane);
+            load_wchunk(dst, cur, li < my_tiles ? tile_at(li) : cur.n_tiles, lc, wave, lane);
         }
     };
     constexpr bool kHasPre = (EPI == EPI_RESIDUAL || epi_is_qkv(EPI));
     const bool stages = kHasPre && wave < kPreTiles && wave < my_tiles;   // this wave finishes tile number `wave`
     EpiPre pre0;
-    if (stages) epilogue_preload<EPI>(a, blockIdx.x + wave * grid, lane, pre0);
+    if (stages) epilogue_preload<EPI>(a, tile_at(wave), lane, pre0);
     fetch(wb, false);
     fetch(wc, true);
     // at most two items: wc holds the next phase's first item (the same for a whole wave: told to the
@@ -369,8 +396,8 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
         if (active) {
             ++step;
             const bool tile_done = (c == n_chunks - 1);
-            const int finished = tile;
-            if (++c == n_chunks) { c = 0; tile += grid; }
+            const int finished = tile_at(ti);
+            if (++c == n_chunks) { c = 0; ++ti; }
             if (tile_done) {
                 float *r = &sh.red[it & 1][0][0];
                 *reinterpret_cast<f32x4 *>(r + ((size_t)wave * 64 + lane) * 4) = acc;
@@ -401,14 +428,14 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
         x0[u] = __builtin_bit_cast(uint4, t0);
         x1[u] = __builtin_bit_cast(uint4, t1);
     }
-    while (tile < cur.n_tiles) {
+    while (ti < my_tiles) {
         do_step(pf, x0, true, false);
-        do_step(wb, x1, tile < cur.n_tiles, false);
-        do_step(wc, x0, tile < cur.n_tiles, cross_wc);
+        do_step(wb, x1, ti < my_tiles, false);
+        do_step(wc, x0, ti < my_tiles, cross_wc);
         if (!STATIONARY) {   // three weight buffers, two operand buffers: the pattern repeats after six steps
-            do_step(pf, x1, tile < cur.n_tiles, false);
-            do_step(wb, x0, tile < cur.n_tiles, false);
-            do_step(wc, x1, tile < cur.n_tiles, cross_wc);
+            do_step(pf, x1, ti < my_tiles, false);
+            do_step(wb, x0, ti < my_tiles, false);
+            do_step(wc, x1, ti < my_tiles, cross_wc);
         }
     }
     if (cross_wc) {   // the next phase expects its first item in pf
@@ -419,7 +446,7 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     // then the other waves' first chunk of the next phase, then (after the acknowledgement) the
     // barrier signal, and only then the rest of the next phase's requests.
     block_sync_lds();                       // the last epilogue's stores have been issued
-    if (!reducer && !next_issued) load_wchunk(pf, next, blockIdx.x, 0, wave, lane);
+    if (!reducer && !next_issued) load_wchunk(pf, next, first_tile(next), 0, wave, lane);
     if (reducer) {
         // this wave's epilogue stores must be out before the block counts its tiles as done; the wave
         // that completes the block's count signals the grid barrier
@@ -435,7 +462,7 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
             const int Tq = a.n_heads * a.head_dim / 16, Tkv = a.n_kv_heads * a.head_dim / 16, tph = a.head_dim / 16;
             const int grp = a.n_heads / a.n_kv_heads;
             for (int i = wave; i < my_tiles; i += kFastWaves) {
-                const int t = (int)blockIdx.x + i * grid;
+                const int t = tile_at(i);
                 if (t < Tq) {
                     __hip_atomic_fetch_add(a.ready + kCounterStride * (t / tph), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 } else {
@@ -445,7 +472,7 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
                 }
             }
         }
-        load_wchunk(pf, next, blockIdx.x, 0, wave, lane);
+        load_wchunk(pf, next, first_tile(next), 0, wave, lane);
     }
     if (BARRIER) block_sync_lds();          // the block's signal (if it was this block's turn) has been issued
     if (BARRIER) {
@@ -527,7 +554,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
         const LayerW w0 = layer_weights(g, 0);
         {   // weights of the first QKV tile go out before anything else
             WSrc first = {w0.qkv, (d + 31) / 32, (d + 2 * g->n_kv_heads * g->head_dim) / 16};
-            load_wchunk(pf, first, blockIdx.x, 0, wave, lane);
+            load_wchunk(pf, first, first_tile(first), 0, wave, lane);
         }
         // ---- embed (+ operand and sums of squares for the first norm)
         FastArgs a = base_args(g);
@@ -535,7 +562,8 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
         a.xp_next = g->xp_d;
         a.ssp_next = g->ssp_a;
         if (wave == 0)
-            for (int t = blockIdx.x; t < d / 16; t += grid) embed_tile<true>(g->embed, (const int32_t *)g->tok, a, t, lane);
+            // (the block that owns a tile of the residual stream here owns it in the O and down phases too)
+            for (int i = 0; i < block_tiles(d / 16); ++i) embed_tile<true>(g->embed, (const int32_t *)g->tok, a, block_tile(d / 16, i), lane);
         bar_arrive(bar);
     }
     for (int l = 0; l < n_layers; ++l) {
@@ -616,7 +644,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             const WSrc o_src = {w.o, (g->d + 31) / 32, g->d / 16};
             bool fetched = false;
             auto prefetch_o = [&]() {
-                if (!fetched) load_wchunk(pf, o_src, blockIdx.x, 0, wave, lane);
+                if (!fetched) load_wchunk(pf, o_src, first_tile(o_src), 0, wave, lane);
                 fetched = true;
             };
             // with the grid a multiple of the head count all tasks of a block belong to one head: they are
