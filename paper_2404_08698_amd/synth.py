@@ -127,6 +127,9 @@ LLAMA_13B = ModelShape(40, 5120, 40, 128, 13824, 32000, "bf16")
 # the paper also evaluates (28 layers, 32 query heads over 2 key/value heads, FFN 13696).
 GLM_6B = ModelShape(28, 4096, 32, 128, 13696, 65024, "bf16", n_kv_heads=2)
 MID_GQA = ModelShape(3, 512, 4, 128, 1408, 2048, "bf16", n_kv_heads=2)
+# d_model 2048 with FFN 6144 and vocabulary 8192: in the one-kernel step on 256 compute units its phases have
+# one, two and three work items per block (a test shape for the ends of the weight pipeline)
+RING_BF16 = ModelShape(2, 2048, 16, 128, 6144, 8192, "bf16")
 TINY_MQA = ModelShape(2, 256, 4, 64, 688, 1024, "f32", n_kv_heads=1)
 TINY_MQA_BF16 = dataclasses.replace(TINY_MQA, dtype="bf16")
 

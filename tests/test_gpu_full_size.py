@@ -220,3 +220,32 @@ def test_glm6b_shape_step_with_grouped_heads():
     k_ref, v_ref = dec.kv_read(shape.n_layers - 1, L, 1)
     assert k_gpu.shape == (1, shape.kv_dim)
     assert np.max(np.abs(k_gpu.cpu().numpy() - k_ref)) < 0.05 and np.max(np.abs(v_gpu.cpu().numpy() - v_ref)) < 0.05
+
+
+def test_phases_of_one_two_and_three_items_per_block():
+    """d_model 2048, FFN 6144, vocabulary 8192 on 256 compute units: QKV 384 tiles of one item (blocks with one
+    and with two), O 128 tiles (half the blocks have none), gate/up three items per block, down one tile of
+    three items with the operand streamed, LM head two: the ends of the persistent kernel's weight ring.
+    Against the oracle, and against the one-launch-per-operation path bit for bit."""
+    shape = synth.RING_BF16
+    L = 200
+    w = synth.make_weights(shape, 9, device="cuda")
+    model = B.Model(shape, w, max_window=32, max_positions=L + 64)
+    model_l = B.Model(shape, w, max_window=32, max_positions=L + 64, gemm_path=B.GEMM_MFMA_LAUNCHES)
+    kv, kv_l = B.KVCache(model, L + 64), B.KVCache(model_l, L + 64)
+    w_host = {k_: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k_, v in w.items()}
+    dec = od.Decoder(shape, w_host, L + 64)
+    _seed_both(shape, dec, [kv, kv_l], L, seed=10)
+    for M in (8, 1, 5):
+        kv.truncate(L)
+        kv_l.truncate(L)
+        window = synth.random_tokens(shape.vocab, 8, 12)[:M]
+        ref = dec.forward(window)
+        a, nxt, preds, got = _step_logits(model, kv, window)
+        a2, nxt2, preds2, got2 = _step_logits(model_l, kv_l, window)
+        assert torch.equal(got, got2) and (a, nxt, preds) == (a2, nxt2, preds2), M
+        err = float(np.max(np.abs(got.cpu().numpy().astype(np.float64) - ref)))
+        assert err < TOL["bf16"], (M, err)
+        for r in range(M):
+            if top2_gap(ref[r]) > TOL["bf16"]:
+                assert preds[r] == od.argmax(ref[r])
