@@ -308,9 +308,6 @@ class Model:
         return {"steps": steps.value, "ms": dict(zip(PROF_CATEGORIES, list(ms))),
                 "intervals": dict(zip(PROF_CATEGORIES, list(cnt)))}
 
-    __del__ = close
-
-
 class KVCache:
     """anpd_kv_*: one sequence's paged KV cache in a torch-allocated pool."""
 

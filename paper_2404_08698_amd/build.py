@@ -24,22 +24,7 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err)
-    build_probe()
     return LIB
-
-
-PROBE = os.path.join(HERE, "stream_probe")
-
-
-def build_probe() -> str:
-    """The stand-alone probe of the weight access pattern (csrc/stream_probe.hip): an executable beside the library."""
-    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-o", PROBE, os.path.join(CSRC, "stream_probe.hip")]
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed on stream_probe.hip:\n" + res.stderr)
-    return PROBE
 
 
 if __name__ == "__main__":

@@ -87,3 +87,46 @@ def test_counts_span_the_prompt_generation_boundary():
     # the pair (2 -> 3) straddles the boundary and must be counted
     assert ngram.query(s, [2], 2) == 3
     assert ngram.query(s, [1, 2], 3) == 3
+
+
+def _independent_level(s, ctx, n):
+    """Level-n answer from a library counter over the n-tuples of s (no scan of windows by index as the oracle
+    does): count every tuple zip(s, s[1:], ..., s[n-1:]), keep those whose first n-1 items are ctx, take the
+    most frequent last item, the one whose last such tuple starts latest among equals."""
+    tuples = list(zip(*[s[j:] for j in range(n)]))
+    counts = collections.Counter(tuples)
+    foll = {t[-1]: c for t, c in counts.items() if t[:-1] == tuple(ctx)}
+    if not foll:
+        return None
+    top = max(foll.values())
+    tied = [f for f, c in foll.items() if c == top]
+    last_start = {f: max(i for i, t in enumerate(tuples) if t == tuple(ctx) + (f,)) for f in tied}
+    return max(tied, key=lambda f: last_start[f])
+
+
+def test_higher_levels_and_mln_against_tuple_counter_exhaustively():
+    # Section 3.1 (Query at level n) and Section 3.2 / Algorithm 2 (longest level first): every sequence over
+    # a 3-letter alphabet up to length 8, every context of length 2 and 3, and the multi-level answer on every
+    # tail of length 3, against a formulation that shares nothing with the oracle's scan
+    alphabet = range(3)
+    contexts = {n: list(itertools.product(alphabet, repeat=n - 1)) for n in (2, 3, 4)}
+    for T in range(1, 9):
+        for s in itertools.product(alphabet, repeat=T):
+            want = {}
+            for n in (2, 3, 4):
+                for ctx in contexts[n]:
+                    want[ctx] = _independent_level(s, ctx, n)
+                    if n > 2:
+                        assert ngram.query(s, list(ctx), n) == want[ctx], (s, ctx, n)
+            for tail in contexts[4]:
+                exp = (None, 0)
+                for n in (4, 3, 2):
+                    r = want[tail[len(tail) - (n - 1):]]
+                    if r is not None:
+                        exp = (r, n)
+                        break
+                assert ngram.mln_query(s, list(tail), 2, 4) == exp, (s, tail)
+            # a tail shorter than a level's context skips that level
+            for tail in contexts[2]:
+                r = want[tail]
+                assert ngram.mln_query(s, list(tail), 2, 4) == ((r, 2) if r is not None else (None, 0))
