@@ -331,6 +331,20 @@ int32_t anpd_linear(const float *X, const void *W, float *Y, int32_t M, int32_t 
                     int32_t dtype, int32_t path, void *workspace, size_t workspace_bytes,
                     void *stream);
 
+/* anpd_linear for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and the same bits as
+ * anpd_linear on path ANPD_GEMM_MFMA (bf16 weights packed by anpd_pack_weights), but the split form of X
+ * is kept in a device array that is part of the library (2 MiB, held by every GPU the library runs on
+ * until the process ends) instead of a workspace argument.  The call allocates and frees nothing and
+ * calls no allocating routine; the array is cleared by a kernel, not by a memset.
+ *   X, Y, W: DEVICE, as in anpd_linear.  1 <= M <= ANPD_MAX_WINDOW, N % 16 == 0, K % 8 == 0,
+ *   K <= ANPD_LINEAR_STATIC_MAX_K (ANPD_E_CAPACITY beyond that, nothing is launched).
+ * Asynchronous on stream.  All calls on one GPU share that GPU's array: calls that overlap on one GPU
+ * (different streams, different threads) race; serialise them. */
+#define ANPD_LINEAR_STATIC_MAX_K 16384
+int32_t anpd_linear_static(const float *X, const void *W, float *Y, int32_t M, int32_t N, int32_t K,
+                           void *stream);
+
 #ifdef __cplusplus
 }
 #endif

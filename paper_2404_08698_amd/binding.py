@@ -32,7 +32,7 @@ EXPORTS = (
     "anpd_kv_set_page_order", "anpd_kv_num_pages", "anpd_kv_write", "anpd_kv_read",
     "anpd_verify", "anpd_verify_tree", "anpd_verify_batch", "anpd_prefill_workspace_bytes", "anpd_prefill", "anpd_linear_workspace_bytes", "anpd_linear",
     "anpd_model_profile", "anpd_model_profile_read", "anpd_packed_bytes", "anpd_pack_weights",
-    "anpd_model_trace", "anpd_model_set_barrier_spin_limit",
+    "anpd_model_trace", "anpd_model_set_barrier_spin_limit", "anpd_linear_static",
 )
 PROF_CATEGORIES = ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "attn", "other", "step")
 
@@ -132,6 +132,8 @@ def lib():
     L.anpd_linear_workspace_bytes.argtypes = [C.c_int32, C.c_int32]
     L.anpd_linear.restype = C.c_int32
     L.anpd_linear.argtypes = [vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, C.c_size_t, vp]
+    L.anpd_linear_static.restype = C.c_int32
+    L.anpd_linear_static.argtypes = [vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, vp]
     L.anpd_packed_bytes.restype = C.c_size_t
     L.anpd_packed_bytes.argtypes = [C.c_int32, C.c_int32]
     L.anpd_pack_weights.restype = C.c_int32
@@ -461,6 +463,14 @@ def linear(X, W, path: int, stream=None, packed=None, Y=None, workspace=None):
         wptr = packed.data_ptr()
     _check(lib().anpd_linear(X.data_ptr(), wptr, Y.data_ptr(), M, N, K, dtype, path, ws.data_ptr(), nb,
                              _stream_ptr(stream)))
+    return Y
+
+
+def linear_static(X, packed, N: int, Y, stream=None):
+    """anpd_linear_static: Y = X @ W.T on the matrix cores with the library's built-in scratch; allocates
+    nothing (the caller passes the output).  ``packed``: W as written by pack_weights."""
+    M, K = X.shape
+    _check(lib().anpd_linear_static(X.data_ptr(), packed.data_ptr(), Y.data_ptr(), M, N, K, _stream_ptr(stream)))
     return Y
 
 

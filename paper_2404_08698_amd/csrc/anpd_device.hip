@@ -1519,3 +1519,72 @@ int32_t anpd_linear(const float *X, const void *W, float *Y, int32_t M, int32_t 
 }
 
 }  // extern "C"
+
+// ---- anpd_linear without a workspace argument and without any allocation ---------------------
+//
+// The split form of X lives in a file-scope device array.  Each device holds its own copy of the
+// array at its own address, so the address is looked up once per device (with that device current)
+// and kept; host code never uses the array's name for anything but that lookup.
+namespace {
+
+constexpr size_t kStaticScratchBytes = (size_t)(ANPD_LINEAR_STATIC_MAX_K / 32) * 4 * 1024;
+constexpr int kMaxDevices = 64;
+
+struct StaticScratch {
+    void *ptr;
+    int n_cu;
+};
+StaticScratch g_static_scratch[kMaxDevices];   // zero-initialised: ptr == nullptr means "not looked up yet"
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Clears `n16` 16-byte words (a kernel rather than a memset node, so that a caller may capture the call).
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint4 *p, size_t n16)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n16) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+extern "C" int32_t anpd_linear_static(const float *X, const void *W, float *Y, int32_t M, int32_t N, int32_t K, void *stream)
+{
+    if (!X || !W || !Y) return fail(ANPD_E_INVAL, "anpd_linear_static: NULL argument");
+    if (M < 1 || M > ANPD_MAX_WINDOW || K < 8 || K % 8 != 0 || N < 16 || N % 16 != 0)
+        return fail(ANPD_E_INVAL, "anpd_linear_static: need 1 <= M <= %d, K %% 8 == 0, N %% 16 == 0", ANPD_MAX_WINDOW);
+    if (K > ANPD_LINEAR_STATIC_MAX_K)
+        return fail(ANPD_E_CAPACITY, "anpd_linear_static: K = %d exceeds the built-in scratch (K <= %d); use anpd_linear with a workspace",
+                    K, ANPD_LINEAR_STATIC_MAX_K);
+    const size_t need = anpd_linear_workspace_bytes(M, K);
+    if (need == 0 || need > kStaticScratchBytes) return fail(ANPD_E_CAPACITY, "anpd_linear_static: operand does not fit the built-in scratch");
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(ANPD_E_CAPACITY, "anpd_linear_static: device index %d not supported", dev);
+    StaticScratch &sc = g_static_scratch[dev];
+    if (!sc.ptr) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(ANPD_E_HIP, "anpd_linear_static: the scratch array has no address on device %d", dev);
+        int n_cu = 0;
+        HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+        sc.n_cu = n_cu > 0 ? n_cu : 256;
+        sc.ptr = p;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const int cls = window_class(M);
+    // the array keeps the previous call's operand: rows and k-steps this call does not write must read as zeros
+    const size_t n16 = need / 16;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, (uint4 *)sc.ptr, n16);
+    hipLaunchKernelGGL(split_packed_kernel, dim3((K / 4 + 255) / 256, M), dim3(256), 0, st, X, (bf16_t *)sc.ptr, M, K, cls);
+    FastArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.Wp = (const uint4 *)W;
+    a.Xp = (const uint4 *)sc.ptr;
+    a.nks = (K + 31) / 32;
+    a.n_tiles = N / 16;
+    a.M = M;
+    a.cls = cls;
+    a.Y = Y;
+    a.ldy = N;
+    return launch_fast<EPI_PLAIN>(a, sc.n_cu, false, st);
+}
