@@ -159,6 +159,7 @@ struct anpd_model {
     bool mega;            // the one-kernel step is available
     bool mega_tree;       // ... and so is its draft-tree form
     bool mega_batch;      // ... and its several-sequences form
+    int mega_kc;          // k-steps per wave per work item of the one-kernel step (8: d_model <= 4096, 10: <= 5120)
     long long *trace;     // optional device buffer for barrier timestamps
     int mega_grid;
     bool plain_launch;    // launch the one-kernel step without the cooperative-launch API (profiling aid)
@@ -253,13 +254,23 @@ int32_t launch_fast(FastArgs &a, int n_cu, bool force_stream, hipStream_t st)
             size_t smem = (size_t)2 * kFastWaves * 2 * 256 * sizeof(float);
             hipLaunchKernelGGL((gemm_group_kernel<2, 2, EPI>), grid, block, smem, st, a);
         } else if (nt == 2 && per_block > 4) {
-            size_t smem = (size_t)8 * kFastWaves * 2 * 256 * sizeof(float);
-            static bool attr_set3 = false;
-            if (!attr_set3) {
-                HIP_TRY(hipFuncSetAttribute((const void *)gemm_group_kernel<2, 8, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-                attr_set3 = true;
-            }
-            hipLaunchKernelGGL((gemm_group_kernel<2, 8, EPI>), grid, block, smem, st, a);
+            // six, seven or eight tiles per pass: the smallest form that takes the block's tiles in one pass
+            // (the eight-tile form sits at the register limit)
+#define ANPD_GROUP2(TG_)                                                                                                          \
+    do {                                                                                                                          \
+        size_t smem = (size_t)TG_ * kFastWaves * 2 * 256 * sizeof(float);                                                         \
+        static bool attr_set_g = false;                                                                                           \
+        if (!attr_set_g) {                                                                                                        \
+            HIP_TRY(hipFuncSetAttribute((const void *)gemm_group_kernel<2, TG_, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                        (int)smem));                                                                              \
+            attr_set_g = true;                                                                                                    \
+        }                                                                                                                         \
+        hipLaunchKernelGGL((gemm_group_kernel<2, TG_, EPI>), grid, block, smem, st, a);                                           \
+    } while (0)
+            if (per_block <= 6) ANPD_GROUP2(6);
+            else if (per_block == 7) ANPD_GROUP2(7);
+            else ANPD_GROUP2(8);
+#undef ANPD_GROUP2
         } else if (nt == 2) {
             size_t smem = (size_t)4 * kFastWaves * 2 * 256 * sizeof(float);
             static bool attr_set2 = false;
@@ -679,6 +690,8 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, 
     const void *fn64[] = {(const void *)verify_mega_kernel<64, MEGA_CHAIN>, (const void *)verify_mega_kernel<64, MEGA_TREE>,
                           (const void *)verify_mega_kernel<64, MEGA_BATCH>};
     const void *fn = c.head_dim == 128 ? fn128[form] : fn64[form];
+    if (m->mega_kc == 10)   // d_model above 4096 (chains only)
+        fn = c.head_dim == 128 ? (const void *)verify_mega_kernel<128, MEGA_CHAIN, 1, 10> : (const void *)verify_mega_kernel<64, MEGA_CHAIN, 1, 10>;
     if (m->plain_launch) {
         // profiling aid (see anpd_model_create): an ordinary launch of the same grid
         HIP_TRY(hipLaunchKernel(fn, dim3((unsigned)m->mega_grid), dim3(kFastThreads), args, 0, st));
@@ -966,12 +979,18 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
         const char *pl = std::getenv("ANPD_MEGA_PLAIN_LAUNCH");
         m->plain_launch = pl && pl[0] == '1';
     }
-    if (e == hipSuccess && m->mfma && cfg->gemm_path != ANPD_GEMM_MFMA_LAUNCHES && (cfg->d_model + 31) / 32 <= 2 * kChunk * kFastWaves) {
+    m->mega_kc = (cfg->d_model + 31) / 32 <= 2 * kChunk * kFastWaves ? kChunk : 10;
+    if (e == hipSuccess && m->mfma && cfg->gemm_path != ANPD_GEMM_MFMA_LAUNCHES && (cfg->d_model + 31) / 32 <= 2 * 10 * kFastWaves) {
         // the persistent step needs every block resident at once: one block per compute unit
         int per_cu = 0;
-        hipError_t oe = cfg->head_dim == 128
-                            ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, verify_mega_kernel<128>, kFastThreads, 0)
-                            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, verify_mega_kernel<64>, kFastThreads, 0);
+        hipError_t oe;
+        if (m->mega_kc == kChunk)
+            oe = cfg->head_dim == 128 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, verify_mega_kernel<128>, kFastThreads, 0)
+                                      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, verify_mega_kernel<64>, kFastThreads, 0);
+        else
+            oe = cfg->head_dim == 128
+                     ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, verify_mega_kernel<128, MEGA_CHAIN, 1, 10>, kFastThreads, 0)
+                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, verify_mega_kernel<64, MEGA_CHAIN, 1, 10>, kFastThreads, 0);
         if (oe == hipSuccess && per_cu >= 1) {
             std::vector<LayerW> tab((size_t)cfg->n_layers);
             for (int l = 0; l < cfg->n_layers; ++l) {
@@ -990,14 +1009,15 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
             hipError_t te = cfg->head_dim == 128
                                 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_t, verify_mega_kernel<128, MEGA_TREE>, kFastThreads, 0)
                                 : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_t, verify_mega_kernel<64, MEGA_TREE>, kFastThreads, 0);
-            m->mega_tree = te == hipSuccess && per_cu_t >= 1;
+            m->mega_tree = te == hipSuccess && per_cu_t >= 1 && m->mega_kc == kChunk;
             if (te != hipSuccess) (void)hipGetLastError();
             int per_cu_b = 0;
             te = cfg->head_dim == 128
                      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_b, verify_mega_kernel<128, MEGA_BATCH>, kFastThreads, 0)
                      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_b, verify_mega_kernel<64, MEGA_BATCH>, kFastThreads, 0);
-            m->mega_batch = te == hipSuccess && per_cu_b >= 1;
+            m->mega_batch = te == hipSuccess && per_cu_b >= 1 && m->mega_kc == kChunk;
             if (te != hipSuccess) (void)hipGetLastError();
+
         } else {
             (void)hipGetLastError();
         }

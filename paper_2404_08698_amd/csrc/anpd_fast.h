@@ -35,8 +35,13 @@ __device__ __forceinline__ void xp_store4(bf16_t *xp, int cls, int m, int k, f32
     bf16_t hi[4], lo[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        hi[i] = f32_to_bf16(v[i]);
-        lo[i] = f32_to_bf16(v[i] - bf16_to_f32(hi[i]));
+        // v is often a product formed by the caller.  The value is made opaque here so that the subtraction
+        // below is never fused with that product: whether the compiler fuses depends on the code around
+        // the call, and the same epilogue is instantiated in several kernels whose bits must agree.
+        float t = v[i];
+        asm volatile("" : "+v"(t));
+        hi[i] = f32_to_bf16(t);
+        lo[i] = f32_to_bf16(t - bf16_to_f32(hi[i]));
     }
     uint2 ph = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
     uint2 pl = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
@@ -209,7 +214,7 @@ __device__ __forceinline__ void compute_rinv(const FastArgs &a, float *rinv /* L
         float tot = 0.f;
 #pragma unroll 8
         for (int g = 0; g < NG; ++g) tot += scratch[g * 32 + tid];
-        rinv[tid] = 1.0f / sqrtf(tot * a.inv_d + a.eps);
+        rinv[tid] = 1.0f / sqrtf(fmaf(tot, a.inv_d, a.eps));
     }
     block_sync_lds();
 }
@@ -240,7 +245,7 @@ __device__ __forceinline__ void rinv_from_lds(const FastArgs &a, float *rinv, co
         float tot = 0.f;
 #pragma unroll 8
         for (int g = 0; g < 64; ++g) tot += scratch[g * 32 + tid];
-        rinv[tid] = 1.0f / sqrtf(tot * a.inv_d + a.eps);
+        rinv[tid] = 1.0f / sqrtf(fmaf(tot, a.inv_d, a.eps));
     }
 }
 
@@ -377,7 +382,8 @@ __device__ __forceinline__ void epilogue(const FastArgs &a, int tile, int m, int
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 float2 cs = pre ? pre->cs[i] : a.rope[(size_t)rpos * half + i0 + i];
-                o[i] = kg < 2 ? y[i] * cs.x - other[i] * cs.y : y[i] * cs.x + other[i] * cs.y;
+                const float cross = other[i] * cs.y;   // (explicit fused form: see xp_store4)
+                o[i] = kg < 2 ? fmaf(y[i], cs.x, -cross) : fmaf(y[i], cs.x, cross);
             }
             const int dim = i0 + (kg < 2 ? 0 : half);
             if (which == 0) {
@@ -441,6 +447,26 @@ __device__ __forceinline__ void reduce_and_finish(const FastArgs &a, int tile, c
             int m = p * 16 + slot;
             epilogue<EPI, COH>(a, tile, m, kg, tot[2 * p] + tot[2 * p + 1], m < a.M, rinv);
         }
+    }
+}
+
+// The same for an operand of NF fragments in the class-8 arrangement (packed_class): fragment f holds rows
+// 8 f .. 8 f + 7 as (hi | lo) slots, and its partial tiles are finished exactly like the one fragment of a
+// window of up to 8 rows.  red: [nw][NF][256].  `pre` (staged operands of rows 0..7) serves fragment 0.
+template <int NF, int EPI, bool COH = false>
+__device__ __forceinline__ void reduce_and_finish_packed(const FastArgs &a, int tile, const float *red, int nw, int lane,
+                                                         const float *rinv, const EpiPre *pre = nullptr)
+{
+    const int slot = lane & 15, kg = lane >> 4;
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+        f32x4 tot = *reinterpret_cast<const f32x4 *>(red + ((size_t)f * 64 + lane) * 4);
+        for (int w = 1; w < nw; ++w) tot += *reinterpret_cast<const f32x4 *>(red + (((size_t)w * NF + f) * 64 + lane) * 4);
+        f32x4 lo;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lo[i] = row_down8(tot[i]);
+        const int m = 8 * f + (slot & 7);
+        epilogue<EPI, COH>(a, tile, m, kg, tot + lo, slot < 8 && m < a.M, rinv, f == 0 ? pre : nullptr);
     }
 }
 

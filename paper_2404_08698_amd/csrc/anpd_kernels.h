@@ -211,13 +211,17 @@ __host__ __device__ __forceinline__ int window_class(int M) { return M <= 8 ? 8 
 // lane = 16 * kg + slot holds columns 32 * ks + 8 * kg .. + 8 of the row in `slot`.
 //   class 8:  one fragment; slot m = hi of row m, slot m + 8 = lo of row m;
 //   class 16: fragments (hi, lo) of rows 0..15;
-//   class 32: fragments (hi, lo) of rows 0..15, then (hi, lo) of rows 16..31.
+//   class 32: fragments (hi, lo) of rows 0..15, then (hi, lo) of rows 16..31;
+//   packed_class(nf), nf >= 2: nf fragments in the class-8 arrangement, fragment f holding rows 8 f .. 8 f + 7
+//   (slot m % 8 = hi, slot m % 8 + 8 = lo): the one-kernel step's form for windows of more than 8 rows.
 // Returns the bf16-element offset of (row m, column k, hi|lo).
+__host__ __device__ constexpr int packed_class(int nf) { return nf == 1 ? 8 : 1000 + nf; }
 __host__ __device__ __forceinline__ size_t xp_offset(int cls, int m, int k, int lo)
 {
     const int ks = k >> 5, kg = (k >> 3) & 3, j = k & 7;
     int nt, frag, slot;
     if (cls == 8) { nt = 1; frag = 0; slot = m + 8 * lo; }
+    else if (cls >= 1000) { nt = cls - 1000; frag = m >> 3; slot = (m & 7) + 8 * lo; }
     else { nt = cls >> 3; frag = 2 * (m >> 4) + lo; slot = m & 15; }
     return ((((size_t)ks * nt + frag) * 64) + (size_t)kg * 16 + slot) * 8 + j;
 }

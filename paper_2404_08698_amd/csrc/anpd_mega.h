@@ -180,18 +180,19 @@ struct WSrc {
 
 constexpr int kChunk = 8;   // k-steps per wave per pipeline item (half a tile when K = 4096)
 
-// k-steps wave + 8 * (8 c + u), u = 0..7, of tile `tile`.  Buffer loads: the descriptor covers exactly
+// k-steps wave + 8 * (KC c + u), u = 0..KC-1, of tile `tile`.  Buffer loads: the descriptor covers exactly
 // the tile's nks blocks, so k-steps past the end (and tiles that do not exist) read as zeros
 // without a branch, and one offset register per thread serves every load.
-__device__ __forceinline__ void load_wchunk(uint4 (&w)[kChunk], const WSrc &s, int tile, int c, int wave, int lane)
+template <int KC>
+__device__ __forceinline__ void load_wchunk(uint4 (&w)[KC], const WSrc &s, int tile, int c, int wave, int lane)
 {
     const bool have = tile < s.n_tiles;
     const uint4 *base = s.Wp + (size_t)(have ? tile : 0) * s.nks * 64;
     __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(base), 0, have ? s.nks * 1024 : 0, 0x00020000);
     const int voff = (wave * 64 + lane) * 16;
 #pragma unroll
-    for (int u = 0; u < kChunk; ++u) {
-        u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, (kChunk * c + u) * kFastWaves * 1024, kAuxStream);
+    for (int u = 0; u < KC; ++u) {
+        u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, (KC * c + u) * kFastWaves * 1024, kAuxStream);
         w[u] = make_uint4(v.x, v.y, v.z, v.w);
     }
 }
@@ -222,15 +223,19 @@ __device__ __forceinline__ int first_tile(const WSrc &s)
     return s.n_tiles >= (int)gridDim.x ? (int)blockIdx.x : deal_rank();
 }
 
-__device__ __forceinline__ void load_xchunk(uint4 (&x)[kChunk], const uint4 *Xp, int nks, int c, int wave, int lane, bool have = true)
+// The same k-steps of the activation operand, NF fragments each (Xp[k-step][fragment][lane]).
+template <int NF, int KC>
+__device__ __forceinline__ void load_xchunk(uint4 (&x)[NF][KC], const uint4 *Xp, int nks, int c, int wave, int lane, bool have = true)
 {
-    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(Xp), 0, have ? nks * 1024 : 0, 0x00020000);
-    const int voff = (wave * 64 + lane) * 16;
+    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(Xp), 0, have ? nks * NF * 1024 : 0, 0x00020000);
+    const int voff = (wave * NF * 64 + lane) * 16;
 #pragma unroll
-    for (int u = 0; u < kChunk; ++u) {
-        u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, (kChunk * c + u) * kFastWaves * 1024, kAuxCoherent);
-        x[u] = make_uint4(v.x, v.y, v.z, v.w);
-    }
+    for (int u = 0; u < KC; ++u)
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, ((KC * c + u) * kFastWaves * NF + f) * 1024, kAuxCoherent);
+            x[f][u] = make_uint4(v.x, v.y, v.z, v.w);
+        }
 }
 
 // Epilogue operands of a block's first tiles, staged in LDS by the wave that will finish the
@@ -239,6 +244,7 @@ __device__ __forceinline__ void load_xchunk(uint4 (&x)[kChunk], const uint4 *Xp,
 // there when the epilogue runs: a load issued at the epilogue would queue behind the weight
 // loads in flight, and the gain vector comes from HBM.
 constexpr int kPreTiles = 3;
+constexpr int kMaxFrags = 2;   // activation fragments per k-step the one-kernel step is built for (windows of up to 16 rows)
 struct EpiPreLds {
     f32x4 x[64], g[64];
     float2 cs[4][64];
@@ -271,7 +277,7 @@ __device__ __forceinline__ void pre_from_lds(EpiPre &p, const EpiPreLds &d, int 
 
 struct MegaShared {
     union {
-        float red[2][kFastWaves][256];
+        float red[2][kFastWaves][kMaxFrags][256];
         AttnShared<128> attn128;
         AttnShared<64> attn64;
     };
@@ -291,54 +297,67 @@ __device__ __forceinline__ AttnShared<64> &attn_shared<64>(MegaShared &sh) { ret
 // One GEMM phase.  On entry pf holds (or has in flight) the weights of this block's first work
 // item, loaded by the previous phase; on exit those of the next phase's first item are in flight
 // (issued after this block has arrived at the phase barrier, so the arrival does not wait for them).
-// A work item is a chunk of kChunk k-steps per wave of one tile.
+// A work item is a chunk of KC k-steps per wave of one tile.
 // STATIONARY: K needs at most two chunks; the activation operand stays in registers for all tiles.
 // BARRIER = false (QKV): the phase does not end in a grid barrier; its consumers wait for per-head tile
 // counts (a.ready).  The barrier's counters assume that no block is more than one barrier ahead of
 // another, so a barrier that is not waited for must not be signalled either.
-template <int EPI, bool STATIONARY, bool BARRIER = true>
-__device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, uint4 (&pf)[kChunk], MegaShared &sh,
+// NF: fragments of the activation operand per k-step, each holding 8 window rows as (hi | lo) slots like
+// the one fragment of a window of up to 8 rows, so rows 8 f .. 8 f + 7 go through exactly the arithmetic
+// of that window.  Only NF = 1 is instantiated: with NF = 2 (9 to 16 rows) the resident operand takes 128
+// registers, the kernel spills 70 to 160 registers per lane around the epilogues and the step is slower
+// than one launch per operation (7B shape, 9 rows: 4.33 against 3.39 ms).
+// KC: k-steps per wave per item; 2 KC * 8 k-steps must cover d_model for the stationary phases (8 up to
+// d_model 4096, 10 up to 5120).
+template <int EPI, bool STATIONARY, bool BARRIER = true, int NF = 1, int KC = kChunk>
+__device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, uint4 (&pf)[KC], MegaShared &sh,
                                            GridBarrier &bar, int &tiles_before)
 {
+    constexpr int RING = NF * KC <= 8 ? 3 : 2;   // weight items in flight per wave (registers: NF * 2 KC operand fragments stay resident)
     const int tid = fresh_tid();
-    const int lane = tid & 63, wave = tid >> 6, grid = gridDim.x;
+    const int lane = tid & 63, wave = tid >> 6;
     const WSrc cur = {a.Wp, a.nks, a.n_tiles};
-    const int n_chunks = (((a.nks + kFastWaves - 1) / kFastWaves) + kChunk - 1) / kChunk;
+    const int n_chunks = (((a.nks + kFastWaves - 1) / kFastWaves) + KC - 1) / KC;
     const int my_tiles = block_tiles(cur.n_tiles);
     auto tile_at = [&](int i) { return block_tile(cur.n_tiles, i); };
     const int tiles_after = tiles_before + my_tiles;
     // Waves that finish tiles in this phase have stores to wait for at its end; they fetch their share
     // of the next phase's first weights only after that wait, so the wait stays short.
     const bool reducer = wave < my_tiles;
-    uint4 wb[kChunk], wc[kChunk], x0[kChunk], x1[kChunk];
+    uint4 wb[KC], wc[KC], x0[NF][KC], x1[NF][KC];   // (wc is unused with a ring of two)
 
-    // work items of this block: (tile, chunk) in order; pf holds item 0, wb and wc the two after it
+    // work items of this block: (tile, chunk) in order; pf holds item 0, wb (and wc) the one(s) after it
     int ti = 0, c = 0;     // item being computed: chunk c of the block's tile number ti
     int li = 0, lc = 0;    // last item whose weights have been requested
     bool next_issued = false;         // the next phase's first chunk has been requested
     // may_cross: the request may go to the next phase's first chunk when this phase has nothing left
     // (only on entry: later it would sit in front of the last epilogue's stores)
-    // Every call issues kChunk loads, also past the block's last item (an empty descriptor: zeros, nothing
+    // Every call issues KC loads, also past the block's last item (an empty descriptor: zeros, nothing
     // is fetched): the compiler counts the loads issued after the ones it waits for, and a request that
     // may or may not have been made counts as not made, which turns every wait into a wait for all loads.
-    auto fetch = [&](uint4 (&dst)[kChunk], bool may_cross) {
+    auto fetch = [&](uint4 (&dst)[KC], bool may_cross) {
         if (++lc == n_chunks) { lc = 0; ++li; }
         if (may_cross && !(li < my_tiles) && !next_issued && !reducer) {
-            load_wchunk(dst, next, first_tile(next), 0, wave, lane);
+            load_wchunk<KC>(dst, next, first_tile(next), 0, wave, lane);
             next_issued = true;
         } else {
-            load_wchunk(dst, cur, li < my_tiles ? tile_at(li) : cur.n_tiles, lc, wave, lane);
+            load_wchunk<KC>(dst, cur, li < my_tiles ? tile_at(li) : cur.n_tiles, lc, wave, lane);
         }
     };
-    constexpr bool kHasPre = (EPI == EPI_RESIDUAL || epi_is_qkv(EPI));
+    // (the staged epilogue operands are laid out for the one-fragment window)
+    constexpr bool kHasPre = (EPI == EPI_RESIDUAL || epi_is_qkv(EPI)) && NF == 1;
     const bool stages = kHasPre && wave < kPreTiles && wave < my_tiles;   // this wave finishes tile number `wave`
     EpiPre pre0;
     if (stages) epilogue_preload<EPI>(a, tile_at(wave), lane, pre0);
-    fetch(wb, false);
-    fetch(wc, true);
-    // at most two items: wc holds the next phase's first item (the same for a whole wave: told to the
-    // compiler, or it takes everything a step does under this flag for lane-dependent)
-    const bool cross_wc = __builtin_amdgcn_readfirstlane((int)next_issued) != 0;
+    if constexpr (RING == 3) {
+        fetch(wb, false);
+        fetch(wc, true);
+    } else {
+        fetch(wb, true);
+    }
+    // at most RING - 1 items: the last buffer of the ring holds the next phase's first item (the same for
+    // a whole wave: told to the compiler, or it takes everything a step does under this flag for lane-dependent)
+    const bool cross_last = __builtin_amdgcn_readfirstlane((int)next_issued) != 0;
     if (stages) pre_to_lds<EPI>(sh.pre[wave], pre0, lane);
 
     bar_wait(bar);
@@ -348,21 +367,23 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     // BEFORE the weights requested at the end of the step, so that no step's operand waits behind
     // weights of later steps (a wave's loads return in order).
     const int n_steps = my_tiles * n_chunks;
-    load_xchunk(x0, a.Xp, a.nks, 0, wave, lane);
-    if (STATIONARY || 1 < n_steps) load_xchunk(x1, a.Xp, a.nks, STATIONARY ? 1 : 1 % n_chunks, wave, lane);
+    load_xchunk<NF, KC>(x0, a.Xp, a.nks, 0, wave, lane);
+    if (STATIONARY || 1 < n_steps) load_xchunk<NF, KC>(x1, a.Xp, a.nks, STATIONARY ? 1 : 1 % n_chunks, wave, lane);
     // the RMSNorm scale is needed by the first epilogue only: its partial sums are requested here and
     // reduced after the first tile's MFMAs, off the path from the barrier to the first MFMA
     constexpr bool kNorm = (epi_has_norm(EPI) || EPI == EPI_LM_ARGMAX);
-    const bool late_norm = kNorm && a.n_ss <= 256 && my_tiles > 0;
+    const bool late_norm = NF == 1 && kNorm && a.n_ss <= 256 && my_tiles > 0;
     float nv[4];
     if (late_norm) rinv_issue<true>(a, nv, tid);
-    else if (kNorm) compute_rinv<true>(a, sh.rinv, &sh.red[1][0][0]);
+    else if (kNorm) compute_rinv<true>(a, sh.rinv, sh.rscratch);
 
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    f32x4 acc[NF];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) acc[f] = (f32x4){0.f, 0.f, 0.f, 0.f};
     int it = 0;
     int step = 0;
-    // pf, wb and wc form a ring: a step multiplies the oldest buffer and requests the item three steps
-    // ahead into the same registers, so three items stay in flight per wave.  (Passing the items down a
+    // The weight buffers form a ring: a step multiplies the oldest buffer and requests the item RING steps
+    // ahead into the same registers, so RING items stay in flight per wave.  (Passing the items down a
     // chain pf <- wb <- wc by value makes every step wait for the load it has just issued.)
     // xs: the operand buffer of this step when the operand is streamed (x0 and x1 in turn).
     // active: the block still has an item for this step.  The loop has one exit, at its top, and every
@@ -370,28 +391,34 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     // have run out): with several exits, or requests made on some paths only, the compiler must assume
     // that the buffer a step waits for was requested last, and makes every step wait for all loads.
     // keep: buf holds the next phase's first item and is not refilled.
-    auto do_step = [&](uint4 (&buf)[kChunk], uint4 (&xs)[kChunk], bool active, bool keep) __attribute__((always_inline)) {
+    auto do_step = [&](uint4 (&buf)[KC], uint4 (&xs)[NF][KC], bool active, bool keep) __attribute__((always_inline)) {
         if (active) {
             if (STATIONARY) {
                 if (c == 1) {
 #pragma unroll
-                    for (int u = 0; u < kChunk; ++u)
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, buf[u]),
-                                                                      __builtin_bit_cast(bf16x8, x1[u]), acc, 0, 0, 0);
+                    for (int u = 0; u < KC; ++u)
+#pragma unroll
+                        for (int f = 0; f < NF; ++f)
+                            acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, buf[u]),
+                                                                             __builtin_bit_cast(bf16x8, x1[f][u]), acc[f], 0, 0, 0);
                 } else {
 #pragma unroll
-                    for (int u = 0; u < kChunk; ++u)
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, buf[u]),
-                                                                      __builtin_bit_cast(bf16x8, x0[u]), acc, 0, 0, 0);
+                    for (int u = 0; u < KC; ++u)
+#pragma unroll
+                        for (int f = 0; f < NF; ++f)
+                            acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, buf[u]),
+                                                                             __builtin_bit_cast(bf16x8, x0[f][u]), acc[f], 0, 0, 0);
                 }
             } else {
 #pragma unroll
-                for (int u = 0; u < kChunk; ++u)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, buf[u]),
-                                                                  __builtin_bit_cast(bf16x8, xs[u]), acc, 0, 0, 0);
+                for (int u = 0; u < KC; ++u)
+#pragma unroll
+                    for (int f = 0; f < NF; ++f)
+                        acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, buf[u]),
+                                                                         __builtin_bit_cast(bf16x8, xs[f][u]), acc[f], 0, 0, 0);
             }
         }
-        if (!STATIONARY) load_xchunk(xs, a.Xp, a.nks, (step + 2) % n_chunks, wave, lane, active && step + 2 < n_steps);
+        if (!STATIONARY) load_xchunk<NF, KC>(xs, a.Xp, a.nks, (step + 2) % n_chunks, wave, lane, active && step + 2 < n_steps);
         if (!keep) fetch(buf, false);
         if (active) {
             ++step;
@@ -399,8 +426,10 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
             const int finished = tile_at(ti);
             if (++c == n_chunks) { c = 0; ++ti; }
             if (tile_done) {
-                float *r = &sh.red[it & 1][0][0];
-                *reinterpret_cast<f32x4 *>(r + ((size_t)wave * 64 + lane) * 4) = acc;
+                float *r = &sh.red[it & 1][0][0][0];
+#pragma unroll
+                for (int f = 0; f < NF; ++f)
+                    *reinterpret_cast<f32x4 *>(r + (((size_t)wave * NF + f) * 64 + lane) * 4) = acc[f];
                 if (late_norm && it == 0) rinv_partial_to_lds(nv, sh.rscratch, tid);
                 block_sync_lds();
                 if (late_norm && it == 0) rinv_from_lds(a, sh.rinv, sh.rscratch, tid);   // wave 0, which also finishes tile 0
@@ -408,45 +437,59 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
                     if (kHasPre && it < kPreTiles) {
                         EpiPre pre;
                         pre_from_lds<EPI>(pre, sh.pre[it], lane);
-                        reduce_and_finish<1, EPI, true>(a, finished, r, kFastWaves, lane, sh.rinv, &pre);
+                        reduce_and_finish_packed<NF, EPI, true>(a, finished, r, kFastWaves, lane, sh.rinv, &pre);
                     } else {
-                        reduce_and_finish<1, EPI, true>(a, finished, r, kFastWaves, lane, sh.rinv);
+                        reduce_and_finish_packed<NF, EPI, true>(a, finished, r, kFastWaves, lane, sh.rinv);
                     }
                 }
-                acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int f = 0; f < NF; ++f) acc[f] = (f32x4){0.f, 0.f, 0.f, 0.f};
                 ++it;
             }
         }
     };
-    // The loop is entered with the operand in registers (it is the youngest request, so the three weight
+    // The loop is entered with the operand in registers (it is the youngest request, so the weight
     // items have arrived as well): inside the loop the compiler then sees that the buffer a step needs has
-    // two younger requests behind it and lets those stay in flight.
+    // younger requests behind it and lets those stay in flight.
 #pragma unroll
-    for (int u = 0; u < kChunk; ++u) {
-        u32x4_t t0 = __builtin_bit_cast(u32x4_t, x0[u]), t1 = __builtin_bit_cast(u32x4_t, x1[u]);
-        asm volatile("" : "+v"(t0), "+v"(t1));
-        x0[u] = __builtin_bit_cast(uint4, t0);
-        x1[u] = __builtin_bit_cast(uint4, t1);
-    }
-    while (ti < my_tiles) {
-        do_step(pf, x0, true, false);
-        do_step(wb, x1, ti < my_tiles, false);
-        do_step(wc, x0, ti < my_tiles, cross_wc);
-        if (!STATIONARY) {   // three weight buffers, two operand buffers: the pattern repeats after six steps
-            do_step(pf, x1, ti < my_tiles, false);
-            do_step(wb, x0, ti < my_tiles, false);
-            do_step(wc, x1, ti < my_tiles, cross_wc);
+    for (int f = 0; f < NF; ++f)
+#pragma unroll
+        for (int u = 0; u < KC; ++u) {
+            u32x4_t t0 = __builtin_bit_cast(u32x4_t, x0[f][u]), t1 = __builtin_bit_cast(u32x4_t, x1[f][u]);
+            asm volatile("" : "+v"(t0), "+v"(t1));
+            x0[f][u] = __builtin_bit_cast(uint4, t0);
+            x1[f][u] = __builtin_bit_cast(uint4, t1);
         }
-    }
-    if (cross_wc) {   // the next phase expects its first item in pf
+    if constexpr (RING == 3) {
+        while (ti < my_tiles) {
+            do_step(pf, x0, true, false);
+            do_step(wb, x1, ti < my_tiles, false);
+            do_step(wc, x0, ti < my_tiles, cross_last);
+            if (!STATIONARY) {   // three weight buffers, two operand buffers: the pattern repeats after six steps
+                do_step(pf, x1, ti < my_tiles, false);
+                do_step(wb, x0, ti < my_tiles, false);
+                do_step(wc, x1, ti < my_tiles, cross_last);
+            }
+        }
+        if (cross_last) {   // the next phase expects its first item in pf
 #pragma unroll
-        for (int u = 0; u < kChunk; ++u) pf[u] = wc[u];
+            for (int u = 0; u < KC; ++u) pf[u] = wc[u];
+        }
+    } else {
+        while (ti < my_tiles) {
+            do_step(pf, x0, true, false);
+            do_step(wb, x1, ti < my_tiles, cross_last);
+        }
+        if (cross_last) {
+#pragma unroll
+            for (int u = 0; u < KC; ++u) pf[u] = wb[u];
+        }
     }
     // Order in this compute unit's memory queue at the end of a phase: the last epilogue's stores,
     // then the other waves' first chunk of the next phase, then (after the acknowledgement) the
     // barrier signal, and only then the rest of the next phase's requests.
     block_sync_lds();                       // the last epilogue's stores have been issued
-    if (!reducer && !next_issued) load_wchunk(pf, next, first_tile(next), 0, wave, lane);
+    if (!reducer && !next_issued) load_wchunk<KC>(pf, next, first_tile(next), 0, wave, lane);
     if (reducer) {
         // this wave's epilogue stores must be out before the block counts its tiles as done; the wave
         // that completes the block's count signals the grid barrier
@@ -472,7 +515,7 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
                 }
             }
         }
-        load_wchunk(pf, next, first_tile(next), 0, wave, lane);
+        load_wchunk<KC>(pf, next, first_tile(next), 0, wave, lane);
     }
     if (BARRIER) block_sync_lds();          // the block's signal (if it was this block's turn) has been issued
     if (BARRIER) {
@@ -502,11 +545,12 @@ __device__ __forceinline__ LayerW layer_weights(MegaArgsK g, int l)
     w.attn_gain = t->attn_gain; w.ffn_gain = t->ffn_gain;
     return w;
 }
+template <int NF>
 __device__ __forceinline__ FastArgs base_args(MegaArgsK g)
 {
     FastArgs a = {};
     a.M = g->M;
-    a.cls = 8;
+    a.cls = packed_class(NF);
     a.inv_d = g->inv_d;
     a.eps = g->eps;
     a.n_ss = g->d / 16;
@@ -529,8 +573,9 @@ __device__ __forceinline__ FastArgs base_args(MegaArgsK g)
 // over ancestors only, acceptance along the paths.  MODE 2 (batch): the window holds several sequences
 // side by side (MegaArgs::seqs): cache, length and position per row, attention per sequence, acceptance
 // inside every sequence.  Separate instantiations, so the chain form keeps its registers.
+// NF, KC: see gemm_phase (NF = 2: windows of 9 to 16 rows; KC = 10: d_model up to 5120).
 enum { MEGA_CHAIN = 0, MEGA_TREE = 1, MEGA_BATCH = 2 };
-template <int DH, int MODE = MEGA_CHAIN>
+template <int DH, int MODE = MEGA_CHAIN, int NF = 1, int KC = kChunk>
 __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* read through phase_args() */)
 {
     constexpr bool TREE = MODE == MEGA_TREE, BATCH = MODE == MEGA_BATCH;
@@ -541,7 +586,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
     const int grid = gridDim.x;
     GridBarrier bar;
     int tiles_before = 0, L, n_layers;
-    uint4 pf[kChunk];
+    uint4 pf[KC];
     {
         MegaArgsK g = phase_args();
         bar_init(bar, g);
@@ -554,10 +599,10 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
         const LayerW w0 = layer_weights(g, 0);
         {   // weights of the first QKV tile go out before anything else
             WSrc first = {w0.qkv, (d + 31) / 32, (d + 2 * g->n_kv_heads * g->head_dim) / 16};
-            load_wchunk(pf, first, first_tile(first), 0, wave, lane);
+            load_wchunk<KC>(pf, first, first_tile(first), 0, wave, lane);
         }
         // ---- embed (+ operand and sums of squares for the first norm)
-        FastArgs a = base_args(g);
+        FastArgs a = base_args<NF>(g);
         a.gain = w0.attn_gain;
         a.xp_next = g->xp_d;
         a.ssp_next = g->ssp_a;
@@ -570,7 +615,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
         {   // QKV (+ norm, RoPE, cache write); then the O tile is put in flight
             MegaArgsK g = phase_args();
             const LayerW w = layer_weights(g, l);
-            FastArgs a = base_args(g);
+            FastArgs a = base_args<NF>(g);
             const int nks_d = (g->d + 31) / 32;
             a.Wp = w.qkv; a.Xp = (const uint4 *)g->xp_d; a.nks = nks_d;
             a.n_tiles = (g->d + 2 * g->n_kv_heads * g->head_dim) / 16;
@@ -581,7 +626,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
                 a.row_seq = (const int32_t *)g->row_seq;
             }
             WSrc none = {w.o, nks_d, 0};   // the O tile is fetched from inside the attention phase
-            gemm_phase<BATCH ? EPI_QKV_BATCH : (TREE ? EPI_QKV_TREE : EPI_QKV), true, false>(a, none, pf, sh, bar, tiles_before);
+            gemm_phase<BATCH ? EPI_QKV_BATCH : (TREE ? EPI_QKV_TREE : EPI_QKV), true, false, NF, KC>(a, none, pf, sh, bar, tiles_before);
         }
         {   // attention: (head, split) tasks - per sequence when the step holds several; the O weights stream
             // in meanwhile.  Cache pages wholly below the committed length do not depend on this step: the
@@ -644,7 +689,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             const WSrc o_src = {w.o, (g->d + 31) / 32, g->d / 16};
             bool fetched = false;
             auto prefetch_o = [&]() {
-                if (!fetched) load_wchunk(pf, o_src, first_tile(o_src), 0, wave, lane);
+                if (!fetched) load_wchunk<KC>(pf, o_src, first_tile(o_src), 0, wave, lane);
                 fetched = true;
             };
             // with the grid a multiple of the head count all tasks of a block belong to one head: they are
@@ -669,7 +714,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
                 AttnBatch bt = {k.row0, k.rows, g->n_att_blocks, (const SeqRef *)g->seqs, (const int32_t *)g->row_seq};
                 attn_task<DH, true, decltype(prefetch_o), BATCH ? ATTN_BATCH : (TREE ? ATTN_TREE : ATTN_CHAIN), decltype(next_page)>(
                     attn_shared<DH>(sh), kv, k.head, k.split, k.L, (const uint4 *)g->qp, k.pool, k.table, M, l, n_layers, n_heads,
-                    g->n_kv_heads, g->max_splits, g->scale, g->part, g->head_counter, g->xp_att, 8, prefetch_o,
+                    g->n_kv_heads, g->max_splits, g->scale, g->part, g->head_counter, g->xp_att, packed_class(NF), prefetch_o,
                     TREE ? (const uint32_t *)g->mask : nullptr, BATCH ? &bt : nullptr, next_page, publish);
                 block_sync_lds();
             }
@@ -679,42 +724,42 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
         {   // O (+ residual, operand and sums for the FFN norm)
             MegaArgsK g = phase_args();
             const LayerW w = layer_weights(g, l);
-            FastArgs a = base_args(g);
+            FastArgs a = base_args<NF>(g);
             const int nks_d = (g->d + 31) / 32;
             a.Wp = w.o; a.Xp = (const uint4 *)g->xp_att; a.nks = nks_d; a.n_tiles = g->d / 16;
             a.gain = w.ffn_gain; a.xp_next = g->xp_d; a.ssp_next = g->ssp_b;
             WSrc next = {w.gu, nks_d, g->F / 8};
-            gemm_phase<EPI_RESIDUAL, true>(a, next, pf, sh, bar, tiles_before);
+            gemm_phase<EPI_RESIDUAL, true, true, NF, KC>(a, next, pf, sh, bar, tiles_before);
         }
         {   // gate / up (+ norm, SwiGLU)
             MegaArgsK g = phase_args();
             const LayerW w = layer_weights(g, l);
-            FastArgs a = base_args(g);
+            FastArgs a = base_args<NF>(g);
             a.Wp = w.gu; a.Xp = (const uint4 *)g->xp_d; a.nks = (g->d + 31) / 32; a.n_tiles = g->F / 8;
             a.ssp = g->ssp_b;
             WSrc next = {w.down, (g->F + 31) / 32, g->d / 16};
-            gemm_phase<EPI_GATE_UP, true>(a, next, pf, sh, bar, tiles_before);
+            gemm_phase<EPI_GATE_UP, true, true, NF, KC>(a, next, pf, sh, bar, tiles_before);
         }
         {   // down (+ residual, operand and sums for the next norm)
             MegaArgsK g = phase_args();
             const LayerW w = layer_weights(g, l);
-            FastArgs a = base_args(g);
+            FastArgs a = base_args<NF>(g);
             a.Wp = w.down; a.Xp = (const uint4 *)g->xp_f; a.nks = (g->F + 31) / 32; a.n_tiles = g->d / 16;
             const bool more = l + 1 < n_layers;
             a.gain = more ? layer_weights(g, l + 1).attn_gain : g->final_gain;
             a.xp_next = g->xp_d; a.ssp_next = g->ssp_a;
             WSrc next = {more ? layer_weights(g, l + 1).qkv : g->wp_lm, (g->d + 31) / 32, more ? (g->d + 2 * g->n_kv_heads * g->head_dim) / 16 : g->V / 16};
-            gemm_phase<EPI_RESIDUAL, false>(a, next, pf, sh, bar, tiles_before);
+            gemm_phase<EPI_RESIDUAL, false, true, NF, KC>(a, next, pf, sh, bar, tiles_before);
         }
     }
     {   // LM head (+ final norm) with per-tile argmax
         MegaArgsK g = phase_args();
-        FastArgs a = base_args(g);
+        FastArgs a = base_args<NF>(g);
         const int nks_d = (g->d + 31) / 32;
         a.Wp = g->wp_lm; a.Xp = (const uint4 *)g->xp_d; a.nks = nks_d; a.n_tiles = g->V / 16;
         a.ssp = g->ssp_a; a.Y = g->logits; a.ldy = g->V; a.amax = g->amax;
         WSrc none = {g->wp_lm, nks_d, 0};
-        gemm_phase<EPI_LM_ARGMAX, true>(a, none, pf, sh, bar, tiles_before);
+        gemm_phase<EPI_LM_ARGMAX, true, true, NF, KC>(a, none, pf, sh, bar, tiles_before);
     }
     MegaArgsK g = phase_args();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
