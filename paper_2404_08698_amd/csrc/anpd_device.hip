@@ -38,6 +38,7 @@ struct Layout {  // byte offsets into the model workspace
     size_t rope_tab, tok, tree, batch, result, counter, x, h, y, qkv, att, gu, a, logits, part;
     // fast path: packed operands, partial sums of squares, packed weights
     size_t xp_d, xp_att, xp_f, ssp_a, ssp_b, qp, head_ctr, layer_tab, amax, row_ctr, bar, wp_lm, total;
+    size_t xp_layers, xp_stride;   // the one-kernel step's operands, a set per layer (bytes; stride in bf16 elements)
     std::vector<size_t> wp_qkv, wp_o, wp_gu, wp_down;
     int max_splits;
 };
@@ -101,10 +102,13 @@ Layout make_layout(const anpd_model_cfg *c)
     L.part = take((size_t)c->n_heads * L.max_splits * (wants_mfma(c) ? 32 : MW) * (c->head_dim + 2) * 4);
     L.xp_d = L.xp_att = L.xp_f = L.ssp_a = L.ssp_b = L.qp = L.head_ctr = L.wp_lm = 0;
     L.layer_tab = L.amax = L.row_ctr = L.bar = 0;
+    L.xp_layers = L.xp_stride = 0;
     if (wants_mfma(c)) {
         L.xp_d = take(((d + 31) / 32) * 4 * 1024);
         L.xp_att = take(((d + 31) / 32) * 4 * 1024);
         L.xp_f = take(((F + 31) / 32) * 4 * 1024);
+        L.xp_stride = 3 * x_operand_elems((int)d) + x_operand_elems((int)F);
+        L.xp_layers = take(((size_t)c->n_layers * L.xp_stride + x_operand_elems((int)d)) * sizeof(bf16_t));
         L.ssp_a = take((d / 16) * 32 * 4);
         L.ssp_b = take((d / 16) * 32 * 4);
         L.qp = take((size_t)c->n_heads * 4 * (c->head_dim / 32) * 1024);
@@ -159,6 +163,7 @@ struct anpd_model {
     bool mega;            // the one-kernel step is available
     bool mega_tree;       // ... and so is its draft-tree form
     bool mega_batch;      // ... and its several-sequences form
+    bool mega_rows16;     // ... and its form for windows of 9 to 16 rows
     int mega_kc;          // k-steps per wave per work item of the one-kernel step (8: d_model <= 4096, 10: <= 5120)
     long long *trace;     // optional device buffer for barrier timestamps
     int mega_grid;
@@ -641,7 +646,8 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, 
     g.M = M; g.mode = mode;
     g.inv_d = 1.0f / (float)c.d_model; g.eps = c.rms_eps; g.scale = 1.0f / sqrtf((float)c.head_dim);
     g.x = (float *)(ws + L.x);
-    g.xp_d = (bf16_t *)(ws + L.xp_d); g.xp_att = (bf16_t *)(ws + L.xp_att); g.xp_f = (bf16_t *)(ws + L.xp_f);
+    g.xp_layers = (bf16_t *)(ws + L.xp_layers);
+    g.xp_stride = L.xp_stride;
     g.qp = (bf16_t *)(ws + L.qp);
     g.ssp_a = (float *)(ws + L.ssp_a); g.ssp_b = (float *)(ws + L.ssp_b); g.part = (float *)(ws + L.part);
     g.head_counter = (uint32_t *)(ws + L.head_ctr);
@@ -650,7 +656,7 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, 
     g.max_splits = L.max_splits;
     g.logits = want_logits ? (float *)(ws + L.logits) : nullptr;
     g.amax = (unsigned long long *)(ws + L.amax);
-    for (int i = 0; i < 8; ++i) g.tok[i] = i < M ? window[i] : 0;
+    for (int i = 0; i < 16; ++i) g.tok[i] = i < M ? window[i] : 0;
     g.result = (int32_t *)(ws + L.result);
     g.host_result = m->pin_dev + 32;
     g.row_counter = (uint32_t *)(ws + L.row_ctr);
@@ -690,7 +696,9 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, 
     const void *fn64[] = {(const void *)verify_mega_kernel<64, MEGA_CHAIN>, (const void *)verify_mega_kernel<64, MEGA_TREE>,
                           (const void *)verify_mega_kernel<64, MEGA_BATCH>};
     const void *fn = c.head_dim == 128 ? fn128[form] : fn64[form];
-    if (m->mega_kc == 10)   // d_model above 4096 (chains only)
+    if (M > 8)   // windows of 9 to 16 rows (chains only; the caller has checked mega_rows16)
+        fn = c.head_dim == 128 ? (const void *)verify_mega_kernel<128, MEGA_CHAIN, 2> : (const void *)verify_mega_kernel<64, MEGA_CHAIN, 2>;
+    else if (m->mega_kc == 10)   // d_model above 4096 (chains only)
         fn = c.head_dim == 128 ? (const void *)verify_mega_kernel<128, MEGA_CHAIN, 1, 10> : (const void *)verify_mega_kernel<64, MEGA_CHAIN, 1, 10>;
     if (m->plain_launch) {
         // profiling aid (see anpd_model_create): an ordinary launch of the same grid
@@ -979,6 +987,7 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
         const char *pl = std::getenv("ANPD_MEGA_PLAIN_LAUNCH");
         m->plain_launch = pl && pl[0] == '1';
     }
+    m->mega_rows16 = false;
     m->mega_kc = (cfg->d_model + 31) / 32 <= 2 * kChunk * kFastWaves ? kChunk : 10;
     if (e == hipSuccess && m->mfma && cfg->gemm_path != ANPD_GEMM_MFMA_LAUNCHES && (cfg->d_model + 31) / 32 <= 2 * 10 * kFastWaves) {
         // the persistent step needs every block resident at once: one block per compute unit
@@ -1016,6 +1025,12 @@ int32_t anpd_model_create(const anpd_model_cfg *cfg, const anpd_weights *w, void
                      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_b, verify_mega_kernel<128, MEGA_BATCH>, kFastThreads, 0)
                      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_b, verify_mega_kernel<64, MEGA_BATCH>, kFastThreads, 0);
             m->mega_batch = te == hipSuccess && per_cu_b >= 1 && m->mega_kc == kChunk;
+            if (te != hipSuccess) (void)hipGetLastError();
+            int per_cu_r = 0;
+            te = cfg->head_dim == 128
+                     ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_r, verify_mega_kernel<128, MEGA_CHAIN, 2>, kFastThreads, 0)
+                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_r, verify_mega_kernel<64, MEGA_CHAIN, 2>, kFastThreads, 0);
+            m->mega_rows16 = te == hipSuccess && per_cu_r >= 1 && m->mega_kc == kChunk;
             if (te != hipSuccess) (void)hipGetLastError();
 
         } else {
@@ -1245,7 +1260,7 @@ int32_t anpd_verify(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, int32
     if (rc != ANPD_OK) return rc;
     // The persistent kernel takes the window by value and writes its result and error flag into the
     // pinned buffer itself; the other paths go through copies.
-    const bool one_kernel = m->mega && n_window <= 8;
+    const bool one_kernel = m->mega && (n_window <= 8 || (n_window <= 16 && m->mega_rows16));
     int32_t *res = m->pin + 32;
     if (one_kernel) {
         rc = run_step_mega(m, kv, window, n_window, mode, out_logits != nullptr, st);

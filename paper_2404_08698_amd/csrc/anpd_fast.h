@@ -219,29 +219,39 @@ __device__ __forceinline__ void compute_rinv(const FastArgs &a, float *rinv /* L
     block_sync_lds();
 }
 
-// compute_rinv in three steps for window class 8 and at most 256 tiles of partial sums, so that the
+// compute_rinv in three steps for windows of 8 NF rows and at most 256 tiles of partial sums, so that the
 // persistent kernel can request the sums when a phase starts and reduce them when the first
 // epilogue needs them, after the first tile's MFMAs.  Same additions in the same order.
-template <bool COH>
-__device__ __forceinline__ void rinv_issue(const FastArgs &a, float (&v)[4], int tid)
+// A thread takes row tid % (8 NF) of group tid / (8 NF) and of the NF - 1 groups a pass further on.
+template <bool COH, int NF = 1>
+__device__ __forceinline__ void rinv_issue(const FastArgs &a, float (&v)[NF][4], int tid)
 {
-    const int m = tid & 7, g = tid >> 3;
+    constexpr int R = 8 * NF, GP = kFastThreads / R;
+    const int m = tid % R, g0 = tid / R;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int t = g + 64 * u;
-        v[u] = (m < a.M && t < a.n_ss) ? ldf_at<COH>(a.ssp, (uint32_t)(t * 32 + m)) : 0.f;
+    for (int p = 0; p < NF; ++p)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int t = g0 + p * GP + 64 * u;
+            v[p][u] = (m < a.M && t < a.n_ss) ? ldf_at<COH>(a.ssp, (uint32_t)(t * 32 + m)) : 0.f;
+        }
+}
+template <int NF = 1>
+__device__ __forceinline__ void rinv_partial_to_lds(const float (&v)[NF][4], float *scratch /* LDS [2048] */, int tid)
+{
+    constexpr int R = 8 * NF, GP = kFastThreads / R;
+#pragma unroll
+    for (int p = 0; p < NF; ++p) {
+        float s = 0.f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s += v[p][u];
+        scratch[(tid / R + p * GP) * 32 + tid % R] = s;
     }
 }
-__device__ __forceinline__ void rinv_partial_to_lds(const float (&v)[4], float *scratch /* LDS [2048] */, int tid)
-{
-    float s = 0.f;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) s += v[u];
-    scratch[(tid >> 3) * 32 + (tid & 7)] = s;
-}
+template <int NF = 1>
 __device__ __forceinline__ void rinv_from_lds(const FastArgs &a, float *rinv, const float *scratch, int tid)
 {
-    if (tid < 8) {
+    if (tid < 8 * NF) {
         float tot = 0.f;
 #pragma unroll 8
         for (int g = 0; g < 64; ++g) tot += scratch[g * 32 + tid];
@@ -258,11 +268,12 @@ struct EpiPre {
     int page;         // QKV: physical page of the row's position
 };
 
+// frag: which 8 rows of the window (rows 8 frag .. 8 frag + 7 sit in lanes with lane % 16 < 8)
 template <int EPI>
-__device__ __forceinline__ void epilogue_preload(const FastArgs &a, int tile, int lane, EpiPre &pre)
+__device__ __forceinline__ void epilogue_preload(const FastArgs &a, int tile, int lane, EpiPre &pre, int frag = 0)
 {
-    const int m = lane & 15, kg = lane >> 4;
-    const bool valid = m < 8 && m < a.M;
+    const int m = 8 * frag + (lane & 7), kg = lane >> 4;
+    const bool valid = (lane & 15) < 8 && m < a.M;
     if (EPI == EPI_RESIDUAL) {
         const int n = tile * 16 + 4 * kg;
         pre.x = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -452,10 +463,10 @@ __device__ __forceinline__ void reduce_and_finish(const FastArgs &a, int tile, c
 
 // The same for an operand of NF fragments in the class-8 arrangement (packed_class): fragment f holds rows
 // 8 f .. 8 f + 7 as (hi | lo) slots, and its partial tiles are finished exactly like the one fragment of a
-// window of up to 8 rows.  red: [nw][NF][256].  `pre` (staged operands of rows 0..7) serves fragment 0.
+// window of up to 8 rows.  red: [nw][NF][256].  pre: the staged operands of every fragment, if any.
 template <int NF, int EPI, bool COH = false>
 __device__ __forceinline__ void reduce_and_finish_packed(const FastArgs &a, int tile, const float *red, int nw, int lane,
-                                                         const float *rinv, const EpiPre *pre = nullptr)
+                                                         const float *rinv, const EpiPre *pre /* [NF] or null */ = nullptr)
 {
     const int slot = lane & 15, kg = lane >> 4;
 #pragma unroll
@@ -466,7 +477,7 @@ __device__ __forceinline__ void reduce_and_finish_packed(const FastArgs &a, int 
 #pragma unroll
         for (int i = 0; i < 4; ++i) lo[i] = row_down8(tot[i]);
         const int m = 8 * f + (slot & 7);
-        epilogue<EPI, COH>(a, tile, m, kg, tot + lo, slot < 8 && m < a.M, rinv, f == 0 ? pre : nullptr);
+        epilogue<EPI, COH>(a, tile, m, kg, tot + lo, slot < 8 && m < a.M, rinv, pre ? pre + f : nullptr);
     }
 }
 

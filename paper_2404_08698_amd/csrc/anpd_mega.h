@@ -38,7 +38,13 @@ struct MegaArgs {
     int d, F, V, n_heads, n_kv_heads, head_dim, M, mode;
     float inv_d, eps, scale;
     float *x;
-    bf16_t *xp_d, *xp_att, *xp_f, *qp;
+    // Activation operands, one set per layer so that no address is written twice in a launch (see x_operand):
+    // xp_layers + l * xp_stride holds, in this order, the QKV operand of layer l, the attention output, the
+    // gate / up operand (d_model columns each) and the down projection's operand (d_ffn columns); the set after
+    // the last layer holds the LM head's operand.  Sized for kMaxFrags fragments per k-step.
+    bf16_t *xp_layers;
+    size_t xp_stride;       // bf16 elements per layer
+    bf16_t *qp;
     float *ssp_a, *ssp_b, *part;
     uint32_t *head_counter;
     bf16_t *pool;
@@ -48,7 +54,7 @@ struct MegaArgs {
     int max_splits;
     float *logits;          // nullable: all logits [M][V]
     unsigned long long *amax;  // [V / 16][32] per-tile (value bits << 32 | index) of the best logit
-    int32_t tok[8];         // the window's tokens, by value (no upload before the launch)
+    int32_t tok[16];        // the window's tokens, by value (no upload before the launch)
     int32_t *result;        // device: [0] accepted, [1] next, [2 + r] prediction of row r
     int32_t *host_result;   // pinned host memory, same layout: written at the end, read by the host after the launch
     uint32_t *row_counter;  // argmax phase hand-off
@@ -74,6 +80,16 @@ struct MegaArgs {
 };
 
 constexpr int kTraceEvents = 1024;
+
+// Cache policy of the activation-operand loads: plain (through the XCD's L2, see x_operand).
+#ifndef ANPD_MEGA_X_COHERENT
+constexpr int kAuxOperand = 0;
+#else
+constexpr int kAuxOperand = kAuxCoherent;
+#endif
+#ifndef ANPD_MEGA_STREAM_LDS
+#define ANPD_MEGA_STREAM_LDS false
+#endif
 
 constexpr int kBarStride = 256;  // uint32 words between barrier counters (1 KiB: separate channels)
 // embed, then attention / O / gate-up / down of every layer, then the LM head (the QKV phase hands over
@@ -233,7 +249,7 @@ __device__ __forceinline__ void load_xchunk(uint4 (&x)[NF][KC], const uint4 *Xp,
     for (int u = 0; u < KC; ++u)
 #pragma unroll
         for (int f = 0; f < NF; ++f) {
-            u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, ((KC * c + u) * kFastWaves * NF + f) * 1024, kAuxCoherent);
+            u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, ((KC * c + u) * kFastWaves * NF + f) * 1024, kAuxOperand);
             x[f][u] = make_uint4(v.x, v.y, v.z, v.w);
         }
 }
@@ -243,56 +259,104 @@ __device__ __forceinline__ void load_xchunk(uint4 (&x)[NF][KC], const uint4 *Xp,
 // residual rows this same block wrote), so they are requested before the phase barrier and are
 // there when the epilogue runs: a load issued at the epilogue would queue behind the weight
 // loads in flight, and the gain vector comes from HBM.
-constexpr int kPreTiles = 3;
+// (the residual epilogue and the QKV epilogues need different operands and never run in the same phase)
+constexpr int pre_tiles(int nf) { return nf == 1 ? 3 : 1;}   // tiles per block whose epilogue operands are staged
 constexpr int kMaxFrags = 2;   // activation fragments per k-step the one-kernel step is built for (windows of up to 16 rows)
 struct EpiPreLds {
-    f32x4 x[64], g[64];
-    float2 cs[4][64];
-    int page[64];
+    union {
+        struct { f32x4 x[64], g[64]; } res;
+        struct { float2 cs[4][64]; int page[64]; } qkv;
+    };
 };
 template <int EPI>
 __device__ __forceinline__ void pre_to_lds(EpiPreLds &d, const EpiPre &p, int lane)
 {
     if (EPI == EPI_RESIDUAL) {
-        d.x[lane] = p.x;
-        d.g[lane] = p.g;
+        d.res.x[lane] = p.x;
+        d.res.g[lane] = p.g;
     } else if (epi_is_qkv(EPI)) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) d.cs[i][lane] = p.cs[i];
-        d.page[lane] = p.page;
+        for (int i = 0; i < 4; ++i) d.qkv.cs[i][lane] = p.cs[i];
+        d.qkv.page[lane] = p.page;
     }
 }
 template <int EPI>
 __device__ __forceinline__ void pre_from_lds(EpiPre &p, const EpiPreLds &d, int lane)
 {
     if (EPI == EPI_RESIDUAL) {
-        p.x = d.x[lane];
-        p.g = d.g[lane];
+        p.x = d.res.x[lane];
+        p.g = d.res.g[lane];
     } else if (epi_is_qkv(EPI)) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) p.cs[i] = d.cs[i][lane];
-        p.page = d.page[lane];
+        for (int i = 0; i < 4; ++i) p.cs[i] = d.qkv.cs[i][lane];
+        p.page = d.qkv.page[lane];
     }
 }
 
+// NF: operand fragments per k-step (see gemm_phase).  With NF > 1 the partial tiles have one buffer instead of
+// two and the epilogue operands of one tile instead of three are staged, which leaves room for the second
+// chunk of the resident operand (x1: per wave its KC k-steps x NF fragments).
+template <int NF>
 struct MegaShared {
+    static constexpr int kRedBufs = NF == 1 ? 2 : 1;
     union {
-        float red[2][kFastWaves][kMaxFrags][256];
+        float red[kRedBufs][kFastWaves][NF][256];
         AttnShared<128> attn128;
         AttnShared<64> attn64;
     };
     float rinv[32];
     int tiles_done;   // epilogues finished by this block since the kernel started
-    EpiPreLds pre[kPreTiles];
+    EpiPreLds pre[pre_tiles(NF)][NF];
     float rscratch[2048];   // group sums of the RMSNorm partials (see rinv_partial_to_lds)
+    uint4 x1[NF == 1 ? 1 : kFastWaves * NF * kChunk * 64];
 };
 
-template <int DH>
-__device__ __forceinline__ AttnShared<DH> &attn_shared(MegaShared &sh);
-template <>
-__device__ __forceinline__ AttnShared<128> &attn_shared<128>(MegaShared &sh) { return sh.attn128; }
-template <>
-__device__ __forceinline__ AttnShared<64> &attn_shared<64>(MegaShared &sh) { return sh.attn64; }
+template <int DH, int NF>
+__device__ __forceinline__ AttnShared<DH> &attn_shared(MegaShared<NF> &sh)
+{
+    if constexpr (DH == 128) return sh.attn128;
+    else return sh.attn64;
+}
+
+// One fragment (16 bytes per lane) from LDS, as assembly: the compiler does not see the read, so it does not
+// make it wait for loads in flight that write LDS.  The caller waits (lds_wait) before it uses the value.
+template <int OFF>
+__device__ __forceinline__ u32x4_t lds_frag(uint32_t addr)
+{
+    u32x4_t v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+    return v;
+}
+// fragment number i (compile-time after unrolling) of a wave's chunk in LDS
+__device__ __forceinline__ u32x4_t lds_frag_at(uint32_t addr, int i)
+{
+    u32x4_t v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "i"(i * 1024) : "memory");
+    return v;
+}
+// Waits until at most PENDING of this wave's LDS reads are outstanding; the fragments are operands so that
+// nothing that uses them is moved in front of the wait.
+template <int PENDING, int NF>
+__device__ __forceinline__ void lds_wait(u32x4_t (&t)[NF])
+{
+    static_assert(NF <= 2, "operand list written for at most two fragments");
+    if constexpr (NF == 1) asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(t[0]) : "n"(PENDING));
+    else asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(t[0]), "+v"(t[1]) : "n"(PENDING));
+}
+// A chunk of the activation operand straight into LDS (no registers while in flight): fragment (u, f) of this
+// wave goes to dst[(u * NF + f) * 64 + lane].
+template <int NF, int KC>
+__device__ __forceinline__ void dma_xchunk(uint4 *dst, const uint4 *Xp, int nks, int c, int wave, int lane, bool have = true)
+{
+    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(Xp), 0, have ? nks * NF * 1024 : 0, 0x00020000);
+    const int voff = (wave * NF * 64 + lane) * 16;
+#pragma unroll
+    for (int u = 0; u < KC; ++u)
+#pragma unroll
+        for (int f = 0; f < NF; ++f)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void *)(dst + (u * NF + f) * 64), 16, voff,
+                                                     ((KC * c + u) * kFastWaves * NF + f) * 1024, 0, kAuxOperand);
+}
 
 // One GEMM phase.  On entry pf holds (or has in flight) the weights of this block's first work
 // item, loaded by the previous phase; on exit those of the next phase's first item are in flight
@@ -304,16 +368,28 @@ __device__ __forceinline__ AttnShared<64> &attn_shared<64>(MegaShared &sh) { ret
 // another, so a barrier that is not waited for must not be signalled either.
 // NF: fragments of the activation operand per k-step, each holding 8 window rows as (hi | lo) slots like
 // the one fragment of a window of up to 8 rows, so rows 8 f .. 8 f + 7 go through exactly the arithmetic
-// of that window.  Only NF = 1 is instantiated: with NF = 2 (9 to 16 rows) the resident operand takes 128
-// registers, the kernel spills 70 to 160 registers per lane around the epilogues and the step is slower
-// than one launch per operation (7B shape, 9 rows: 4.33 against 3.39 ms).
+// of that window.  NF = 2 (9 to 16 rows) doubles the operand; with both of its chunks and a ring of weight
+// items in registers the kernel spilled 70 to 160 registers per lane around the epilogues, and a reload from
+// scratch memory queues behind the weights in flight (7B shape, 9 rows: 4.33 ms against 3.39 ms as separate
+// launches).  So the second of the two operand buffers lives in LDS: requested straight into LDS (no
+// registers while in flight) and read fragment by fragment next to the MFMAs that use it.  In a stationary
+// phase that is chunk 1 of the operand; in a streaming phase (down projection) the chunks of the odd steps.
 // KC: k-steps per wave per item; 2 KC * 8 k-steps must cover d_model for the stationary phases (8 up to
 // d_model 4096, 10 up to 5120).
 template <int EPI, bool STATIONARY, bool BARRIER = true, int NF = 1, int KC = kChunk>
-__device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, uint4 (&pf)[KC], MegaShared &sh,
+__device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, uint4 (&pf)[KC], MegaShared<NF> &sh,
                                            GridBarrier &bar, int &tiles_before)
 {
-    constexpr int RING = NF * KC <= 8 ? 3 : 2;   // weight items in flight per wave (registers: NF * 2 KC operand fragments stay resident)
+    // weight items in flight per wave, and how many steps ahead a streamed operand chunk is requested
+    // kStreamLds: a streaming phase with NF > 1 passes the chunks of its odd steps through LDS and keeps a ring
+    // of three.  Otherwise it has a ring of two and ONE operand buffer in registers, refilled for the next step
+    // as soon as a step's MFMAs have read it (with two items in flight the operand of step s + 1 may be
+    // requested behind the weights of step s + 1 without holding anything back: a wave's loads return in order).
+    constexpr bool kStreamLds = ANPD_MEGA_STREAM_LDS;
+    constexpr int RING = NF == 1 ? (KC <= 8 ? 3 : 2) : ((STATIONARY || kStreamLds) ? 3 : 2);
+    constexpr int XLOOK = (NF > 1 && !STATIONARY && !kStreamLds) ? 1 : 2;
+    constexpr bool kX1Lds = NF > 1 && (STATIONARY || kStreamLds);   // the second operand buffer (x1) lives in LDS
+    static_assert(NF == 1 || KC == kChunk, "the LDS copy of the operand is sized for items of kChunk k-steps");
     const int tid = fresh_tid();
     const int lane = tid & 63, wave = tid >> 6;
     const WSrc cur = {a.Wp, a.nks, a.n_tiles};
@@ -344,11 +420,14 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
             load_wchunk<KC>(dst, cur, li < my_tiles ? tile_at(li) : cur.n_tiles, lc, wave, lane);
         }
     };
-    // (the staged epilogue operands are laid out for the one-fragment window)
-    constexpr bool kHasPre = (EPI == EPI_RESIDUAL || epi_is_qkv(EPI)) && NF == 1;
+    constexpr bool kHasPre = (EPI == EPI_RESIDUAL || epi_is_qkv(EPI));
+    constexpr int kPreTiles = pre_tiles(NF);
     const bool stages = kHasPre && wave < kPreTiles && wave < my_tiles;   // this wave finishes tile number `wave`
-    EpiPre pre0;
-    if (stages) epilogue_preload<EPI>(a, tile_at(wave), lane, pre0);
+    EpiPre pre0[NF];
+    if (stages) {
+#pragma unroll
+        for (int f = 0; f < NF; ++f) epilogue_preload<EPI>(a, tile_at(wave), lane, pre0[f], f);
+    }
     if constexpr (RING == 3) {
         fetch(wb, false);
         fetch(wc, true);
@@ -358,7 +437,10 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     // at most RING - 1 items: the last buffer of the ring holds the next phase's first item (the same for
     // a whole wave: told to the compiler, or it takes everything a step does under this flag for lane-dependent)
     const bool cross_last = __builtin_amdgcn_readfirstlane((int)next_issued) != 0;
-    if (stages) pre_to_lds<EPI>(sh.pre[wave], pre0, lane);
+    if (stages) {
+#pragma unroll
+        for (int f = 0; f < NF; ++f) pre_to_lds<EPI>(sh.pre[wave][f], pre0[f], lane);
+    }
 
     bar_wait(bar);
     if (BARRIER && my_tiles == 0 && tid == 0) bar_signal(bar);
@@ -367,14 +449,19 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     // BEFORE the weights requested at the end of the step, so that no step's operand waits behind
     // weights of later steps (a wave's loads return in order).
     const int n_steps = my_tiles * n_chunks;
+    uint4 *const x1_lds = sh.x1 + (kX1Lds ? wave * NF * KC * 64 : 0);
+    // (chunk 1 is requested first: once chunk 0 has arrived in registers - the loop below is entered with
+    // it - chunk 1 is in LDS as well, because a wave's loads complete in order)
+    if (kX1Lds) dma_xchunk<NF, KC>(x1_lds, a.Xp, a.nks, STATIONARY ? 1 : 1 % n_chunks, wave, lane, STATIONARY || 1 < n_steps);
     load_xchunk<NF, KC>(x0, a.Xp, a.nks, 0, wave, lane);
-    if (STATIONARY || 1 < n_steps) load_xchunk<NF, KC>(x1, a.Xp, a.nks, STATIONARY ? 1 : 1 % n_chunks, wave, lane);
+    if (!kX1Lds && XLOOK == 2 && (STATIONARY || 1 < n_steps))
+        load_xchunk<NF, KC>(x1, a.Xp, a.nks, STATIONARY ? 1 : 1 % n_chunks, wave, lane);
     // the RMSNorm scale is needed by the first epilogue only: its partial sums are requested here and
     // reduced after the first tile's MFMAs, off the path from the barrier to the first MFMA
     constexpr bool kNorm = (epi_has_norm(EPI) || EPI == EPI_LM_ARGMAX);
-    const bool late_norm = NF == 1 && kNorm && a.n_ss <= 256 && my_tiles > 0;
-    float nv[4];
-    if (late_norm) rinv_issue<true>(a, nv, tid);
+    const bool late_norm = kNorm && a.n_ss <= 256 && my_tiles > 0;
+    float nv[NF][4];
+    if (late_norm) rinv_issue<true, NF>(a, nv, tid);
     else if (kNorm) compute_rinv<true>(a, sh.rinv, sh.rscratch);
 
     f32x4 acc[NF];
@@ -391,34 +478,64 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     // have run out): with several exits, or requests made on some paths only, the compiler must assume
     // that the buffer a step waits for was requested last, and makes every step wait for all loads.
     // keep: buf holds the next phase's first item and is not refilled.
-    auto do_step = [&](uint4 (&buf)[KC], uint4 (&xs)[NF][KC], bool active, bool keep) __attribute__((always_inline)) {
+    // the MFMAs of one item against an operand chunk in registers / in this wave's LDS buffer (fragments read
+    // one k-step ahead of the MFMAs that use them)
+    auto mfma_reg = [&](uint4 (&buf)[KC], uint4 (&xr)[NF][KC]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < KC; ++u)
+#pragma unroll
+            for (int f = 0; f < NF; ++f)
+                acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, buf[u]),
+                                                                 __builtin_bit_cast(bf16x8, xr[f][u]), acc[f], 0, 0, 0);
+    };
+    auto mfma_lds = [&](uint4 (&buf)[KC]) __attribute__((always_inline)) {
+        const uint32_t xa = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)x1_lds + (uint32_t)lane * 16;
+        u32x4_t t[2][NF];
+#pragma unroll
+        for (int f = 0; f < NF; ++f) t[0][f] = lds_frag_at(xa, f);
+#pragma unroll
+        for (int u = 0; u < KC; ++u) {
+            if (u + 1 < KC) {
+#pragma unroll
+                for (int f = 0; f < NF; ++f) t[(u + 1) & 1][f] = lds_frag_at(xa, (u + 1) * NF + f);
+                lds_wait<NF>(t[u & 1]);
+            } else {
+                lds_wait<0>(t[u & 1]);
+            }
+#pragma unroll
+            for (int f = 0; f < NF; ++f)
+                acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, buf[u]),
+                                                                 __builtin_bit_cast(bf16x8, t[u & 1][f]), acc[f], 0, 0, 0);
+        }
+    };
+    // from_lds (streaming phases with kX1Lds): this step's operand chunk is the one in LDS
+    auto do_step = [&](uint4 (&buf)[KC], uint4 (&xs)[NF][KC], bool active, bool keep, bool from_lds = false) __attribute__((always_inline)) {
         if (active) {
             if (STATIONARY) {
                 if (c == 1) {
-#pragma unroll
-                    for (int u = 0; u < KC; ++u)
-#pragma unroll
-                        for (int f = 0; f < NF; ++f)
-                            acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, buf[u]),
-                                                                             __builtin_bit_cast(bf16x8, x1[f][u]), acc[f], 0, 0, 0);
+                    if constexpr (kX1Lds) mfma_lds(buf);
+                    else mfma_reg(buf, x1);
                 } else {
-#pragma unroll
-                    for (int u = 0; u < KC; ++u)
-#pragma unroll
-                        for (int f = 0; f < NF; ++f)
-                            acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, buf[u]),
-                                                                             __builtin_bit_cast(bf16x8, x0[f][u]), acc[f], 0, 0, 0);
+                    mfma_reg(buf, x0);
                 }
+            } else if (kX1Lds && from_lds) {
+                // The chunk was requested into LDS two steps ago (or on entry), and since then this wave has
+                // issued the weights of one item, the operand chunk of the step in between and the weights of
+                // another item - NF * KC + 2 * KC loads, every one of them on every path.  A wave's loads complete
+                // in order, so once at most that many are outstanding the chunk is in LDS.  (The reads below are
+                // assembly the compiler does not connect with that request.)
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NF * KC + 2 * KC) : "memory");
+                mfma_lds(buf);
             } else {
-#pragma unroll
-                for (int u = 0; u < KC; ++u)
-#pragma unroll
-                    for (int f = 0; f < NF; ++f)
-                        acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, buf[u]),
-                                                                         __builtin_bit_cast(bf16x8, xs[f][u]), acc[f], 0, 0, 0);
+                mfma_reg(buf, xs);
             }
         }
-        if (!STATIONARY) load_xchunk<NF, KC>(xs, a.Xp, a.nks, (step + 2) % n_chunks, wave, lane, active && step + 2 < n_steps);
+        if (!STATIONARY) {
+            if (kX1Lds && from_lds)
+                dma_xchunk<NF, KC>(x1_lds, a.Xp, a.nks, (step + XLOOK) % n_chunks, wave, lane, active && step + XLOOK < n_steps);
+            else
+                load_xchunk<NF, KC>(xs, a.Xp, a.nks, (step + XLOOK) % n_chunks, wave, lane, active && step + XLOOK < n_steps);
+        }
         if (!keep) fetch(buf, false);
         if (active) {
             ++step;
@@ -426,24 +543,29 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
             const int finished = tile_at(ti);
             if (++c == n_chunks) { c = 0; ++ti; }
             if (tile_done) {
-                float *r = &sh.red[it & 1][0][0][0];
+                float *r = &sh.red[MegaShared<NF>::kRedBufs == 2 ? (it & 1) : 0][0][0][0];
+                if (MegaShared<NF>::kRedBufs == 1) block_sync_lds();   // the previous tile's partial sums have been read
 #pragma unroll
                 for (int f = 0; f < NF; ++f)
                     *reinterpret_cast<f32x4 *>(r + (((size_t)wave * NF + f) * 64 + lane) * 4) = acc[f];
-                if (late_norm && it == 0) rinv_partial_to_lds(nv, sh.rscratch, tid);
+                if (late_norm && it == 0) rinv_partial_to_lds<NF>(nv, sh.rscratch, tid);
                 block_sync_lds();
-                if (late_norm && it == 0) rinv_from_lds(a, sh.rinv, sh.rscratch, tid);   // wave 0, which also finishes tile 0
+                if (late_norm && it == 0) rinv_from_lds<NF>(a, sh.rinv, sh.rscratch, tid);   // wave 0, which also finishes tile 0
                 if (wave == (it & (kFastWaves - 1))) {
                     if (kHasPre && it < kPreTiles) {
-                        EpiPre pre;
-                        pre_from_lds<EPI>(pre, sh.pre[it], lane);
-                        reduce_and_finish_packed<NF, EPI, true>(a, finished, r, kFastWaves, lane, sh.rinv, &pre);
+                        EpiPre pre[NF];
+#pragma unroll
+                        for (int f = 0; f < NF; ++f) pre_from_lds<EPI>(pre[f], sh.pre[it][f], lane);
+                        reduce_and_finish_packed<NF, EPI, true>(a, finished, r, kFastWaves, lane, sh.rinv, pre);
                     } else {
                         reduce_and_finish_packed<NF, EPI, true>(a, finished, r, kFastWaves, lane, sh.rinv);
                     }
                 }
 #pragma unroll
                 for (int f = 0; f < NF; ++f) acc[f] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#ifdef ANPD_TRACE_FINE
+                if (it == 0) bar_stamp(bar);   // the first tile's epilogue has been issued
+#endif
                 ++it;
             }
         }
@@ -455,20 +577,27 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     for (int f = 0; f < NF; ++f)
 #pragma unroll
         for (int u = 0; u < KC; ++u) {
-            u32x4_t t0 = __builtin_bit_cast(u32x4_t, x0[f][u]), t1 = __builtin_bit_cast(u32x4_t, x1[f][u]);
-            asm volatile("" : "+v"(t0), "+v"(t1));
+            u32x4_t t0 = __builtin_bit_cast(u32x4_t, x0[f][u]);
+            asm volatile("" : "+v"(t0));
             x0[f][u] = __builtin_bit_cast(uint4, t0);
-            x1[f][u] = __builtin_bit_cast(uint4, t1);
+            if (!kX1Lds && XLOOK == 2) {
+                u32x4_t t1 = __builtin_bit_cast(u32x4_t, x1[f][u]);
+                asm volatile("" : "+v"(t1));
+                x1[f][u] = __builtin_bit_cast(uint4, t1);
+            }
         }
+#ifdef ANPD_TRACE_FINE
+    bar_stamp(bar);   // the operand has arrived
+#endif
     if constexpr (RING == 3) {
         while (ti < my_tiles) {
             do_step(pf, x0, true, false);
-            do_step(wb, x1, ti < my_tiles, false);
+            do_step(wb, x1, ti < my_tiles, false, true);
             do_step(wc, x0, ti < my_tiles, cross_last);
             if (!STATIONARY) {   // three weight buffers, two operand buffers: the pattern repeats after six steps
-                do_step(pf, x1, ti < my_tiles, false);
+                do_step(pf, x1, ti < my_tiles, false, true);
                 do_step(wb, x0, ti < my_tiles, false);
-                do_step(wc, x1, ti < my_tiles, cross_last);
+                do_step(wc, x1, ti < my_tiles, cross_last, true);
             }
         }
         if (cross_last) {   // the next phase expects its first item in pf
@@ -478,13 +607,16 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     } else {
         while (ti < my_tiles) {
             do_step(pf, x0, true, false);
-            do_step(wb, x1, ti < my_tiles, cross_last);
+            do_step(wb, XLOOK == 2 ? x1 : x0, ti < my_tiles, cross_last, true);
         }
         if (cross_last) {
 #pragma unroll
             for (int u = 0; u < KC; ++u) pf[u] = wb[u];
         }
     }
+#ifdef ANPD_TRACE_FINE
+    if (my_tiles == 0) { bar_stamp(bar); }   // (keeps the number of stamps per phase fixed)
+#endif
     // Order in this compute unit's memory queue at the end of a phase: the last epilogue's stores,
     // then the other waves' first chunk of the next phase, then (after the acknowledgement) the
     // barrier signal, and only then the rest of the next phase's requests.
@@ -530,6 +662,17 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
 // registers across the others (kept live, these values push the weight pipeline into scratch
 // memory, and a scratch reload queues behind the weight loads in flight).
 typedef const MegaArgs __attribute__((address_space(4))) *MegaArgsK;
+
+// The four activation operands of layer l (which = 0 QKV, 1 attention output, 2 gate / up, 3 down).
+// Every operand has addresses of its own for the whole launch, so a compute unit's L2 cannot hold an older
+// version of a line it reads (the L2s are cleared of other XCDs' data when a launch starts, producers write
+// through, and a 128-byte line is written by one block only): consumers may read the operands through their
+// XCD's L2, where the 32 blocks of an XCD share one fetch, instead of each at the coherence point.
+__host__ __device__ __forceinline__ size_t x_operand_elems(int columns) { return (size_t)((columns + 31) / 32) * kMaxFrags * 512; }
+__device__ __forceinline__ bf16_t *x_operand(MegaArgsK g, int l, int which)
+{
+    return g->xp_layers + (size_t)l * g->xp_stride + (size_t)which * x_operand_elems(g->d);
+}
 typedef const LayerW __attribute__((address_space(4))) *LayerWK;
 __device__ __forceinline__ MegaArgsK phase_args()
 {
@@ -565,7 +708,6 @@ __device__ __forceinline__ FastArgs base_args(MegaArgsK g)
     a.n_kv_heads = g->n_kv_heads;
     a.head_dim = g->head_dim;
     a.qp = g->qp;
-    a.ap = g->xp_f;
     return a;
 }
 
@@ -579,7 +721,7 @@ template <int DH, int MODE = MEGA_CHAIN, int NF = 1, int KC = kChunk>
 __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* read through phase_args() */)
 {
     constexpr bool TREE = MODE == MEGA_TREE, BATCH = MODE == MEGA_BATCH;
-    __shared__ MegaShared sh;
+    __shared__ MegaShared<NF> sh;
     __shared__ float bval[kFastWaves];
     __shared__ int bidx[kFastWaves];
     __shared__ bool last_row;
@@ -604,7 +746,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
         // ---- embed (+ operand and sums of squares for the first norm)
         FastArgs a = base_args<NF>(g);
         a.gain = w0.attn_gain;
-        a.xp_next = g->xp_d;
+        a.xp_next = x_operand(g, 0, 0);
         a.ssp_next = g->ssp_a;
         if (wave == 0)
             // (the block that owns a tile of the residual stream here owns it in the O and down phases too)
@@ -617,7 +759,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             const LayerW w = layer_weights(g, l);
             FastArgs a = base_args<NF>(g);
             const int nks_d = (g->d + 31) / 32;
-            a.Wp = w.qkv; a.Xp = (const uint4 *)g->xp_d; a.nks = nks_d;
+            a.Wp = w.qkv; a.Xp = (const uint4 *)x_operand(g, l, 0); a.nks = nks_d;
             a.n_tiles = (g->d + 2 * g->n_kv_heads * g->head_dim) / 16;
             a.ssp = g->ssp_a; a.layer = l; a.ready = g->qkv_ready;
             if (TREE) a.depth = (const int32_t *)g->depth;
@@ -714,7 +856,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
                 AttnBatch bt = {k.row0, k.rows, g->n_att_blocks, (const SeqRef *)g->seqs, (const int32_t *)g->row_seq};
                 attn_task<DH, true, decltype(prefetch_o), BATCH ? ATTN_BATCH : (TREE ? ATTN_TREE : ATTN_CHAIN), decltype(next_page)>(
                     attn_shared<DH>(sh), kv, k.head, k.split, k.L, (const uint4 *)g->qp, k.pool, k.table, M, l, n_layers, n_heads,
-                    g->n_kv_heads, g->max_splits, g->scale, g->part, g->head_counter, g->xp_att, packed_class(NF), prefetch_o,
+                    g->n_kv_heads, g->max_splits, g->scale, g->part, g->head_counter, x_operand(g, l, 1), packed_class(NF), prefetch_o,
                     TREE ? (const uint32_t *)g->mask : nullptr, BATCH ? &bt : nullptr, next_page, publish);
                 block_sync_lds();
             }
@@ -726,8 +868,8 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             const LayerW w = layer_weights(g, l);
             FastArgs a = base_args<NF>(g);
             const int nks_d = (g->d + 31) / 32;
-            a.Wp = w.o; a.Xp = (const uint4 *)g->xp_att; a.nks = nks_d; a.n_tiles = g->d / 16;
-            a.gain = w.ffn_gain; a.xp_next = g->xp_d; a.ssp_next = g->ssp_b;
+            a.Wp = w.o; a.Xp = (const uint4 *)x_operand(g, l, 1); a.nks = nks_d; a.n_tiles = g->d / 16;
+            a.gain = w.ffn_gain; a.xp_next = x_operand(g, l, 2); a.ssp_next = g->ssp_b;
             WSrc next = {w.gu, nks_d, g->F / 8};
             gemm_phase<EPI_RESIDUAL, true, true, NF, KC>(a, next, pf, sh, bar, tiles_before);
         }
@@ -735,7 +877,8 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             MegaArgsK g = phase_args();
             const LayerW w = layer_weights(g, l);
             FastArgs a = base_args<NF>(g);
-            a.Wp = w.gu; a.Xp = (const uint4 *)g->xp_d; a.nks = (g->d + 31) / 32; a.n_tiles = g->F / 8;
+            a.Wp = w.gu; a.Xp = (const uint4 *)x_operand(g, l, 2); a.nks = (g->d + 31) / 32; a.n_tiles = g->F / 8;
+            a.ap = x_operand(g, l, 3);
             a.ssp = g->ssp_b;
             WSrc next = {w.down, (g->F + 31) / 32, g->d / 16};
             gemm_phase<EPI_GATE_UP, true, true, NF, KC>(a, next, pf, sh, bar, tiles_before);
@@ -744,10 +887,10 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             MegaArgsK g = phase_args();
             const LayerW w = layer_weights(g, l);
             FastArgs a = base_args<NF>(g);
-            a.Wp = w.down; a.Xp = (const uint4 *)g->xp_f; a.nks = (g->F + 31) / 32; a.n_tiles = g->d / 16;
+            a.Wp = w.down; a.Xp = (const uint4 *)x_operand(g, l, 3); a.nks = (g->F + 31) / 32; a.n_tiles = g->d / 16;
             const bool more = l + 1 < n_layers;
             a.gain = more ? layer_weights(g, l + 1).attn_gain : g->final_gain;
-            a.xp_next = g->xp_d; a.ssp_next = g->ssp_a;
+            a.xp_next = x_operand(g, l + 1, 0); a.ssp_next = g->ssp_a;
             WSrc next = {more ? layer_weights(g, l + 1).qkv : g->wp_lm, (g->d + 31) / 32, more ? (g->d + 2 * g->n_kv_heads * g->head_dim) / 16 : g->V / 16};
             gemm_phase<EPI_RESIDUAL, false, true, NF, KC>(a, next, pf, sh, bar, tiles_before);
         }
@@ -756,7 +899,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
         MegaArgsK g = phase_args();
         FastArgs a = base_args<NF>(g);
         const int nks_d = (g->d + 31) / 32;
-        a.Wp = g->wp_lm; a.Xp = (const uint4 *)g->xp_d; a.nks = nks_d; a.n_tiles = g->V / 16;
+        a.Wp = g->wp_lm; a.Xp = (const uint4 *)x_operand(g, g->n_layers, 0); a.nks = nks_d; a.n_tiles = g->V / 16;
         a.ssp = g->ssp_a; a.Y = g->logits; a.ldy = g->V; a.amax = g->amax;
         WSrc none = {g->wp_lm, nks_d, 0};
         gemm_phase<EPI_LM_ARGMAX, true, true, NF, KC>(a, none, pf, sh, bar, tiles_before);
