@@ -482,7 +482,7 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
     int32_t *result = (int32_t *)(ws + L.result);
     uint32_t *counter = (uint32_t *)(ws + L.counter);
     const float scale = 1.0f / sqrtf((float)dh);
-    const int n_splits = batch ? batch->grid_splits : (kv->len + M + kFastSplit - 1) / kFastSplit;
+    const int n_splits = batch ? batch->grid_splits : n_splits_of(kv->len + M);
     const int nks_d = (d + 31) / 32, nks_f = (F + 31) / 32;
     const int32_t *b_row_seq = (const int32_t *)(ws + L.batch);
     const SeqRef *b_seqs = (const SeqRef *)(ws + L.batch + ANPD_MAX_WINDOW * sizeof(int32_t));
@@ -680,7 +680,7 @@ int32_t run_step_mega(anpd_model *m, anpd_kv *kv, const int32_t *window, int M, 
         for (int s = 0; s < batch->n_seq; ++s) {
             g.seqs[s] = batch->seqs[s];
             g.task0[s] = tasks;
-            const int splits = (batch->len[s] + batch->seqs[s].n_rows + kFastSplit - 1) / kFastSplit;
+            const int splits = n_splits_of(batch->len[s] + batch->seqs[s].n_rows);
             tasks += splits * c.n_heads;
             g.n_att_blocks += splits;
         }
@@ -1395,7 +1395,7 @@ int32_t anpd_verify_batch(anpd_model_t *m, anpd_kv_t *const *kvs, int32_t n_seq,
         seqs[s].len_ptr = kv->d_len;
         seqs[s].row0 = row;
         seqs[s].n_rows = n_windows[s];
-        const int splits = (kv->len + n_windows[s] + kFastSplit - 1) / kFastSplit;
+        const int splits = n_splits_of(kv->len + n_windows[s]);
         bl.n_blocks += splits;
         if (splits > bl.grid_splits) bl.grid_splits = splits;
         for (int i = 0; i < n_windows[s]; ++i, ++row) {

@@ -734,17 +734,39 @@ __global__ __launch_bounds__(256) void split_packed_kernel(const float *__restri
 
 typedef short bf16x4s __attribute__((ext_vector_type(4)));
 
-// Window-causal attention on the matrix cores.  Block (head, split) covers
-// kFastSplit = 128 absolute key positions, one 16-token page per wave.  Per
-// group of 8 window rows: S = K q^T with the query as a split-bf16 B operand
-// (scores land with keys in registers and rows across lanes), softmax
-// statistics over the split with the block maximum, P as a split-bf16 B
-// operand straight from those registers, O = V^T P; the waves' tiles are
-// added in a fixed order through LDS.  Each block stores (o, max, denominator)
-// of its split; the last block of a head to finish merges the head's splits
-// in increasing order and writes the packed operand of the output projection.
+// Window-causal attention on the matrix cores.  The key positions are cut into splits at fixed absolute
+// positions: 4 splits of 128 keys, then 2 of 256, then splits of 384 (split_begin).  A block works on one
+// (head, split); wave w takes the 16-token pages w, w + 8, ... of the split (1, 2 or 3 pages), one after
+// the other.  Per group of 8 window rows and per page: S = K q^T with the query as a split-bf16 B operand
+// (scores land with keys in registers and rows across lanes), P as a split-bf16 B operand straight from
+// those registers, O += V^T P in the matrix cores' accumulators; the wave keeps a running (maximum,
+// denominator, output) over its pages and rescales it when a page raises the maximum - no exchange with
+// other waves until the wave's pages are done.  Then the waves' maxima meet in LDS, every wave scales its
+// result to the block maximum and the tiles are added in a fixed order.  Each block stores (o, max,
+// denominator) of its split; the last block of a head to finish merges the head's splits in increasing
+// order and writes the packed operand of the output projection.  Short contexts get many small tasks (one
+// page per wave, nothing sequential), long ones fewer and larger ones (15 per head at 4096 positions, where
+// splits of 128 gave 33): a task costs a chain of round trips - query rows, reduction, stores, counter -
+// whatever its size.  The cut depends on absolute key positions only, so a row's sums do not depend on the
+// window size, on how a prompt was cut into pieces or on the cache's capacity.
+// Scores are kept in the base-2 domain (scaled by log2 e) so that every exponential is one v_exp_f32.
 // Row r sees keys 0..len + r; keys it must not see get weight exactly 0.
-constexpr int kFastSplit = kFastWaves * 16;
+constexpr int kFastPages = 3;   // most pages per wave per task
+__host__ __device__ constexpr int split_begin(int s)
+{
+    return s <= 4 ? s * 128 : s <= 6 ? 512 + (s - 4) * 256 : 1024 + (s - 6) * 384;
+}
+__host__ __device__ constexpr int split_pages(int s) { return s < 4 ? 1 : s < 6 ? 2 : kFastPages; }   // per wave
+__host__ __device__ constexpr int split_of(int key)
+{
+    return key < 512 ? key >> 7 : key < 1024 ? 4 + ((key - 512) >> 8) : 6 + (key - 1024) / 384;
+}
+// number of splits that hold at least one of the keys 0 .. n_keys - 1
+__host__ __device__ constexpr int n_splits_of(int n_keys) { return n_keys <= 0 ? 0 : split_of(n_keys - 1) + 1; }
+static_assert(split_begin(4) == 512 && split_begin(6) == 1024 && split_of(511) == 3 && split_of(512) == 4 &&
+              split_of(1023) == 5 && split_of(1024) == 6 && split_of(split_begin(9)) == 9 && split_of(split_begin(9) - 1) == 8 &&
+              split_begin(10) - split_begin(9) == 16 * kFastWaves * kFastPages,
+              "cut of the key positions");
 // uint32 words between per-head counters: one 256-byte line each.  Atomics of different heads on one
 // line serialise at the memory side (measured with polled counters: +16 % step time when packed).
 constexpr int kCounterStride = 64;
@@ -775,26 +797,62 @@ struct AttnKV {
     bool loaded;
 };
 
+// Pages 1 and 2 of a task, per wave, parked in LDS by a caller that requested them ahead of the task (the
+// persistent kernel does: for a block's first task while the QKV weights stream, for its later tasks while
+// the task before is reduced): a wave has registers for two pages at a time.  The pages go from memory straight into LDS, in the order the fragments have in memory, so
+// every lane reads back the 16 / 8 bytes a register load would have given it.
+struct AttnStash {
+    uint4 k[2][kFastWaves][4][64];
+    uint2 v[2][kFastWaves][8][64];
+};
+template <int DH>
+__device__ __forceinline__ void stash_get(const AttnStash &st, int slot, AttnKV<DH> &kv, int wave, int lane)
+{
+#pragma unroll
+    for (int i = 0; i < DH / 32; ++i) kv.kf[i] = st.k[slot][wave][i][lane];
+#pragma unroll
+    for (int i = 0; i < DH / 16; ++i) kv.vf[i] = st.v[slot][wave][i][lane];
+    kv.loaded = true;
+}
+
 // Requests the wave's K / V page.  With only_old, only a page that lies wholly below position L:
 // such a page was written by earlier steps, so the persistent kernel can request it before the
 // barrier that ends the QKV phase (the window's own rows are written in that phase).
 // `head` is the key / value head, one of n_kv_heads.
+// j: which of the wave's pages of the split.
+// ids: the page table's entries for the wave's pages, requested earlier (attn_page_ids), or null: a request
+// that looks its entry up itself waits for it, and with it for everything the wave requested before.
+struct AttnPageIds {
+    int e[kFastPages];
+};
+__device__ __forceinline__ AttnPageIds attn_page_ids(int split, int L, int M, const int32_t *__restrict__ page_table)
+{
+    const int wave = fresh_tid() >> 6;
+    AttnPageIds ids;
+#pragma unroll
+    for (int j = 0; j < kFastPages; ++j) {
+        const int key0 = split_begin(split) + (wave + kFastWaves * j) * 16;
+        ids.e[j] = (j < split_pages(split) && key0 < L + M) ? page_table[key0 >> 4] : 0;
+    }
+    return ids;
+}
 template <int DH, bool COH>
 __device__ __forceinline__ void attn_load_kv(AttnKV<DH> &kv, int head, int split, int L, int M,
                                              const bf16_t *__restrict__ pool, const int32_t *__restrict__ page_table,
-                                             int layer, int n_layers, int n_heads, bool only_old)
+                                             int layer, int n_layers, int n_heads, bool only_old, int j = 0,
+                                             const AttnPageIds *ids = nullptr)
 {
     const int tid = fresh_tid();
     constexpr int NKS = DH / 32, NDT = DH / 16;
     const int lane = tid & 63, wave = tid >> 6;
-    const int key0 = split * kFastSplit + wave * 16;
+    const int key0 = split_begin(split) + (wave + kFastWaves * j) * 16;
 #pragma unroll
     for (int i = 0; i < NKS; ++i) kv.kf[i] = make_uint4(0, 0, 0, 0);
 #pragma unroll
     for (int i = 0; i < NDT; ++i) kv.vf[i] = make_uint2(0, 0);
     kv.loaded = false;
     if (key0 < L + M && (!only_old || key0 + 15 < L)) {
-        const int page = __builtin_amdgcn_readfirstlane(page_table[key0 >> 4]);
+        const int page = __builtin_amdgcn_readfirstlane(ids ? ids->e[j] : page_table[key0 >> 4]);
         const uint4 *kp = reinterpret_cast<const uint4 *>(pool + kvf_base(page, layer, n_layers, 0, head, n_heads, DH));
         const uint2 *vp = reinterpret_cast<const uint2 *>(pool + kvf_base(page, layer, n_layers, 1, head, n_heads, DH));
 #pragma unroll
@@ -803,6 +861,45 @@ __device__ __forceinline__ void attn_load_kv(AttnKV<DH> &kv, int head, int split
         for (int i = 0; i < NDT; ++i) kv.vf[i] = ld8_at<COH>(vp, (uint32_t)(i * 64 + lane));
         kv.loaded = true;
     }
+}
+
+// The query rows of row group rg of a head: the wave's B operand of the score MFMAs.
+template <int DH, bool COH>
+__device__ __forceinline__ void attn_load_q(uint4 (&qf)[DH / 32], const uint4 *__restrict__ qp, int head, int rg)
+{
+    const int lane = fresh_tid() & 63;
+    const uint4 *q = qp + ((size_t)(head * 4 + rg) * (DH / 32)) * 64;
+#pragma unroll
+    for (int ks = 0; ks < DH / 32; ++ks) qf[ks] = ld16_at<COH>(q, (uint32_t)(ks * 64 + lane));
+}
+// Whether attn_park parks page j of wave `wave` of this split (the same answer wherever it is asked).
+__device__ __forceinline__ bool attn_parks(int split, int L, int wave, int j)
+{
+    return split_begin(split) + (wave + kFastWaves * j) * 16 + 15 < L;
+}
+// Requests page j of this wave straight into slot `slot` of the stash, if the page lies wholly below
+// position L (see attn_load_kv, only_old).  Returns whether it did (the same for the whole wave).
+template <int DH>
+__device__ __forceinline__ bool attn_park(AttnStash &st, int slot, int head, int split, int L, const bf16_t *__restrict__ pool,
+                                          const int32_t *__restrict__ page_table, int layer, int n_layers, int n_heads, int j,
+                                          const AttnPageIds *ids = nullptr)
+{
+    typedef __attribute__((address_space(3))) void *lds_ptr;
+    const int tid = fresh_tid();
+    const int lane = tid & 63, wave = tid >> 6;
+    const int key0 = split_begin(split) + (wave + kFastWaves * j) * 16;
+    if (!attn_parks(split, L, wave, j)) return false;
+    const int page = __builtin_amdgcn_readfirstlane(ids ? ids->e[j] : page_table[key0 >> 4]);
+    __amdgpu_buffer_rsrc_t rk = wave_buffer(pool + kvf_base(page, layer, n_layers, 0, head, n_heads, DH));
+    __amdgpu_buffer_rsrc_t rv = wave_buffer(pool + kvf_base(page, layer, n_layers, 1, head, n_heads, DH));
+    // K: DH / 32 fragments of 16 bytes per lane; V: DH / 16 fragments of 8 bytes per lane, the same number of bytes
+#pragma unroll
+    for (int i = 0; i < DH / 32; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_ptr)&st.k[slot][wave][i][0], 16, lane * 16, i * 1024, 0, kAuxCoherent);
+#pragma unroll
+    for (int i = 0; i < DH / 32; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_ptr)&st.v[slot][wave][2 * i][0], 16, lane * 16, i * 1024, 0, kAuxCoherent);
+    return true;
 }
 
 // Partial results of the splits: outputs [head][split][32 rows][DH], then (maximum, denominator)
@@ -816,8 +913,10 @@ __device__ __forceinline__ size_t part_s_index(int n_heads, int head, int split,
     return (size_t)n_heads * max_splits * 32 * DH + (((size_t)head * max_splits + split) * 32 + row) * 2;
 }
 
-// One (head, split) task; every thread of the block calls it.  kv holds the wave's page if
-// kv.loaded, else it is requested here.  `after_loads` runs right after the task's own loads have
+// One (head, split) task; every thread of the block calls it.  kv holds the wave's first page if
+// kv.loaded, else it is requested here; pages 1 and 2 are read from `stash` where stashed1 / stashed2 say so.
+// q_lds: 16 * DH bytes of LDS for the copy of the query rows (or null); q_in_lds: the copy is there.
+// more_tasks: after_values will request something.  `after_loads` runs right after the task's own loads have
 // been issued (the persistent kernel puts its weight prefetch there, so that the prefetch queues
 // behind the loads attention is waiting for, not in front of them).
 // MODE 1 (tree): the window is a draft tree; row_mask[m] has bit r set if window row r is row m itself
@@ -841,98 +940,161 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
                                           const int32_t *__restrict__ page_table, int M, int layer, int n_layers, int n_heads,
                                           int n_kv_heads, int max_splits, float scale, float *__restrict__ part,
                                           uint32_t *__restrict__ head_counter, bf16_t *__restrict__ xp_att, int cls,
-                                          AfterLoads after_loads = AfterLoads(), const uint32_t *__restrict__ row_mask = nullptr,
-                                          const AttnBatch *batch = nullptr, AfterValues after_values = AfterValues(),
-                                          int publish = 1)
+                                          AfterLoads after_loads, const uint32_t *__restrict__ row_mask,
+                                          const AttnBatch *batch, AfterValues after_values,
+                                          int publish, const AttnStash *stash, bool stashed1, bool stashed2,
+                                          uint4 *q_lds, bool q_in_lds, bool more_tasks)
 {
     constexpr bool TREE = MODE == ATTN_TREE, BATCH = MODE == ATTN_BATCH;
     const int tid = fresh_tid();
     constexpr int NKS = DH / 32, NDT = DH / 16;
     const int lane = tid & 63, wave = tid >> 6, slot = lane & 15, kg = lane >> 4;
-    const int key0 = split * kFastSplit + wave * 16;
     const int row0 = BATCH ? batch->row0 : 0, row_end = BATCH ? batch->row0 + batch->n_rows : M;   // this task's rows
     const int rg0 = row0 >> 3;
-    const bool active = key0 < L + (row_end - row0);
+    const int kv_head = head / (n_heads / n_kv_heads);
     ANPD_STAMP(0);
 
-    if (!kv.loaded)
-        attn_load_kv<DH, COH>(kv, head / (n_heads / n_kv_heads), split, L, row_end - row0, pool, page_table, layer, n_layers,
-                              n_kv_heads, false);
+    // The wave has registers for two pages: kv (page 0, then page 2) and kvb (page 1).  What is not parked
+    // in LDS is requested here; the requests go out before `after_loads`: loads come back in the order they
+    // were issued, and what after_loads requests is further away.
+    const int n_pages = split_pages(split);
+    AttnKV<DH> kvb;
+    kvb.loaded = false;
+    auto request = [&](AttnKV<DH> &dst, int j) __attribute__((always_inline)) {
+        attn_load_kv<DH, COH>(dst, kv_head, split, L, row_end - row0, pool, page_table, layer, n_layers, n_kv_heads, false, j);
+    };
+    if (!kv.loaded) request(kv, 0);
+    if (n_pages > 1 && !stashed1) request(kvb, 1);
+    // the query rows of the first row group: from memory, or from the copy an earlier task of this block left
+    // in LDS (same head, same rows) - a block's later tasks then do not wait for memory before their first page
     uint4 qf[NKS];
-    {
-        const uint4 *q = qp + ((size_t)(head * 4 + rg0) * NKS) * 64;
+    if (q_in_lds) {
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) qf[ks] = ld16_at<COH>(q, (uint32_t)(ks * 64 + lane));
+        for (int ks = 0; ks < NKS; ++ks) qf[ks] = q_lds[ks * 64 + lane];
+    } else {
+        attn_load_q<DH, COH>(qf, qp, head, rg0);
     }
-    after_loads();
+    // (a task of several pages waits for loads while it goes through them, and what after_loads requests
+    // would be in front of those in the queue: there it is called once the pages are done)
+    // (... nor when another task follows: its first requests wait for a table entry, and would wait for
+    // everything requested before it)
+    const bool loads_late = n_pages > 1 || more_tasks;
+    if (!loads_late) after_loads();
 
+    const float scale2 = scale * 1.44269504088896f;   // scores in the base-2 domain
     for (int rg = rg0; rg * 8 < row_end; ++rg) {
-        // ---- scores S[key][row]
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         if (rg > rg0) {
-            const uint4 *q = qp + ((size_t)(head * 4 + rg) * NKS) * 64;
-#pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) qf[ks] = ld16_at<COH>(q, (uint32_t)(ks * 64 + lane));
+            attn_load_q<DH, COH>(qf, qp, head, rg);
+            if (n_pages > 2) request(kv, 0);   // (otherwise every page is still in its registers)
         }
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kv.kf[ks]),
-                                                          __builtin_bit_cast(bf16x8, qf[ks]), acc, 0, 0, 0);
         const int m = rg * 8 + (slot & 7);
+        const bool row_ok = slot < 8 && m < M && (!BATCH || (m >= row0 && m < row_end));
         uint32_t vis = 0;
         if (TREE) vis = row_mask[m < M ? m : 0];
-        float sc[4], mx = kMasked;
+        // running maximum and denominator of this wave's pages for row m; the output accumulates in the
+        // matrix cores' layout (hi products in slots 0..7, lo products in 8..15, added once at the end)
+        float m_run = kMasked, d_run = 0.f;
+        f32x4 o_acc[NDT];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float lo = row_down8(acc[i]);
-            const int key = key0 + 4 * kg + i;
-            const bool sees = TREE    ? (key < L || (key - L < 32 && ((vis >> (key - L)) & 1u)))
-                              : BATCH ? (m >= row0 && m < row_end && key <= L + (m - row0))
-                                      : key <= L + m;
-            const bool ok = active && slot < 8 && m < M && sees;
-            sc[i] = ok ? (acc[i] + lo) * scale : kMasked;
-            mx = fmaxf(mx, sc[i]);
+        for (int dt = 0; dt < NDT; ++dt) o_acc[dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        // one page: scores, exponentials against the new running maximum, P, O += V^T P
+        auto page = [&](const AttnKV<DH> &cur, int j) __attribute__((always_inline)) {
+            const int key0 = split_begin(split) + (wave + kFastWaves * j) * 16;
+            if (key0 >= L + (row_end - row0)) return;   // (whole wave) nothing of this page exists yet
+            // ---- scores S[key][row]
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.kf[ks]),
+                                                              __builtin_bit_cast(bf16x8, qf[ks]), acc, 0, 0, 0);
+            float sc[4], mx = kMasked;
+            // a page wholly below the committed length is seen by every row (whole-wave branch)
+            const bool all_seen = key0 + 15 < L;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float v = (acc[i] + row_down8(acc[i])) * scale2;
+                bool ok = row_ok;
+                if (!all_seen) {
+                    const int key = key0 + 4 * kg + i;
+                    const bool sees = TREE    ? (key < L || (key - L < 32 && ((vis >> (key - L)) & 1u)))
+                                      : BATCH ? key <= L + (m - row0)
+                                              : key <= L + m;
+                    ok = ok && sees;
+                }
+                sc[i] = ok ? v : kMasked;
+                mx = fmaxf(mx, sc[i]);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+            // ---- the page's exponentials against the new running maximum
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            float p[4], den = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                p[i] = sc[i] > 0.5f * kMasked ? __builtin_amdgcn_exp2f(sc[i] - m_new) : 0.f;
+                den += p[i];
+            }
+            den += __shfl_xor(den, 16, kWave);
+            den += __shfl_xor(den, 32, kWave);
+            d_run = fmaf(d_run, alpha, den);
+            m_run = m_new;
+            // ---- what the wave has so far is rescaled only if some row's maximum went up (whole-wave
+            // branch; a factor of exactly 1 changes nothing, so the result does not depend on it)
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+                const float up = row_up8(alpha);
+                const float af = slot < 8 ? alpha : up;
+#pragma unroll
+                for (int dt = 0; dt < NDT; ++dt) o_acc[dt] = o_acc[dt] * af;
+            }
+            // ---- P operand (hi rows in slots 0..7, lo rows in 8..15)
+            bf16x4s pb;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float up = row_up8(p[i]);
+                float pv = slot < 8 ? p[i] : up;
+                bf16_t hi = f32_to_bf16(pv);
+                bf16_t o = slot < 8 ? hi : f32_to_bf16(pv - bf16_to_f32(hi));
+                pb[i] = (short)o;
+            }
+            // ---- O[dim][row] += V^T P, one 16-dim tile at a time
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt)
+                o_acc[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4s, cur.vf[dt]), pb, o_acc[dt], 0, 0, 0);
+        };
+        static_assert(kFastPages == 3, "page 2 takes the registers of page 0");
+        page(kv, 0);
+        if (n_pages > 1) {
+            if (stashed1) stash_get<DH>(*stash, 0, kvb, wave, lane);
+            if (n_pages > 2 && !stashed2) request(kv, 2);
+            page(kvb, 1);
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-        if (kg == 0 && slot < 8) sh.wmax[wave][slot] = mx;
-        block_sync_lds();
+        if (n_pages > 2) {
+            if (stashed2) stash_get<DH>(*stash, 1, kv, wave, lane);
+            page(kv, 2);
+        }
+        if (!q_in_lds && q_lds && more_tasks && wave == 0 && rg == rg0) {   // (read by later tasks: block barriers lie in between)
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) q_lds[ks * 64 + lane] = qf[ks];
+        }
+        if ((rg + 1) * 8 >= row_end) after_values();
+        if (loads_late && rg == rg0) after_loads();
         ANPD_STAMP(1);
+        // ---- the waves' maxima meet; every wave scales its result to the block maximum
+        if (kg == 0 && slot < 8) sh.wmax[wave][slot] = m_run;
+        block_sync_lds();
         float bm = sh.wmax[0][slot & 7];
 #pragma unroll
         for (int w = 1; w < kFastWaves; ++w) bm = fmaxf(bm, sh.wmax[w][slot & 7]);
-        // ---- exponentials, denominators, P operand (hi rows in slots 0..7, lo rows in 8..15)
-        float p[4], den = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            p[i] = (slot < 8 && sc[i] > 0.5f * kMasked) ? expf(sc[i] - bm) : 0.f;
-            den += p[i];
-        }
-        den += __shfl_xor(den, 16, kWave);
-        den += __shfl_xor(den, 32, kWave);
-        if (kg == 0 && slot < 8) sh.wden[wave][slot] = den;
+        const float wf = __builtin_amdgcn_exp2f(m_run - bm);
+        if (kg == 0 && slot < 8) sh.wden[wave][slot] = d_run * wf;
         ANPD_STAMP(7);
-        bf16x4s pb;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float up = row_up8(p[i]);
-            float pv = slot < 8 ? p[i] : up;
-            bf16_t hi = f32_to_bf16(pv);
-            bf16_t o = slot < 8 ? hi : f32_to_bf16(pv - bf16_to_f32(hi));
-            pb[i] = (short)o;
-        }
-        // ---- O[dim][row] = V^T P, one 16-dim tile at a time
         f32x4 ot[NDT];
 #pragma unroll
         for (int dt = 0; dt < NDT; ++dt) {
-            f32x4 o = {0.f, 0.f, 0.f, 0.f};
-            o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4s, kv.vf[dt]), pb, o, 0, 0, 0);
-            f32x4 lo;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) lo[i] = row_down8(o[i]);
-            ot[dt] = o + lo;
+            for (int i = 0; i < 4; ++i) ot[dt][i] = (o_acc[dt][i] + row_down8(o_acc[dt][i])) * wf;
         }
-        if ((rg + 1) * 8 >= row_end) after_values();
         // ---- add the waves' tiles: wave w + H into wave w (H = half the waves), then waves 0..H-1 in
         // order, one or two dim tiles per wave.  LDS is addressed by compacted lane (kg * 8 + slot).
         const int cl = kg * 8 + (slot & 7);
@@ -982,7 +1144,7 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
     wait_stores();
     block_sync_lds();
     ANPD_STAMP(3);
-    const int n_blocks = BATCH ? batch->n_blocks : (L + M + kFastSplit - 1) / kFastSplit;
+    const int n_blocks = BATCH ? batch->n_blocks : n_splits_of(L + M);
     if (tid == 0)
         sh.last = __hip_atomic_fetch_add(&head_counter[head * kCounterStride], (uint32_t)publish, __ATOMIC_RELAXED,
                                          __HIP_MEMORY_SCOPE_AGENT) + (uint32_t)publish == (uint32_t)n_blocks;
@@ -999,10 +1161,10 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
     const uint2 *ps = reinterpret_cast<const uint2 *>(part + part_s_index(n_heads, head, 0, max_splits, 0, DH));
     for (int idx = tid; idx < M * DQ; idx += kFastThreads) {
         const int row = idx / DQ, e4 = idx - row * DQ;
-        int ns = (L + row) / kFastSplit + 1;
+        int ns = split_of(L + row) + 1;
         if (BATCH) {   // the row's own sequence decides how many splits it has
             const SeqRef sq = batch->seqs[batch->row_seq[row]];
-            ns = (*sq.len_ptr + (row - sq.row0)) / kFastSplit + 1;
+            ns = split_of(*sq.len_ptr + (row - sq.row0)) + 1;
         }
         float g = kMasked;
         if (ns > SB) {   // long contexts: the maximum needs a pass of its own, SB splits per round trip
@@ -1033,7 +1195,7 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
 #pragma unroll
             for (int j = 0; j < SB; ++j) {
                 if (s0 + j < ns) {
-                    const float wgt = expf(__uint_as_float(st[j].x) - g);
+                    const float wgt = __builtin_amdgcn_exp2f(__uint_as_float(st[j].x) - g);
                     den = fmaf(wgt, __uint_as_float(st[j].y), den);
                     o[0] = fmaf(wgt, __uint_as_float(ov[j].x), o[0]);
                     o[1] = fmaf(wgt, __uint_as_float(ov[j].y), o[1]);
@@ -1048,7 +1210,7 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
     ANPD_STAMP(6);
 }
 
-// grid: (n_heads, ceil((len + M) / kFastSplit)), kFastWaves waves.
+// grid: (n_heads, n_splits_of(len + M)), kFastWaves waves.
 template <int DH, bool TREE = false>
 __global__ __launch_bounds__(kFastThreads) void attn_fast_kernel(const uint4 *__restrict__ qp, const bf16_t *__restrict__ pool,
                                                           const int32_t *__restrict__ page_table,
@@ -1060,12 +1222,13 @@ __global__ __launch_bounds__(kFastThreads) void attn_fast_kernel(const uint4 *__
 {
     __shared__ AttnShared<DH> sh;
     const int L = *len_ptr;
-    if ((int)blockIdx.y * kFastSplit >= L + M) return;
+    if (split_begin(blockIdx.y) >= L + M) return;
     AttnKV<DH> kv;
     kv.loaded = false;
     attn_task<DH, false, NoPrefetch, TREE ? ATTN_TREE : ATTN_CHAIN>(sh, kv, blockIdx.x, blockIdx.y, L, qp, pool, page_table, M, layer,
                                                                     n_layers, n_heads, n_kv_heads, max_splits, scale, part,
-                                                                    head_counter, xp_att, cls, NoPrefetch(), row_mask);
+                                                                    head_counter, xp_att, cls, NoPrefetch(), row_mask, nullptr,
+                                                                    NoPrefetch(), 1, nullptr, false, false, nullptr, false, false);
 }
 
 // Several sequences' windows in one step: block (head, split, sequence) works on that sequence's rows
@@ -1081,13 +1244,13 @@ __global__ __launch_bounds__(kFastThreads) void attn_batch_kernel(const uint4 *_
     __shared__ AttnShared<DH> sh;
     const SeqRef sq = seqs[blockIdx.z];
     const int L = *sq.len_ptr;
-    if ((int)blockIdx.y * kFastSplit >= L + sq.n_rows) return;
+    if (split_begin(blockIdx.y) >= L + sq.n_rows) return;
     AttnKV<DH> kv;
     kv.loaded = false;
     AttnBatch bt = {sq.row0, sq.n_rows, n_blocks, seqs, row_seq};
     attn_task<DH, false, NoPrefetch, ATTN_BATCH>(sh, kv, blockIdx.x, blockIdx.y, L, qp, sq.pool, sq.page_table, M, layer, n_layers,
                                                  n_heads, n_kv_heads, max_splits, scale, part, head_counter, xp_att, cls,
-                                                 NoPrefetch(), nullptr, &bt);
+                                                 NoPrefetch(), nullptr, &bt, NoPrefetch(), 1, nullptr, false, false, nullptr, false, false);
 }
 
 // After a draft tree has been verified: the accepted path's rows path[1..a] sit in cache slots

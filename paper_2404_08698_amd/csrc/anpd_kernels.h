@@ -138,7 +138,12 @@ __device__ __forceinline__ uint4 ld_stream(const uint4 *p)
 }
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t wave_buffer(const void *base)
 {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0x7fffffff, 0x00020000);
+    // (said explicitly to be the same in every lane: a base that was computed on the vector ALU - an index
+    // from an integer division, say - would otherwise make every load a loop over the distinct descriptors)
+    const unsigned long long a = (unsigned long long)base;
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)a);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(a >> 32));
+    return __builtin_amdgcn_make_buffer_rsrc((void *)(((unsigned long long)hi << 32) | lo), 0, 0x7fffffff, 0x00020000);
 }
 template <bool COH>
 __device__ __forceinline__ uint4 ld16_at(const uint4 *base, uint32_t idx)

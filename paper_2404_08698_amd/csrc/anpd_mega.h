@@ -306,9 +306,13 @@ struct MegaShared {
     };
     float rinv[32];
     int tiles_done;   // epilogues finished by this block since the kernel started
+    unsigned long long att_splits;   // the splits of its head this block's attention works on (see attention_splits)
     EpiPreLds pre[pre_tiles(NF)][NF];
     float rscratch[2048];   // group sums of the RMSNorm partials (see rinv_partial_to_lds)
-    uint4 x1[NF == 1 ? 1 : kFastWaves * NF * kChunk * 64];
+    union {
+        uint4 x1[NF == 1 ? 1 : kFastWaves * NF * kChunk * 64];
+        AttnStash stash;   // attention phase only: no GEMM operand is staged while it runs
+    };
 };
 
 template <int DH, int NF>
@@ -376,9 +380,10 @@ __device__ __forceinline__ void dma_xchunk(uint4 *dst, const uint4 *Xp, int nks,
 // phase that is chunk 1 of the operand; in a streaming phase (down projection) the chunks of the odd steps.
 // KC: k-steps per wave per item; 2 KC * 8 k-steps must cover d_model for the stationary phases (8 up to
 // d_model 4096, 10 up to 5120).
-template <int EPI, bool STATIONARY, bool BARRIER = true, int NF = 1, int KC = kChunk>
+// after_operand: called once the phase's operand has been requested.
+template <int EPI, bool STATIONARY, bool BARRIER = true, int NF = 1, int KC = kChunk, typename AfterOperand = NoPrefetch>
 __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, uint4 (&pf)[KC], MegaShared<NF> &sh,
-                                           GridBarrier &bar, int &tiles_before)
+                                           GridBarrier &bar, int &tiles_before, AfterOperand after_operand = AfterOperand())
 {
     // weight items in flight per wave, and how many steps ahead a streamed operand chunk is requested
     // kStreamLds: a streaming phase with NF > 1 passes the chunks of its odd steps through LDS and keeps a ring
@@ -463,6 +468,9 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     float nv[NF][4];
     if (late_norm) rinv_issue<true, NF>(a, nv, tid);
     else if (kNorm) compute_rinv<true>(a, sh.rinv, sh.rscratch);
+    // (requests of the caller that nothing in this phase waits for: behind the barrier's polls and this
+    // phase's operand in the queue, in front of the weights of later items only)
+    after_operand();
 
     f32x4 acc[NF];
 #pragma unroll
@@ -711,6 +719,120 @@ __device__ __forceinline__ FastArgs base_args(MegaArgsK g)
     return a;
 }
 
+// Attention tasks of a long context are unequal (splits of 1, 2 or 4 pages per wave) and every task of a
+// block costs a chain of round trips on top of its pages.  With the grid a multiple of the head count,
+// the `bins` blocks of a head share the head's splits by the longest-task-first rule: splits in decreasing
+// size (the last, partly filled one at the end) each go to the block with the least work so far.  Every
+// block works the rule out for itself; the result is the set of splits of block `bin`, one bit each.
+// bins <= 8, n_split <= 64.
+__device__ inline unsigned long long attention_splits(int n_split, int n_keys, int bins, int bin)
+{
+    unsigned long long load = 0, mine = 0;   // load: one byte per bin
+    for (int i = 0; i < n_split; ++i) {
+        const int s = i + 1 < n_split ? n_split - 2 - i : n_split - 1;
+        int pages = split_pages(s);
+        if (s == n_split - 1) pages = min(pages, (n_keys - split_begin(s) + 16 * kFastWaves - 1) / (16 * kFastWaves));
+        int best = 0;
+        unsigned least = (unsigned)load & 0xffu;
+        for (int b = 1; b < bins; ++b) {
+            const unsigned v = (unsigned)(load >> (8 * b)) & 0xffu;
+            if (v < least) { least = v; best = b; }
+        }
+        load += (unsigned long long)(pages + 2) << (8 * best);   // + 2: the task's fixed cost, in pages' worth
+        if (best == bin) mine |= 1ull << s;
+    }
+    return mine;
+}
+__device__ inline bool attention_shares_heads(int grid, int n_heads, int n_split)
+{
+    return grid % n_heads == 0 && grid / n_heads <= 8 && n_split <= 64;
+}
+
+// An attention task: (head, split) and the cache it works on.
+struct AttTask {
+    int head, split, L, rows, row0;
+    const bf16_t *pool;
+    const int32_t *table;
+};
+// Task t of the list that the blocks share out by turns: the last splits of a long context are the large
+// ones and go first.  Several sequences: tasks run sequence by sequence, every sequence has a multiple of
+// n_heads of them.
+template <bool BATCH>
+__device__ __forceinline__ AttTask attention_task(MegaArgsK g, int L, int t)
+{
+    const int n_heads = g->n_heads;
+    AttTask k;
+    if (BATCH) {
+        int s = 0;
+        while (s + 1 < g->n_seq && t >= g->task0[s + 1]) ++s;
+        const int local = t - g->task0[s];
+        k.L = *g->seqs[s].len_ptr;
+        k.rows = g->seqs[s].n_rows;
+        k.head = local % n_heads;
+        k.split = n_splits_of(k.L + k.rows) - 1 - local / n_heads;
+        k.row0 = g->seqs[s].row0;
+        k.pool = g->seqs[s].pool;
+        k.table = g->seqs[s].page_table;
+    } else {
+        k.head = t % n_heads;
+        k.split = n_splits_of(L + g->M) - 1 - t / n_heads;
+        k.L = L;
+        k.rows = g->M;
+        k.row0 = 0;
+        k.pool = g->pool;
+        k.table = g->page_table;
+    }
+    return k;
+}
+// The block's tasks in the order it runs them.  With the grid a multiple of the head count: the splits of
+// head blockIdx.x % n_heads that attention_splits gave it (todo: one bit per split); otherwise every grid-th
+// task of the list (t).
+template <bool BATCH>
+struct AttQueue {
+    bool shared_heads;
+    unsigned long long todo;
+    int t, n_tasks, grid, last_split;
+    __device__ __forceinline__ AttQueue(MegaArgsK g, int L, int grid_, unsigned long long splits_in_lds)
+    {
+        const int n_split = n_splits_of(L + g->M);
+        last_split = n_split - 1;
+        grid = grid_;
+        n_tasks = BATCH ? g->task0[g->n_seq] : g->n_heads * n_split;
+        shared_heads = !BATCH && attention_shares_heads(grid, g->n_heads, n_split);
+        todo = 0ull;
+        if (shared_heads)   // (read from LDS; said to be the same in every lane, so that what follows stays scalar)
+            todo = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(splits_in_lds >> 32)) << 32) |
+                   (unsigned)__builtin_amdgcn_readfirstlane((int)splits_in_lds);
+        t = blockIdx.x;
+    }
+    __device__ __forceinline__ bool have() const { return shared_heads ? todo != 0 : t < n_tasks; }
+    __device__ __forceinline__ AttTask current(MegaArgsK g, int L) const
+    {
+        if (!shared_heads) return attention_task<BATCH>(g, L, t);
+        AttTask k;
+        k.head = blockIdx.x % g->n_heads;
+        k.split = pick();
+        k.L = L;
+        k.rows = g->M;
+        k.row0 = 0;
+        k.pool = g->pool;
+        k.table = g->page_table;
+        return k;
+    }
+    // large splits first; the last split of the context (partly filled, and the one that holds this step's own
+    // rows) at the end: the block's first task is the one whose pages are requested ahead of time
+    __device__ __forceinline__ int pick() const
+    {
+        const unsigned long long body = todo & ~(1ull << last_split);
+        return 63 - __builtin_clzll(body ? body : todo);
+    }
+    __device__ __forceinline__ void advance()
+    {
+        if (shared_heads) todo &= ~(1ull << pick());
+        else t += grid;
+    }
+};
+
 // MODE 1 (tree): the window is a draft tree (see MegaArgs::parent): rotary positions by depth, attention
 // over ancestors only, acceptance along the paths.  MODE 2 (batch): the window holds several sequences
 // side by side (MegaArgs::seqs): cache, length and position per row, attention per sequence, acceptance
@@ -721,6 +843,8 @@ template <int DH, int MODE = MEGA_CHAIN, int NF = 1, int KC = kChunk>
 __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* read through phase_args() */)
 {
     constexpr bool TREE = MODE == MEGA_TREE, BATCH = MODE == MEGA_BATCH;
+    // LDS holds nothing else during the QKV phase when the activation operand stays in registers (NF = 1)
+    constexpr bool kParkEarly = NF == 1;
     __shared__ MegaShared<NF> sh;
     __shared__ float bval[kFastWaves];
     __shared__ int bidx[kFastWaves];
@@ -733,9 +857,15 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
         MegaArgsK g = phase_args();
         bar_init(bar, g);
         bar_stamp(bar);
-        if (threadIdx.x == 0) sh.tiles_done = 0;   // ordered by the first block barrier below
-        L = BATCH ? 0 : *g->len_ptr;
+        L = BATCH ? 0 : __builtin_amdgcn_readfirstlane(*g->len_ptr);   // (scalar: split and page indices derive from it)
         n_layers = g->n_layers;
+        if (threadIdx.x == 0) {   // ordered by the first block barrier below
+            sh.tiles_done = 0;
+            const int n_split = n_splits_of(L + g->M);
+            sh.att_splits = !BATCH && attention_shares_heads(grid, g->n_heads, n_split)
+                                ? attention_splits(n_split, L + g->M, grid / g->n_heads, blockIdx.x / g->n_heads)
+                                : 0ull;
+        }
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
         const int d = g->d;
         const LayerW w0 = layer_weights(g, 0);
@@ -767,8 +897,22 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
                 a.seqs = (const SeqRef *)g->seqs;
                 a.row_seq = (const int32_t *)g->row_seq;
             }
+            // Pages 1 and 2 of this block's first attention task go from memory straight into LDS while the
+            // QKV weights stream: they lie below the committed length, so they do not depend on this step.
+            auto park = [&]() {
+                if (!kParkEarly) return;
+                AttQueue<BATCH> queue(g, L, grid, sh.att_splits);
+                if (queue.have()) {
+                    const AttTask k = queue.current(g, L);
+                    const int np = split_pages(k.split), kvh = k.head / (g->n_heads / g->n_kv_heads);
+                    const AttnPageIds ids = attn_page_ids(k.split, k.L, k.rows, k.table);
+                    if (np > 1) attn_park<DH>(sh.stash, 0, kvh, k.split, k.L, k.pool, k.table, l, n_layers, g->n_kv_heads, 1, &ids);
+                    if (np > 2) attn_park<DH>(sh.stash, 1, kvh, k.split, k.L, k.pool, k.table, l, n_layers, g->n_kv_heads, 2, &ids);
+                }
+            };
             WSrc none = {w.o, nks_d, 0};   // the O tile is fetched from inside the attention phase
-            gemm_phase<BATCH ? EPI_QKV_BATCH : (TREE ? EPI_QKV_TREE : EPI_QKV), true, false, NF, KC>(a, none, pf, sh, bar, tiles_before);
+            gemm_phase<BATCH ? EPI_QKV_BATCH : (TREE ? EPI_QKV_TREE : EPI_QKV), true, false, NF, KC, decltype(park)>(a, none, pf, sh, bar,
+                                                                                                                      tiles_before, park);
         }
         {   // attention: (head, split) tasks - per sequence when the step holds several; the O weights stream
             // in meanwhile.  Cache pages wholly below the committed length do not depend on this step: the
@@ -779,43 +923,32 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             const int lane = tid & 63, wave = tid >> 6;
             const int M = g->M, n_heads = g->n_heads;
             const int grp = n_heads / g->n_kv_heads;
-            const int n_tasks = BATCH ? g->task0[g->n_seq] : n_heads * ((L + M + kFastSplit - 1) / kFastSplit);
-            // task -> (head, split) and the cache it works on.  Several sequences: tasks run sequence by
-            // sequence, every sequence has a multiple of n_heads of them
-            struct Task {
-                int head, split, L, rows, row0;
-                const bf16_t *pool;
-                const int32_t *table;
-            };
-            auto locate = [&](int t) {
-                Task k;
-                if (BATCH) {
-                    int s = 0;
-                    while (s + 1 < g->n_seq && t >= g->task0[s + 1]) ++s;
-                    const int local = t - g->task0[s];
-                    k.head = local % n_heads;
-                    k.split = local / n_heads;
-                    k.L = *g->seqs[s].len_ptr;
-                    k.rows = g->seqs[s].n_rows;
-                    k.row0 = g->seqs[s].row0;
-                    k.pool = g->seqs[s].pool;
-                    k.table = g->seqs[s].page_table;
-                } else {
-                    k.head = t % n_heads;
-                    k.split = t / n_heads;
-                    k.L = L;
-                    k.rows = M;
-                    k.row0 = 0;
-                    k.pool = g->pool;
-                    k.table = g->page_table;
-                }
-                return k;
-            };
+            typedef AttTask Task;
+            AttQueue<BATCH> queue(g, L, grid, sh.att_splits);
+            const int n_tasks = queue.n_tasks;
+            auto have = [&]() { return queue.have(); };
+            auto current = [&]() { return queue.current(g, L); };
+            auto advance = [&]() { queue.advance(); };
+            // the first task's pages: page 0 is requested into registers now; pages 1 and 2 are parked in LDS,
+            // since the start of the QKV phase where LDS was free then (kParkEarly), else from now
             AttnKV<DH> kv;
             kv.loaded = false;
-            if ((int)blockIdx.x < n_tasks) {
-                const Task k = locate(blockIdx.x);
-                attn_load_kv<DH, true>(kv, k.head / grp, k.split, k.L, k.rows, k.pool, k.table, l, n_layers, g->n_kv_heads, true);
+            bool stashed1 = false, stashed2 = false, q_in_lds = false;
+            // (the RMSNorm scratch is idle between the QKV and the gate / up phase: room for the query rows)
+            static_assert(sizeof(sh.rscratch) >= (DH / 32) * 64 * sizeof(uint4), "query rows of one row group");
+            uint4 *const q_lds = reinterpret_cast<uint4 *>(sh.rscratch);
+            if (have()) {
+                const Task k = current();
+                const int np = split_pages(k.split);
+                const AttnPageIds ids = attn_page_ids(k.split, k.L, k.rows, k.table);
+                attn_load_kv<DH, true>(kv, k.head / grp, k.split, k.L, k.rows, k.pool, k.table, l, n_layers, g->n_kv_heads, true, 0, &ids);
+                if (kParkEarly) {
+                    stashed1 = np > 1 && attn_parks(k.split, k.L, wave, 1);
+                    stashed2 = np > 2 && attn_parks(k.split, k.L, wave, 2);
+                } else {
+                    if (np > 1) stashed1 = attn_park<DH>(sh.stash, 0, k.head / grp, k.split, k.L, k.pool, k.table, l, n_layers, g->n_kv_heads, 1, &ids);
+                    if (np > 2) stashed2 = attn_park<DH>(sh.stash, 1, k.head / grp, k.split, k.L, k.pool, k.table, l, n_layers, g->n_kv_heads, 2, &ids);
+                }
             }
             // No grid barrier here: a task needs the q / k / v tiles of its own head only, and every
             // block still arrives at the barrier that ends this phase after its QKV tiles, which is
@@ -823,8 +956,11 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             if (tid == 0) {
                 const uint32_t target = (uint32_t)(3 * g->head_dim / 16) * (g->ready_epoch + (uint32_t)l + 1u);
                 // (with the grid a multiple of the head count all of a block's tasks wait for the same head)
-                const int t_end = grid % n_heads == 0 ? ((int)blockIdx.x < n_tasks ? (int)blockIdx.x + 1 : 0) : n_tasks;
-                for (int t = blockIdx.x; t < t_end; t += grid) wait_count(bar, g->qkv_ready + kCounterStride * (t % n_heads), target);
+                if (grid % n_heads == 0) {
+                    if (have()) wait_count(bar, g->qkv_ready + kCounterStride * ((int)blockIdx.x % n_heads), target);
+                } else {
+                    for (int tt = blockIdx.x; tt < n_tasks; tt += grid) wait_count(bar, g->qkv_ready + kCounterStride * (tt % n_heads), target);
+                }
             }
             block_sync_lds();
             bar_stamp(bar);
@@ -838,26 +974,46 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             // reported to the head's counter together, by the last one
             const bool one_head = grid % n_heads == 0;
             int unreported = 0;
-            for (int t = blockIdx.x; t < n_tasks; t += grid) {
-                const Task k = locate(t);
+            while (have()) {
+                const Task k = current();
+                advance();
                 unreported += 1;
-                const int publish = (!one_head || t + grid >= n_tasks) ? unreported : 0;
+                const int publish = (!one_head || !have()) ? unreported : 0;
                 if (publish) unreported = 0;
                 // a block with several tasks (long contexts) requests the next task's page as soon as this
                 // task has used its own: every wait for the block's counters is over by now
-                const int tn = t + grid;
+                // (and its further pages into the LDS slots this task has finished with)
+                // The next task's page table entries are asked for now and read then: asked for then, they would
+                // come back behind everything this task requests in between.
+                bool next1 = false, next2 = false;
+                AttnPageIds next_ids = {};
+                if (have()) {
+                    const Task k2 = current();
+                    next_ids = attn_page_ids(k2.split, k2.L, k2.rows, k2.table);
+                }
                 auto next_page = [&]() {
-                    if (tn < n_tasks) {
-                        const Task k2 = locate(tn);
+                    if (have()) {
+                        const Task k2 = current();
+                        const int np = split_pages(k2.split);
                         attn_load_kv<DH, true>(kv, k2.head / grp, k2.split, k2.L, k2.rows, k2.pool, k2.table, l, n_layers, g->n_kv_heads,
-                                               false);
+                                               false, 0, &next_ids);
+                        if (np > 1)
+                            next1 = attn_park<DH>(sh.stash, 0, k2.head / grp, k2.split, k2.L, k2.pool, k2.table, l, n_layers, g->n_kv_heads, 1,
+                                                  &next_ids);
+                        if (np > 2)
+                            next2 = attn_park<DH>(sh.stash, 1, k2.head / grp, k2.split, k2.L, k2.pool, k2.table, l, n_layers, g->n_kv_heads, 2,
+                                                  &next_ids);
                     }
                 };
                 AttnBatch bt = {k.row0, k.rows, g->n_att_blocks, (const SeqRef *)g->seqs, (const int32_t *)g->row_seq};
                 attn_task<DH, true, decltype(prefetch_o), BATCH ? ATTN_BATCH : (TREE ? ATTN_TREE : ATTN_CHAIN), decltype(next_page)>(
                     attn_shared<DH>(sh), kv, k.head, k.split, k.L, (const uint4 *)g->qp, k.pool, k.table, M, l, n_layers, n_heads,
                     g->n_kv_heads, g->max_splits, g->scale, g->part, g->head_counter, x_operand(g, l, 1), packed_class(NF), prefetch_o,
-                    TREE ? (const uint32_t *)g->mask : nullptr, BATCH ? &bt : nullptr, next_page, publish);
+                    TREE ? (const uint32_t *)g->mask : nullptr, BATCH ? &bt : nullptr, next_page, publish, &sh.stash, stashed1,
+                    stashed2, q_lds, q_in_lds, have());
+                stashed1 = next1;
+                stashed2 = next2;
+                q_in_lds = one_head && !BATCH;   // (the block's later tasks: same head, same rows)
                 block_sync_lds();
             }
             prefetch_o();
