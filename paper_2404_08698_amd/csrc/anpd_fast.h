@@ -735,9 +735,8 @@ __global__ __launch_bounds__(256) void split_packed_kernel(const float *__restri
 typedef short bf16x4s __attribute__((ext_vector_type(4)));
 
 // Window-causal attention on the matrix cores.  The key positions are cut into splits at fixed absolute
-// positions: 4 splits of 128 keys, then 2 of 256, then splits of 384 (split_begin).  A block works on one
-// (head, split); wave w takes the 16-token pages w, w + 8, ... of the split (1, 2 or 3 pages), one after
-// the other.  Per group of 8 window rows and per page: S = K q^T with the query as a split-bf16 B operand
+// positions: 8 splits of 128 keys, then splits of 384 (split_begin).  A block works on one (head, split);
+// wave w takes the 16-token pages w, w + 8, ... of the split (1 or 3 pages), one after the other.  Per group of 8 window rows and per page: S = K q^T with the query as a split-bf16 B operand
 // (scores land with keys in registers and rows across lanes), P as a split-bf16 B operand straight from
 // those registers, O += V^T P in the matrix cores' accumulators; the wave keeps a running (maximum,
 // denominator, output) over its pages and rescales it when a page raises the maximum - no exchange with
@@ -745,27 +744,27 @@ typedef short bf16x4s __attribute__((ext_vector_type(4)));
 // result to the block maximum and the tiles are added in a fixed order.  Each block stores (o, max,
 // denominator) of its split; the last block of a head to finish merges the head's splits in increasing
 // order and writes the packed operand of the output projection.  Short contexts get many small tasks (one
-// page per wave, nothing sequential), long ones fewer and larger ones (15 per head at 4096 positions, where
+// page per wave, nothing sequential), long ones fewer and larger ones (17 per head at 4096 positions, where
 // splits of 128 gave 33): a task costs a chain of round trips - query rows, reduction, stores, counter -
 // whatever its size.  The cut depends on absolute key positions only, so a row's sums do not depend on the
 // window size, on how a prompt was cut into pieces or on the cache's capacity.
 // Scores are kept in the base-2 domain (scaled by log2 e) so that every exponential is one v_exp_f32.
 // Row r sees keys 0..len + r; keys it must not see get weight exactly 0.
 constexpr int kFastPages = 3;   // most pages per wave per task
+constexpr int kSmallSplits = 8;   // splits of one page per wave: the first 1024 positions
 __host__ __device__ constexpr int split_begin(int s)
 {
-    return s <= 4 ? s * 128 : s <= 6 ? 512 + (s - 4) * 256 : 1024 + (s - 6) * 384;
+    return s <= kSmallSplits ? s * 128 : 128 * kSmallSplits + (s - kSmallSplits) * 128 * kFastPages;
 }
-__host__ __device__ constexpr int split_pages(int s) { return s < 4 ? 1 : s < 6 ? 2 : kFastPages; }   // per wave
+__host__ __device__ constexpr int split_pages(int s) { return s < kSmallSplits ? 1 : kFastPages; }   // per wave
 __host__ __device__ constexpr int split_of(int key)
 {
-    return key < 512 ? key >> 7 : key < 1024 ? 4 + ((key - 512) >> 8) : 6 + (key - 1024) / 384;
+    return key < 128 * kSmallSplits ? key >> 7 : kSmallSplits + (key - 128 * kSmallSplits) / (128 * kFastPages);
 }
 // number of splits that hold at least one of the keys 0 .. n_keys - 1
 __host__ __device__ constexpr int n_splits_of(int n_keys) { return n_keys <= 0 ? 0 : split_of(n_keys - 1) + 1; }
-static_assert(split_begin(4) == 512 && split_begin(6) == 1024 && split_of(511) == 3 && split_of(512) == 4 &&
-              split_of(1023) == 5 && split_of(1024) == 6 && split_of(split_begin(9)) == 9 && split_of(split_begin(9) - 1) == 8 &&
-              split_begin(10) - split_begin(9) == 16 * kFastWaves * kFastPages,
+static_assert(split_begin(8) == 1024 && split_begin(9) == 1408 && split_of(1023) == 7 && split_of(1024) == 8 &&
+              split_of(1407) == 8 && split_of(1408) == 9 && split_of(split_begin(12)) == 12 && split_of(split_begin(12) - 1) == 11,
               "cut of the key positions");
 // uint32 words between per-head counters: one 256-byte line each.  Atomics of different heads on one
 // line serialise at the memory side (measured with polled counters: +16 % step time when packed).
@@ -1024,8 +1023,7 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
                 sc[i] = ok ? v : kMasked;
                 mx = fmaxf(mx, sc[i]);
             }
-            mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+            mx = rows_max(mx);
             // ---- the page's exponentials against the new running maximum
             const float m_new = fmaxf(m_run, mx);
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
@@ -1035,9 +1033,7 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
                 p[i] = sc[i] > 0.5f * kMasked ? __builtin_amdgcn_exp2f(sc[i] - m_new) : 0.f;
                 den += p[i];
             }
-            den += __shfl_xor(den, 16, kWave);
-            den += __shfl_xor(den, 32, kWave);
-            d_run = fmaf(d_run, alpha, den);
+            d_run = fmaf(d_run, alpha, den);   // (this lane's four keys of every page; the lanes' sums meet after the pages)
             m_run = m_new;
             // ---- what the wave has so far is rescaled only if some row's maximum went up (whole-wave
             // branch; a factor of exactly 1 changes nothing, so the result does not depend on it)
@@ -1081,6 +1077,7 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
         if (loads_late && rg == rg0) after_loads();
         ANPD_STAMP(1);
         // ---- the waves' maxima meet; every wave scales its result to the block maximum
+        d_run = rows_sum(d_run);
         if (kg == 0 && slot < 8) sh.wmax[wave][slot] = m_run;
         block_sync_lds();
         float bm = sh.wmax[0][slot & 7];

@@ -194,6 +194,25 @@ __device__ __forceinline__ float row_up8(float v)
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x118, 0xF, 0xF, true));
 }
 
+// Maximum / sum over the four lanes l, l ^ 16, l ^ 32, l ^ 48 (one lane of each row of 16), the same value in
+// all four: two row swaps on the vector ALU (v_permlane16_swap exchanges the odd rows of its first operand
+// with the even rows of its second, v_permlane32_swap the upper half with the lower half), no trip through
+// LDS.  The sum adds in the order of the xor-16, xor-32 butterfly.
+__device__ __forceinline__ float rows_max(float v)
+{
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float rows_sum(float v)
+{
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll

@@ -306,7 +306,6 @@ struct MegaShared {
     };
     float rinv[32];
     int tiles_done;   // epilogues finished by this block since the kernel started
-    unsigned long long att_splits;   // the splits of its head this block's attention works on (see attention_splits)
     EpiPreLds pre[pre_tiles(NF)][NF];
     float rscratch[2048];   // group sums of the RMSNorm partials (see rinv_partial_to_lds)
     union {
@@ -380,10 +379,9 @@ __device__ __forceinline__ void dma_xchunk(uint4 *dst, const uint4 *Xp, int nks,
 // phase that is chunk 1 of the operand; in a streaming phase (down projection) the chunks of the odd steps.
 // KC: k-steps per wave per item; 2 KC * 8 k-steps must cover d_model for the stationary phases (8 up to
 // d_model 4096, 10 up to 5120).
-// after_operand: called once the phase's operand has been requested.
-template <int EPI, bool STATIONARY, bool BARRIER = true, int NF = 1, int KC = kChunk, typename AfterOperand = NoPrefetch>
+template <int EPI, bool STATIONARY, bool BARRIER = true, int NF = 1, int KC = kChunk>
 __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, uint4 (&pf)[KC], MegaShared<NF> &sh,
-                                           GridBarrier &bar, int &tiles_before, AfterOperand after_operand = AfterOperand())
+                                           GridBarrier &bar, int &tiles_before)
 {
     // weight items in flight per wave, and how many steps ahead a streamed operand chunk is requested
     // kStreamLds: a streaming phase with NF > 1 passes the chunks of its odd steps through LDS and keeps a ring
@@ -455,8 +453,7 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     // weights of later steps (a wave's loads return in order).
     const int n_steps = my_tiles * n_chunks;
     uint4 *const x1_lds = sh.x1 + (kX1Lds ? wave * NF * KC * 64 : 0);
-    // (chunk 1 is requested first: once chunk 0 has arrived in registers - the loop below is entered with
-    // it - chunk 1 is in LDS as well, because a wave's loads complete in order)
+    // (chunk 1 goes straight into LDS; the block's first step waits for it, see do_step)
     if (kX1Lds) dma_xchunk<NF, KC>(x1_lds, a.Xp, a.nks, STATIONARY ? 1 : 1 % n_chunks, wave, lane, STATIONARY || 1 < n_steps);
     load_xchunk<NF, KC>(x0, a.Xp, a.nks, 0, wave, lane);
     if (!kX1Lds && XLOOK == 2 && (STATIONARY || 1 < n_steps))
@@ -468,9 +465,6 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
     float nv[NF][4];
     if (late_norm) rinv_issue<true, NF>(a, nv, tid);
     else if (kNorm) compute_rinv<true>(a, sh.rinv, sh.rscratch);
-    // (requests of the caller that nothing in this phase waits for: behind the barrier's polls and this
-    // phase's operand in the queue, in front of the weights of later items only)
-    after_operand();
 
     f32x4 acc[NF];
 #pragma unroll
@@ -527,12 +521,13 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
                     mfma_reg(buf, x0);
                 }
             } else if (kX1Lds && from_lds) {
-                // The chunk was requested into LDS two steps ago (or on entry), and since then this wave has
-                // issued the weights of one item, the operand chunk of the step in between and the weights of
-                // another item - NF * KC + 2 * KC loads, every one of them on every path.  A wave's loads complete
-                // in order, so once at most that many are outstanding the chunk is in LDS.  (The reads below are
-                // assembly the compiler does not connect with that request.)
-                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NF * KC + 2 * KC) : "memory");
+                // The chunk was requested into LDS two steps ago (or on entry).  The reads below are assembly the
+                // compiler does not connect with that request, and it places the requests into LDS among the
+                // register loads around them as it sees fit: counting the loads that the source issues after the
+                // request proves nothing (it let a step read a fragment before it had arrived, one tile in some
+                // ten thousand).  So the wait is for everything this wave has requested, the next step's weights
+                // and operand included.
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 mfma_lds(buf);
             } else {
                 mfma_reg(buf, xs);
@@ -543,6 +538,14 @@ __device__ __forceinline__ void gemm_phase(const FastArgs &a, const WSrc &next, 
                 dma_xchunk<NF, KC>(x1_lds, a.Xp, a.nks, (step + XLOOK) % n_chunks, wave, lane, active && step + XLOOK < n_steps);
             else
                 load_xchunk<NF, KC>(xs, a.Xp, a.nks, (step + XLOOK) % n_chunks, wave, lane, active && step + XLOOK < n_steps);
+        }
+        if constexpr (STATIONARY && kX1Lds) {
+            // Chunk 1 of the operand was requested into LDS when the phase began and is first read in the block's
+            // second step.  That the source requests it before chunk 0, which has arrived, proves nothing (see
+            // below: the compiler interleaves the two): wait here, before this step's refill goes out, when all
+            // that is outstanding besides it are the weights of the next two steps and the norm's partial sums -
+            // all of it needed in a moment anyway.
+            if (step == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
         if (!keep) fetch(buf, false);
         if (active) {
@@ -719,35 +722,6 @@ __device__ __forceinline__ FastArgs base_args(MegaArgsK g)
     return a;
 }
 
-// Attention tasks of a long context are unequal (splits of 1, 2 or 4 pages per wave) and every task of a
-// block costs a chain of round trips on top of its pages.  With the grid a multiple of the head count,
-// the `bins` blocks of a head share the head's splits by the longest-task-first rule: splits in decreasing
-// size (the last, partly filled one at the end) each go to the block with the least work so far.  Every
-// block works the rule out for itself; the result is the set of splits of block `bin`, one bit each.
-// bins <= 8, n_split <= 64.
-__device__ inline unsigned long long attention_splits(int n_split, int n_keys, int bins, int bin)
-{
-    unsigned long long load = 0, mine = 0;   // load: one byte per bin
-    for (int i = 0; i < n_split; ++i) {
-        const int s = i + 1 < n_split ? n_split - 2 - i : n_split - 1;
-        int pages = split_pages(s);
-        if (s == n_split - 1) pages = min(pages, (n_keys - split_begin(s) + 16 * kFastWaves - 1) / (16 * kFastWaves));
-        int best = 0;
-        unsigned least = (unsigned)load & 0xffu;
-        for (int b = 1; b < bins; ++b) {
-            const unsigned v = (unsigned)(load >> (8 * b)) & 0xffu;
-            if (v < least) { least = v; best = b; }
-        }
-        load += (unsigned long long)(pages + 2) << (8 * best);   // + 2: the task's fixed cost, in pages' worth
-        if (best == bin) mine |= 1ull << s;
-    }
-    return mine;
-}
-__device__ inline bool attention_shares_heads(int grid, int n_heads, int n_split)
-{
-    return grid % n_heads == 0 && grid / n_heads <= 8 && n_split <= 64;
-}
-
 // An attention task: (head, split) and the cache it works on.
 struct AttTask {
     int head, split, L, rows, row0;
@@ -784,53 +758,21 @@ __device__ __forceinline__ AttTask attention_task(MegaArgsK g, int L, int t)
     }
     return k;
 }
-// The block's tasks in the order it runs them.  With the grid a multiple of the head count: the splits of
-// head blockIdx.x % n_heads that attention_splits gave it (todo: one bit per split); otherwise every grid-th
-// task of the list (t).
+// The block's tasks in the order it runs them: every grid-th task of the list.  (Sharing a head's splits out
+// among its blocks by size, longest first, was measured slower at every length: 2.62 against 2.60 ms per step
+// at 512 positions, 3.25 against 3.18 at 4096, 7B shape.)
 template <bool BATCH>
 struct AttQueue {
-    bool shared_heads;
-    unsigned long long todo;
-    int t, n_tasks, grid, last_split;
-    __device__ __forceinline__ AttQueue(MegaArgsK g, int L, int grid_, unsigned long long splits_in_lds)
+    int t, n_tasks, grid;
+    __device__ __forceinline__ AttQueue(MegaArgsK g, int L, int grid_)
     {
-        const int n_split = n_splits_of(L + g->M);
-        last_split = n_split - 1;
         grid = grid_;
-        n_tasks = BATCH ? g->task0[g->n_seq] : g->n_heads * n_split;
-        shared_heads = !BATCH && attention_shares_heads(grid, g->n_heads, n_split);
-        todo = 0ull;
-        if (shared_heads)   // (read from LDS; said to be the same in every lane, so that what follows stays scalar)
-            todo = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(splits_in_lds >> 32)) << 32) |
-                   (unsigned)__builtin_amdgcn_readfirstlane((int)splits_in_lds);
+        n_tasks = BATCH ? g->task0[g->n_seq] : g->n_heads * n_splits_of(L + g->M);
         t = blockIdx.x;
     }
-    __device__ __forceinline__ bool have() const { return shared_heads ? todo != 0 : t < n_tasks; }
-    __device__ __forceinline__ AttTask current(MegaArgsK g, int L) const
-    {
-        if (!shared_heads) return attention_task<BATCH>(g, L, t);
-        AttTask k;
-        k.head = blockIdx.x % g->n_heads;
-        k.split = pick();
-        k.L = L;
-        k.rows = g->M;
-        k.row0 = 0;
-        k.pool = g->pool;
-        k.table = g->page_table;
-        return k;
-    }
-    // large splits first; the last split of the context (partly filled, and the one that holds this step's own
-    // rows) at the end: the block's first task is the one whose pages are requested ahead of time
-    __device__ __forceinline__ int pick() const
-    {
-        const unsigned long long body = todo & ~(1ull << last_split);
-        return 63 - __builtin_clzll(body ? body : todo);
-    }
-    __device__ __forceinline__ void advance()
-    {
-        if (shared_heads) todo &= ~(1ull << pick());
-        else t += grid;
-    }
+    __device__ __forceinline__ bool have() const { return t < n_tasks; }
+    __device__ __forceinline__ AttTask current(MegaArgsK g, int L) const { return attention_task<BATCH>(g, L, t); }
+    __device__ __forceinline__ void advance() { t += grid; }
 };
 
 // MODE 1 (tree): the window is a draft tree (see MegaArgs::parent): rotary positions by depth, attention
@@ -843,8 +785,6 @@ template <int DH, int MODE = MEGA_CHAIN, int NF = 1, int KC = kChunk>
 __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* read through phase_args() */)
 {
     constexpr bool TREE = MODE == MEGA_TREE, BATCH = MODE == MEGA_BATCH;
-    // LDS holds nothing else during the QKV phase when the activation operand stays in registers (NF = 1)
-    constexpr bool kParkEarly = NF == 1;
     __shared__ MegaShared<NF> sh;
     __shared__ float bval[kFastWaves];
     __shared__ int bidx[kFastWaves];
@@ -859,13 +799,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
         bar_stamp(bar);
         L = BATCH ? 0 : __builtin_amdgcn_readfirstlane(*g->len_ptr);   // (scalar: split and page indices derive from it)
         n_layers = g->n_layers;
-        if (threadIdx.x == 0) {   // ordered by the first block barrier below
-            sh.tiles_done = 0;
-            const int n_split = n_splits_of(L + g->M);
-            sh.att_splits = !BATCH && attention_shares_heads(grid, g->n_heads, n_split)
-                                ? attention_splits(n_split, L + g->M, grid / g->n_heads, blockIdx.x / g->n_heads)
-                                : 0ull;
-        }
+        if (threadIdx.x == 0) sh.tiles_done = 0;   // ordered by the first block barrier below
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
         const int d = g->d;
         const LayerW w0 = layer_weights(g, 0);
@@ -897,22 +831,8 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
                 a.seqs = (const SeqRef *)g->seqs;
                 a.row_seq = (const int32_t *)g->row_seq;
             }
-            // Pages 1 and 2 of this block's first attention task go from memory straight into LDS while the
-            // QKV weights stream: they lie below the committed length, so they do not depend on this step.
-            auto park = [&]() {
-                if (!kParkEarly) return;
-                AttQueue<BATCH> queue(g, L, grid, sh.att_splits);
-                if (queue.have()) {
-                    const AttTask k = queue.current(g, L);
-                    const int np = split_pages(k.split), kvh = k.head / (g->n_heads / g->n_kv_heads);
-                    const AttnPageIds ids = attn_page_ids(k.split, k.L, k.rows, k.table);
-                    if (np > 1) attn_park<DH>(sh.stash, 0, kvh, k.split, k.L, k.pool, k.table, l, n_layers, g->n_kv_heads, 1, &ids);
-                    if (np > 2) attn_park<DH>(sh.stash, 1, kvh, k.split, k.L, k.pool, k.table, l, n_layers, g->n_kv_heads, 2, &ids);
-                }
-            };
-            WSrc none = {w.o, nks_d, 0};   // the O tile is fetched from inside the attention phase
-            gemm_phase<BATCH ? EPI_QKV_BATCH : (TREE ? EPI_QKV_TREE : EPI_QKV), true, false, NF, KC, decltype(park)>(a, none, pf, sh, bar,
-                                                                                                                      tiles_before, park);
+            WSrc none = {w.o, nks_d, 0};   // the O tile is requested by the attention phase
+            gemm_phase<BATCH ? EPI_QKV_BATCH : (TREE ? EPI_QKV_TREE : EPI_QKV), true, false, NF, KC>(a, none, pf, sh, bar, tiles_before);
         }
         {   // attention: (head, split) tasks - per sequence when the step holds several; the O weights stream
             // in meanwhile.  Cache pages wholly below the committed length do not depend on this step: the
@@ -924,13 +844,14 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             const int M = g->M, n_heads = g->n_heads;
             const int grp = n_heads / g->n_kv_heads;
             typedef AttTask Task;
-            AttQueue<BATCH> queue(g, L, grid, sh.att_splits);
+            AttQueue<BATCH> queue(g, L, grid);
             const int n_tasks = queue.n_tasks;
             auto have = [&]() { return queue.have(); };
             auto current = [&]() { return queue.current(g, L); };
             auto advance = [&]() { queue.advance(); };
-            // the first task's pages: page 0 is requested into registers now; pages 1 and 2 are parked in LDS,
-            // since the start of the QKV phase where LDS was free then (kParkEarly), else from now
+            // the first task's pages are requested now, during the wait for the head: page 0 into registers, pages 1
+            // and 2 into LDS.  (Requested when the QKV phase starts instead, the pages cost that phase more than
+            // they save this one: 7B shape, 3.266 against 3.248 ms per step at 4096 positions, 2.627 against 2.618 at 512.)
             AttnKV<DH> kv;
             kv.loaded = false;
             bool stashed1 = false, stashed2 = false, q_in_lds = false;
@@ -942,14 +863,15 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
                 const int np = split_pages(k.split);
                 const AttnPageIds ids = attn_page_ids(k.split, k.L, k.rows, k.table);
                 attn_load_kv<DH, true>(kv, k.head / grp, k.split, k.L, k.rows, k.pool, k.table, l, n_layers, g->n_kv_heads, true, 0, &ids);
-                if (kParkEarly) {
-                    stashed1 = np > 1 && attn_parks(k.split, k.L, wave, 1);
-                    stashed2 = np > 2 && attn_parks(k.split, k.L, wave, 2);
-                } else {
-                    if (np > 1) stashed1 = attn_park<DH>(sh.stash, 0, k.head / grp, k.split, k.L, k.pool, k.table, l, n_layers, g->n_kv_heads, 1, &ids);
-                    if (np > 2) stashed2 = attn_park<DH>(sh.stash, 1, k.head / grp, k.split, k.L, k.pool, k.table, l, n_layers, g->n_kv_heads, 2, &ids);
-                }
+                if (np > 1) stashed1 = attn_park<DH>(sh.stash, 0, k.head / grp, k.split, k.L, k.pool, k.table, l, n_layers, g->n_kv_heads, 1, &ids);
+                if (np > 2) stashed2 = attn_park<DH>(sh.stash, 1, k.head / grp, k.split, k.L, k.pool, k.table, l, n_layers, g->n_kv_heads, 2, &ids);
             }
+            // The first O tile's weights go out now, behind the pages: requested inside the tasks they would
+            // either queue in front of a task's own loads or still be in flight when the task waits for its
+            // stores (one counter covers a wave's loads and stores).  The wait for the head below is longer
+            // than their way from memory.
+            const WSrc o_src = {w.o, (g->d + 31) / 32, g->d / 16};
+            load_wchunk<KC>(pf, o_src, first_tile(o_src), 0, wave, lane);
             // No grid barrier here: a task needs the q / k / v tiles of its own head only, and every
             // block still arrives at the barrier that ends this phase after its QKV tiles, which is
             // what the O phase waits for.
@@ -964,12 +886,7 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
             }
             block_sync_lds();
             bar_stamp(bar);
-            const WSrc o_src = {w.o, (g->d + 31) / 32, g->d / 16};
-            bool fetched = false;
-            auto prefetch_o = [&]() {
-                if (!fetched) load_wchunk<KC>(pf, o_src, first_tile(o_src), 0, wave, lane);
-                fetched = true;
-            };
+            auto prefetch_o = NoPrefetch();
             // with the grid a multiple of the head count all tasks of a block belong to one head: they are
             // reported to the head's counter together, by the last one
             const bool one_head = grid % n_heads == 0;
@@ -1016,7 +933,6 @@ __global__ __launch_bounds__(kFastThreads) void verify_mega_kernel(MegaArgs /* r
                 q_in_lds = one_head && !BATCH;   // (the block's later tasks: same head, same rows)
                 block_sync_lds();
             }
-            prefetch_o();
             bar_arrive(bar);
         }
         {   // O (+ residual, operand and sums for the FFN norm)

@@ -358,3 +358,36 @@ def test_phases_of_one_two_and_three_items_per_block():
         for r in range(M):
             if top2_gap(ref[r]) > TOL["bf16"]:
                 assert preds[r] == od.argmax(ref[r])
+
+
+def test_two_fragment_windows_repeat_their_bits_after_other_steps():
+    """Windows of 9 to 15 rows run the one-kernel step with two operand fragments of which the second is partly
+    filled.  Their bits must not depend on what ran before: every repetition, after a 17-row step (separate
+    launches) or a 16-row step (the same kernel) on the same model, equals the one-launch-per-operation path.
+    (A step that read its LDS copy of the operand before the copy had arrived got one tile in some ten
+    thousand wrong: a few repetitions of 32 layers x 4 phases x 256 tiles find that.)"""
+    shape = synth.LLAMA_7B
+    L = 512
+    w = synth.make_weights(shape, 2, device="cuda")
+    model = B.Model(shape, w, max_window=32, max_positions=L + 64)
+    model_l = B.Model(shape, w, max_window=32, max_positions=L + 64, gemm_path=B.GEMM_MFMA_LAUNCHES)
+    kv, kv_l = B.KVCache(model, L + 64), B.KVCache(model_l, L + 64)
+    for layer in range(shape.n_layers):
+        k, v = synth.kv_fill(shape, 7, layer, L, device="cuda")
+        kf, vf = k.float().contiguous(), v.float().contiguous()
+        kv.write(layer, 0, kf, vf)
+        kv_l.write(layer, 0, kf, vf)
+    wide = synth.random_tokens(shape.vocab, 17, 21)
+
+    def run(m, k_, M):
+        k_.truncate(L)
+        buf = torch.empty(M, m.vocab, dtype=torch.float32, device="cuda")
+        B.verify(m, k_, wide[:M], B.APPEND, out_logits=buf)
+        return buf
+
+    for M in (9, 12, 15):
+        want = run(model_l, kv_l, M)
+        for it in range(24):
+            run(model, kv, 17 if it % 2 == 0 else 16)
+            got = run(model, kv, M)
+            assert torch.equal(got, want), (M, it)
