@@ -53,6 +53,30 @@ def run_stream(stream: Sequence[int], prompt_len: int, n_min: int, n_max: int, K
             "windows": windows}
 
 
+def accept_pattern(stream: Sequence[int], prompt_len: int, n_min: int, n_max: int, K: int, vocab: int, n_steps: int,
+                   adaptive: bool = False) -> List[tuple]:
+    """(drafts proposed, drafts accepted) of the first n_steps steps of Algorithm 1 over stream[prompt_len:]:
+    what the table really proposes on that stream and what a lossless verifier keeps.  ``adaptive`` cuts a
+    step's drafts to adaptive_draft_length()."""
+    table = B.NgramTable(n_min, n_max, vocab)
+    table.update(list(stream[:prompt_len]))
+    pos, out = prompt_len, []
+    while len(out) < n_steps and pos < len(stream):
+        table.update([stream[pos]])
+        drafts, levels = table.propose(K)
+        if adaptive:
+            drafts = drafts[:B.adaptive_draft_length(levels, K)]
+        a = 0
+        while a < len(drafts) and pos + 1 + a < len(stream) and drafts[a] == stream[pos + 1 + a]:
+            a += 1
+        if a:
+            table.update(list(stream[pos + 1:pos + 1 + a]))
+        out.append((len(drafts), a))
+        pos += 1 + a
+    table.close()
+    return out
+
+
 def run_stream_multi(stream: Sequence[int], prompt_len: int, n_min: int, n_max: int, K: int, n_cand: int, vocab: int,
                      max_drafts: int = 31, max_tokens: Optional[int] = None) -> Dict[str, float]:
     """run_stream with up to n_cand candidate drafts per step (anpd_ngram_propose_tree), verified together:
