@@ -49,8 +49,9 @@ enum { ANPD_VERIFY = 0, ANPD_APPEND = 1 };          /* anpd_verify modes */
 /* GEMM forms.  DOT: wavefront dot products on the caller's row-major weights (any dtype).
  * MFMA: matrix cores on bf16 weights repacked into fragment order.  MFMA_STREAM (anpd_linear
  * only) forces the MFMA form that streams the activation operand instead of holding it in
- * registers; both MFMA forms give bit-identical results.  With MFMA, windows of up to 8 rows
- * run as ONE persistent kernel per step when the model allows it (d_model <= 4096);
+ * registers; both MFMA forms give bit-identical results.  With MFMA, a window runs as ONE
+ * persistent kernel per step when the model allows it: up to 16 rows for d_model <= 4096, up to
+ * 8 rows for d_model <= 5120 (draft trees and several sequences: up to 8 rows, d_model <= 4096);
  * MFMA_LAUNCHES (model option) keeps the same arithmetic as one launch per operation. */
 enum { ANPD_GEMM_AUTO = 0, ANPD_GEMM_DOT = 1, ANPD_GEMM_MFMA = 2, ANPD_GEMM_MFMA_STREAM = 3,
        ANPD_GEMM_MFMA_LAUNCHES = 4 };
@@ -238,9 +239,10 @@ int32_t anpd_verify_tree(anpd_model_t *m, anpd_kv_t *kv, const int32_t *window, 
                          int32_t *out_predicts, float *out_logits, void *stream);
 
 /* Several sequences in one step: their windows go through every weight matrix together, so the
- * weights are streamed once for all of them (the step is bound by that stream, and a window of up to
- * 8 / 16 / 32 rows costs 1 / 1.4 / 1.8 times a one-row step).  The paper verifies one sequence at
- * a time (Algorithm 1); this is the same step for n_seq independent runs of it.
+ * weights are streamed once for all of them (the step is bound by that stream: measured at the 7B
+ * shape, up to 8 rows cost a one-row step, 9 to 16 rows 1.3 and 17 to 32 rows 1.9 times that).  The
+ * paper verifies one sequence at a time (Algorithm 1); this is the same step for n_seq independent
+ * runs of it.
  *   kvs (host array of n_seq handles): one cache per sequence, all of model m, all different.
  *   windows[s] (host, n_windows[s] ints): window of sequence s as in anpd_verify; the rows of all
  *   windows together must not exceed cfg.max_window.  mode: ANPD_VERIFY or ANPD_APPEND, for all.

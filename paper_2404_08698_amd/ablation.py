@@ -54,10 +54,10 @@ def run_stream(stream: Sequence[int], prompt_len: int, n_min: int, n_max: int, K
 
 
 def accept_pattern(stream: Sequence[int], prompt_len: int, n_min: int, n_max: int, K: int, vocab: int, n_steps: int,
-                   adaptive: bool = False) -> List[tuple]:
+                   adaptive: bool = False, k_adaptive: Optional[int] = None) -> List[tuple]:
     """(drafts proposed, drafts accepted) of the first n_steps steps of Algorithm 1 over stream[prompt_len:]:
     what the table really proposes on that stream and what a lossless verifier keeps.  ``adaptive`` cuts a
-    step's drafts to adaptive_draft_length()."""
+    step's drafts to adaptive_draft_length() with at most ``k_adaptive`` (default K) drafts."""
     table = B.NgramTable(n_min, n_max, vocab)
     table.update(list(stream[:prompt_len]))
     pos, out = prompt_len, []
@@ -65,7 +65,7 @@ def accept_pattern(stream: Sequence[int], prompt_len: int, n_min: int, n_max: in
         table.update([stream[pos]])
         drafts, levels = table.propose(K)
         if adaptive:
-            drafts = drafts[:B.adaptive_draft_length(levels, K)]
+            drafts = drafts[:B.adaptive_draft_length(levels, K if k_adaptive is None else k_adaptive)]
         a = 0
         while a < len(drafts) and pos + 1 + a < len(stream) and drafts[a] == stream[pos + 1 + a]:
             a += 1
