@@ -57,3 +57,22 @@ def test_multi_candidate_driver_counts_match_the_oracle_loop():
         if n_cand == 1:
             one = ablation.run_stream(stream, P, n_min, n_max, K, vocab, max_tokens=got["tokens"])
             assert (one["steps"], one["accepted"]) == (got["steps"], got["accepted"])
+
+
+def test_accept_pattern_follows_the_stream_and_the_adaptive_cut():
+    # (drafts, accepted) per step: what the table proposes on the stream and what a lossless verifier keeps;
+    # the adaptive form cuts a step's drafts to 2^(level - 2) of the level that answered, and to k_adaptive
+    period = [5, 9, 2, 7, 11, 3, 8]
+    stream = period * 40
+    plain = ablation.accept_pattern(stream, 28, 2, 6, 16, 16, 12)
+    assert all(d == 16 and a == 16 for d, a in plain)                # a periodic stream is drafted perfectly
+    adaptive = ablation.accept_pattern(stream, 28, 2, 6, 16, 16, 12, adaptive=True)
+    assert all(d == 16 and a == 16 for d, a in adaptive)             # level 6 answers: 2^4 drafts
+    capped = ablation.accept_pattern(stream, 28, 2, 6, 16, 16, 12, adaptive=True, k_adaptive=15)
+    assert all(d == 15 and a == 15 for d, a in capped)
+    low = ablation.accept_pattern(stream, 28, 2, 3, 16, 16, 12, adaptive=True, k_adaptive=15)
+    assert all(d == 2 and a == 2 for d, a in low)                    # level 3 answers: 2 drafts
+    vocab = 64
+    noisy = synth.markov_stream(vocab, 400, 0.5, 3, 9, 77)
+    for d, a in ablation.accept_pattern(noisy, 48, 2, 5, 7, vocab, 60):
+        assert 0 <= a <= d <= 7
