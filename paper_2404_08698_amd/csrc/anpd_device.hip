@@ -486,6 +486,7 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
     uint32_t *counter = (uint32_t *)(ws + L.counter);
     const float scale = 1.0f / sqrtf((float)dh);
     const int n_splits = batch ? batch->grid_splits : n_splits_of(kv->len + M);
+    const bool one_page = n_splits <= kSmallSplits;
     const int nks_d = (d + 31) / 32, nks_f = (F + 31) / 32;
     const int32_t *b_row_seq = (const int32_t *)(ws + L.batch);
     const SeqRef *b_seqs = (const SeqRef *)(ws + L.batch + ANPD_MAX_WINDOW * sizeof(int32_t));
@@ -542,24 +543,28 @@ int32_t run_step_fast(anpd_model *m, anpd_kv *kv, int M, int mode, hipStream_t s
             if (rc != ANPD_OK) return rc;
         }
         mark(m, ANPD_PROF_GEMM_QKV, st);
+        // (n_splits <= kSmallSplits: every split of the step has one page per wave: the leaner instantiation)
         if (batch) {
-            if (dh == 128)
-                hipLaunchKernelGGL((attn_batch_kernel<128>), dim3(H, n_splits, batch->n_seq), dim3(kFastThreads), 0, st, (const uint4 *)qp,
-                                   b_seqs, b_row_seq, batch->n_blocks, M, l, c.n_layers, H, Hkv, L.max_splits, scale, part, head_ctr,
-                                   xp_att, cls);
-            else
-                hipLaunchKernelGGL((attn_batch_kernel<64>), dim3(H, n_splits, batch->n_seq), dim3(kFastThreads), 0, st, (const uint4 *)qp,
-                                   b_seqs, b_row_seq, batch->n_blocks, M, l, c.n_layers, H, Hkv, L.max_splits, scale, part, head_ctr,
-                                   xp_att, cls);
-        } else
-#define ANPD_ATTN(DH_, TREE_)                                                                                              \
-    hipLaunchKernelGGL((attn_fast_kernel<DH_, TREE_>), dim3(H, n_splits), dim3(kFastThreads), 0, st, (const uint4 *)qp,  \
+#define ANPD_ATTN_B(DH_, MAXP_)                                                                                            \
+    hipLaunchKernelGGL((attn_batch_kernel<DH_, MAXP_>), dim3(H, n_splits, batch->n_seq), dim3(kFastThreads), 0, st,      \
+                       (const uint4 *)qp, b_seqs, b_row_seq, batch->n_blocks, M, l, c.n_layers, H, Hkv, L.max_splits, scale, part, \
+                       head_ctr, xp_att, cls)
+            if (dh == 128) { if (one_page) ANPD_ATTN_B(128, 1); else ANPD_ATTN_B(128, kFastPages); }
+            else if (one_page) ANPD_ATTN_B(64, 1);
+            else ANPD_ATTN_B(64, kFastPages);
+#undef ANPD_ATTN_B
+        } else {
+#define ANPD_ATTN(DH_, TREE_, MAXP_)                                                                                       \
+    hipLaunchKernelGGL((attn_fast_kernel<DH_, TREE_, MAXP_>), dim3(H, n_splits), dim3(kFastThreads), 0, st, (const uint4 *)qp,  \
                        (const bf16_t *)kv->pool, kv->d_table, kv->d_len, M, l, c.n_layers, H, Hkv, L.max_splits, scale, part,   \
                        head_ctr, xp_att, cls, t_mask)
-        if (dh == 128) { if (tree) ANPD_ATTN(128, true); else ANPD_ATTN(128, false); }
-        else if (tree) ANPD_ATTN(64, true);
-        else ANPD_ATTN(64, false);
+#define ANPD_ATTN_T(DH_, MAXP_) do { if (tree) ANPD_ATTN(DH_, true, MAXP_); else ANPD_ATTN(DH_, false, MAXP_); } while (0)
+            if (dh == 128) { if (one_page) ANPD_ATTN_T(128, 1); else ANPD_ATTN_T(128, kFastPages); }
+            else if (one_page) ANPD_ATTN_T(64, 1);
+            else ANPD_ATTN_T(64, kFastPages);
+#undef ANPD_ATTN_T
 #undef ANPD_ATTN
+        }
         mark(m, ANPD_PROF_ATTN, st);
         {
             FastArgs a = base;

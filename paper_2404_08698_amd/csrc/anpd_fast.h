@@ -933,7 +933,11 @@ struct AttnBatch {
 // `after_values` runs once the task's last use of its K / V registers is behind it (the persistent kernel
 // requests its next task's page there: into the same registers, while this task's partial results are
 // reduced, stored and merged).
-template <int DH, bool COH = false, typename AfterLoads = NoPrefetch, int MODE = ATTN_CHAIN, typename AfterValues = NoPrefetch>
+// MAXP: the most pages per wave that a split of this call can have (1: every key position lies below
+// split_begin(kSmallSplits), so the code for further pages - a second set of page registers among it - is left
+// out: the separate kernels then fit two blocks on a compute unit instead of one).
+template <int DH, bool COH = false, typename AfterLoads = NoPrefetch, int MODE = ATTN_CHAIN, typename AfterValues = NoPrefetch,
+          int MAXP = kFastPages>
 __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, int head, int split, int L,
                                           const uint4 *__restrict__ qp, const bf16_t *__restrict__ pool,
                                           const int32_t *__restrict__ page_table, int M, int layer, int n_layers, int n_heads,
@@ -956,7 +960,7 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
     // The wave has registers for two pages: kv (page 0, then page 2) and kvb (page 1).  What is not parked
     // in LDS is requested here; the requests go out before `after_loads`: loads come back in the order they
     // were issued, and what after_loads requests is further away.
-    const int n_pages = split_pages(split);
+    const int n_pages = MAXP == 1 ? 1 : split_pages(split);
     AttnKV<DH> kvb;
     kvb.loaded = false;
     auto request = [&](AttnKV<DH> &dst, int j) __attribute__((always_inline)) {
@@ -1208,7 +1212,7 @@ __device__ __forceinline__ void attn_task(AttnShared<DH> &sh, AttnKV<DH> &kv, in
 }
 
 // grid: (n_heads, n_splits_of(len + M)), kFastWaves waves.
-template <int DH, bool TREE = false>
+template <int DH, bool TREE = false, int MAXP = kFastPages>
 __global__ __launch_bounds__(kFastThreads) void attn_fast_kernel(const uint4 *__restrict__ qp, const bf16_t *__restrict__ pool,
                                                           const int32_t *__restrict__ page_table,
                                                           const int32_t *__restrict__ len_ptr, int M, int layer, int n_layers,
@@ -1222,7 +1226,7 @@ __global__ __launch_bounds__(kFastThreads) void attn_fast_kernel(const uint4 *__
     if (split_begin(blockIdx.y) >= L + M) return;
     AttnKV<DH> kv;
     kv.loaded = false;
-    attn_task<DH, false, NoPrefetch, TREE ? ATTN_TREE : ATTN_CHAIN>(sh, kv, blockIdx.x, blockIdx.y, L, qp, pool, page_table, M, layer,
+    attn_task<DH, false, NoPrefetch, TREE ? ATTN_TREE : ATTN_CHAIN, NoPrefetch, MAXP>(sh, kv, blockIdx.x, blockIdx.y, L, qp, pool, page_table, M, layer,
                                                                     n_layers, n_heads, n_kv_heads, max_splits, scale, part,
                                                                     head_counter, xp_att, cls, NoPrefetch(), row_mask, nullptr,
                                                                     NoPrefetch(), 1, nullptr, false, false, nullptr, false, false);
@@ -1230,7 +1234,7 @@ __global__ __launch_bounds__(kFastThreads) void attn_fast_kernel(const uint4 *__
 
 // Several sequences' windows in one step: block (head, split, sequence) works on that sequence's rows
 // against that sequence's cache.   grid: (n_heads, largest number of splits of any sequence, n_seq).
-template <int DH>
+template <int DH, int MAXP = kFastPages>
 __global__ __launch_bounds__(kFastThreads) void attn_batch_kernel(const uint4 *__restrict__ qp, const SeqRef *__restrict__ seqs,
                                                            const int32_t *__restrict__ row_seq, int n_blocks, int M, int layer,
                                                            int n_layers, int n_heads, int n_kv_heads, int max_splits,
@@ -1245,7 +1249,7 @@ __global__ __launch_bounds__(kFastThreads) void attn_batch_kernel(const uint4 *_
     AttnKV<DH> kv;
     kv.loaded = false;
     AttnBatch bt = {sq.row0, sq.n_rows, n_blocks, seqs, row_seq};
-    attn_task<DH, false, NoPrefetch, ATTN_BATCH>(sh, kv, blockIdx.x, blockIdx.y, L, qp, sq.pool, sq.page_table, M, layer, n_layers,
+    attn_task<DH, false, NoPrefetch, ATTN_BATCH, NoPrefetch, MAXP>(sh, kv, blockIdx.x, blockIdx.y, L, qp, sq.pool, sq.page_table, M, layer, n_layers,
                                                  n_heads, n_kv_heads, max_splits, scale, part, head_counter, xp_att, cls,
                                                  NoPrefetch(), nullptr, &bt, NoPrefetch(), 1, nullptr, false, false, nullptr, false, false);
 }
