@@ -255,6 +255,9 @@ int32_t launch_fast(FastArgs &a, int n_cu, bool force_stream, hipStream_t st)
         // activation fragment is loaded once for several weight tiles
         const int nt = a.cls / 8;
         int blocks = a.n_tiles / 2 < n_cu ? a.n_tiles / 2 : n_cu;
+        // (two fragments, between one and two tiles per compute unit: every compute unit gets a block of one or
+        // two tiles rather than half of them a block of two: 13B shape, 9 rows: -0.8 % per step)
+        if (nt == 2 && a.n_tiles < 2 * n_cu) blocks = a.n_tiles < n_cu ? a.n_tiles : n_cu;
         if (blocks < 1) blocks = 1;
         dim3 grid((unsigned)blocks), block(kFastWaves * 64);
         const int per_block = (a.n_tiles + blocks - 1) / blocks;
